@@ -1,0 +1,223 @@
+"""Oracle: TASP schedules as plain integer lists (test infrastructure).
+
+What is written here
+--------------------
+* ``hamilton_rings(n)``      -- the K_n-decomposition of Sec. 3.1.2, Algorithm 1: the complete
+                               directed graph on n ranks split into n-1 directed Hamiltonian cycles
+                               ("orthogonal ring datapaths", Sec. 3.1.1, eq. (2)).
+* ``routing_table``          -- Algorithm 2 (in / out mapping).
+* ``simulate_allgather``     -- the Multi-Ring AllGather of Sec. 3.2.2 / Fig. 4 played hop by hop.
+* ``arrival_table``          -- the same thing in closed form for one rank.
+* ``subchunk_ranges``        -- the chunk placements of Sec. 3.2.3: eq. (3) (contiguous), eq. (4)
+                               (zig-zag halves) and eq. (5), (6) (zig-zag TASP sub-chunks).
+* validators                 -- brute-force checks of the definitions (Hamiltonian, arc-disjoint,
+                               accessibility, zero-copy), independent of how the rings were built.
+
+Readings taken where the paper leaves a gap (each is pinned by tests/test_oracle_schedule.py):
+  R1  Algorithm 1 names GetPath and GenCycles without bodies.  GetPath(m) is read as the m cyclic
+      translates of the zig-zag sequence 0,1,m-1,2,m-2,... on Z_m (the row-complete Latin square the
+      multi-node paragraph of Sec. 3.1.3 refers to); GenCycles puts the one new vertex in front of a path.
+  R2  Data moves list-forward along a ring; out_mapping is Algorithm 2 with d=+1, in_mapping d=-1.
+  R3  Sub-chunk index i travels on ring i (t[i,j] of Fig. 4).
+  R4  Step 0 is the local sub-chunks; the sub-chunk seen at step s started s hops upstream.
+  R5  Sub-chunk bounds use floors: piece i of a length-len block is [i*len//m, (i+1)*len//m).
+  R6  Eq. (5), (6) are read with the index (n-1)*j+i (piece i of half-chunk j) and its mirror
+      image; the printed index 2nj+i does not tile the sequence.
+  R7  n=4 admits no decomposition (Algorithm 1 requires n>=8); three Hamiltonian rings with the
+      least possible arc overlap are used instead, the lexicographically smallest such triple.
+"""
+from itertools import combinations, permutations
+
+FULL = 0           # bi-directional attention, contiguous placement, eq. (3)
+ZIGZAG_CAUSAL = 1  # causal attention, zig-zag placement, eq. (4)-(6)
+
+
+# ----------------------------------------------------------------------------------------------
+# Sec. 3.1.2, Algorithm 1
+# ----------------------------------------------------------------------------------------------
+def zigzag_sequence(m):
+    """0, 1, m-1, 2, m-2, ..., m/2: consecutive differences are all distinct mod m (m even)."""
+    z = [0]
+    for t in range(1, m):
+        z.append((t + 1) // 2 if t % 2 == 1 else m - t // 2)
+    return z
+
+
+def get_path(m):
+    """GetPath(m) of Algorithm 1 (reading R1): m Hamiltonian paths on Z_m."""
+    z = zigzag_sequence(m)
+    return [[(i + zt) % m for zt in z] for i in range(m)]
+
+
+def gen_cycles(paths, new_vertex):
+    """GenCycles of Algorithm 1 (reading R1): close every path through one extra vertex."""
+    return [[new_vertex] + list(p) for p in paths]
+
+
+def hamilton_rings(n):
+    """K_n-decomposition: n-1 rings, each a list of the n ranks; ring[j] sends to ring[(j+1)%n]."""
+    if n == 4:
+        return _least_overlap_rings_k4()
+    if n < 8 or n % 4 != 0:
+        raise ValueError("Algorithm 1 is defined for n >= 8 with n % 4 == 0 (and the n = 4 stand-in)")
+    init_paths = get_path(n - 2)
+    init_cycles = gen_cycles(init_paths, n - 2)          # cycles on the n-1 vertices 0..n-2
+    k = n // 4 - 1
+    shifts = {0: 1, k + 1: 4 * k + 2, 2 * k + 2: 3, 3 * k + 2: 4 * k}
+    rotated = []
+    appender = {}
+    for i in range(n - 2):
+        shift = shifts.get(i, 2 * k)
+        row = [init_cycles[i][(j + shift) % (n - 1)] for j in range(n - 1)]
+        rotated.append(row)
+        # the arc that closes the rotated list is the one taken out of cycle i
+        appender[row[-1]] = row[0]
+    appender_list = [n - 2]
+    for _ in range(n - 2):
+        appender_list.append(appender[appender_list[-1]])
+    # the removed arcs form one more Hamiltonian path; every path is closed through vertex n-1
+    return [row + [n - 1] for row in rotated] + [appender_list + [n - 1]]
+
+
+def _least_overlap_rings_k4():
+    """Reading R7: K_4 has 6 directed Hamiltonian cycles and no 3 of them are arc-disjoint."""
+    cycles = [[0] + list(p) for p in permutations([1, 2, 3])]
+    best = None
+    for triple in combinations(cycles, 3):
+        load = {}
+        for ring in triple:
+            for j in range(4):
+                a = (ring[j], ring[(j + 1) % 4])
+                load[a] = load.get(a, 0) + 1
+        key = (max(load.values()), sum(c - 1 for c in load.values()), [list(r) for r in triple])
+        if best is None or key < best:
+            best = key
+    return best[2]
+
+
+# ----------------------------------------------------------------------------------------------
+# Algorithm 2
+# ----------------------------------------------------------------------------------------------
+def routing_table(looping, d):
+    """mapping[u][v] = i when v follows (d=+1) or precedes (d=-1) u on ring i; -1 elsewhere.
+
+    When an arc lies on two rings (possible only for the n=4 stand-in, reading R7) the lower ring id
+    is kept, which is why the rings are written from the highest id down.
+    """
+    n = len(looping[0])
+    mapping = [[-1] * n for _ in range(n)]
+    for i in reversed(range(len(looping))):
+        for j in range(n):
+            u = looping[i][j]
+            v = looping[i][(j + d) % n]
+            mapping[u][v] = i
+    return mapping
+
+
+def out_mapping(looping):
+    return routing_table(looping, +1)
+
+
+def in_mapping(looping):
+    return routing_table(looping, -1)
+
+
+# ----------------------------------------------------------------------------------------------
+# Sec. 3.2.2 / Fig. 4: Multi-Ring AllGather
+# ----------------------------------------------------------------------------------------------
+def simulate_allgather(looping):
+    """Play the primitive: held[s][rank][i] = source rank of the sub-chunk that `rank` holds on
+    ring i at step s.  Also checks, at every hop, that no buffer slot receives two sub-chunks."""
+    n = len(looping[0])
+    m = len(looping)
+    cur = [[rank for _ in range(m)] for rank in range(n)]     # t[i, j] starts at rank j
+    held = [cur]
+    for _ in range(n - 1):
+        nxt = [[None] * m for _ in range(n)]
+        for i, ring in enumerate(looping):
+            for j in range(n):
+                u, v = ring[j], ring[(j + 1) % n]
+                assert nxt[v][i] is None, "two sub-chunks landed in one buffer slot"
+                nxt[v][i] = cur[u][i]
+        cur = nxt
+        held.append(cur)
+    return held
+
+
+def arrival_table(looping, rank):
+    """arrival[s][i] = source rank of the sub-chunk seen on ring i at step s (readings R3, R4)."""
+    n = len(looping[0])
+    table = []
+    for s in range(n):
+        row = []
+        for ring in looping:
+            pos = ring.index(rank)
+            row.append(ring[(pos - s) % n])
+        table.append(row)
+    return table
+
+
+# ----------------------------------------------------------------------------------------------
+# Sec. 3.2.3: chunk placement
+# ----------------------------------------------------------------------------------------------
+def piece(i, length, m):
+    """Reading R5."""
+    return (i * length) // m, ((i + 1) * length) // m
+
+
+def subchunk_ranges(n, S, mask_mode, ring, src):
+    """Global token ranges [start, end) of sub-chunk t[ring, src]; one range for FULL (eq. (3) cut
+    in n-1 pieces), two for ZIGZAG_CAUSAL (eq. (5) and its mirror image eq. (6))."""
+    m = n - 1
+    if mask_mode == FULL:
+        if S % n:
+            raise ValueError("S must be a multiple of n")
+        L = S // n
+        a, b = piece(ring, L, m)
+        return [(src * L + a, src * L + b)]
+    if S % (2 * n):
+        raise ValueError("S must be a multiple of 2n")
+    H = S // (2 * n)
+    a, b = piece(ring, H, m)
+    return [(src * H + a, src * H + b), (S - src * H - b, S - src * H - a)]
+
+
+def local_positions(n, rank, S, mask_mode):
+    """Global position of every local query row (eq. (3) or eq. (4))."""
+    if mask_mode == FULL:
+        L = S // n
+        return list(range(rank * L, (rank + 1) * L))
+    H = S // (2 * n)
+    return list(range(rank * H, (rank + 1) * H)) + list(range(S - (rank + 1) * H, S - rank * H))
+
+
+# ----------------------------------------------------------------------------------------------
+# Brute-force validators (they know nothing about how the rings were made)
+# ----------------------------------------------------------------------------------------------
+def is_hamiltonian_cycle(ring, n):
+    return len(ring) == n and sorted(ring) == list(range(n))
+
+
+def arc_loads(looping):
+    n = len(looping[0])
+    load = {}
+    for ring in looping:
+        for j in range(n):
+            a = (ring[j], ring[(j + 1) % n])
+            load[a] = load.get(a, 0) + 1
+    return load
+
+
+def is_decomposition(looping):
+    """n-1 Hamiltonian cycles that use each of the n(n-1) arcs of K_n exactly once."""
+    n = len(looping[0])
+    if len(looping) != n - 1 or not all(is_hamiltonian_cycle(r, n) for r in looping):
+        return False
+    load = arc_loads(looping)
+    return len(load) == n * (n - 1) and max(load.values()) == 1 and all(u != v for u, v in load)
+
+
+def count_disjoint_triples_k4():
+    """How many triples of directed Hamiltonian cycles of K_4 are arc-disjoint (the answer is 0)."""
+    cycles = [[0] + list(p) for p in permutations([1, 2, 3])]
+    return sum(1 for t in combinations(cycles, 3) if max(arc_loads(list(t)).values()) == 1)
