@@ -1,0 +1,166 @@
+/*
+ * tasp.h -- C ABI of the single-GPU hot path of TASP (topology-aware sequence parallelism,
+ * arXiv 2509.26541) for AMD MI355X (gfx950).
+ *
+ * One process drives one GPU and plays one "virtual rank" r of an N-rank sequence-parallel group:
+ * the GPU holds the whole K and V of the sequence and rank r's local queries, and performs rank r's
+ * share of the forward pass of Algorithm 3 -- N steps; at step s the rank attends to the N-1 KV
+ * sub-chunks that the Multi-Ring AllGather (Sec. 3.2.2) would have delivered to it at that step,
+ * concatenated in ring order, and folds the partial (output, lse) into a running pair.  The
+ * transport itself (AlltoAll between GPUs) is not part of this library.
+ *
+ * Conventions
+ *   - Every function returns TASP_OK (0) or a negative tasp_status.  Nothing throws, aborts or prints.
+ *   - "host" / "device" is stated for every pointer.  The library never allocates device memory and
+ *     keeps no global state; device work is enqueued on the caller's HIP stream and is asynchronous.
+ *   - Tensors are dense, row-major, with the last index fastest.
+ *   - Token positions are global positions in [0, S).
+ */
+#ifndef TASP_H
+#define TASP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tasp_status {
+  TASP_OK = 0,
+  TASP_EINVAL = -1,            /* null pointer, N < 2, rank outside [0,N), S not divisible, Hq % Hkv != 0 ... */
+  TASP_EUNSUPPORTED_N = -2,    /* N for which no ring decomposition is implemented (see tasp_schedule_create) */
+  TASP_EUNSUPPORTED_SHAPE = -3,/* head dim / dtype / size outside what the kernels cover */
+  TASP_EALIGN = -4,            /* a device pointer is not 16-byte aligned */
+  TASP_EWORKSPACE = -5,        /* workspace missing or smaller than tasp_chunk_attn_workspace_bytes() */
+  TASP_EHIP = -6,              /* a HIP call or kernel launch failed */
+  TASP_ENOMEM = -7             /* host allocation failed */
+} tasp_status;
+
+enum { TASP_MASK_FULL = 0, TASP_MASK_ZIGZAG_CAUSAL = 1 };
+enum { TASP_DTYPE_FP32 = 0, TASP_DTYPE_BF16 = 1 };
+enum { TASP_ORDER_TASP = 0, TASP_ORDER_RING = 1 };
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char* tasp_strerror(int status);
+
+/* ------------------------------------------------------------------------------------------------
+ * tasp_schedule(N, rank): ring decomposition, routing tables and arrival order.      [host only]
+ *
+ * Sec. 3.1.2, Algorithm 1: the complete directed graph K_N is decomposed into N-1 arc-disjoint
+ * directed Hamiltonian cycles ("orthogonal ring datapaths", Sec. 3.1.1 eq. (2)).  Algorithm 1 is
+ * defined for N >= 8 with N % 4 == 0.  N == 4 has no such decomposition; three Hamiltonian rings
+ * with the least possible overlap are used ([0,1,2,3] [0,1,3,2] [0,2,3,1]) and
+ * tasp_schedule_max_arc_load() reports 2 instead of 1.  Any other N gives TASP_EUNSUPPORTED_N.
+ *
+ * The object is immutable, lives in host memory and is owned by the library until
+ * tasp_schedule_destroy().  All array accessors return host pointers into it.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct tasp_schedule tasp_schedule_t;
+
+int  tasp_schedule_create(int32_t n_ranks, int32_t rank, tasp_schedule_t** out);
+void tasp_schedule_destroy(tasp_schedule_t* s);
+
+int32_t tasp_schedule_n_ranks(const tasp_schedule_t* s);
+int32_t tasp_schedule_rank(const tasp_schedule_t* s);
+int32_t tasp_schedule_n_rings(const tasp_schedule_t* s);          /* N-1 */
+int32_t tasp_schedule_max_arc_load(const tasp_schedule_t* s);     /* 1: true decomposition, 2: N == 4 */
+
+/* rings[i*N + j], i < N-1, j < N: rank at position j of ring i; data moves from position j to
+ * position (j+1) % N (Algorithm 1's h_cycles, Algorithm 2's looping matrix). */
+const int32_t* tasp_schedule_rings(const tasp_schedule_t* s);
+/* Algorithm 2.  out_mapping[u*N + v] = ring on which u sends to v; in_mapping[u*N + v] = ring on
+ * which u receives from v; -1 on the diagonal and on arcs no ring uses.  For an arc on two rings
+ * (N == 4 only) the lower ring id is stored. */
+const int32_t* tasp_schedule_out_mapping(const tasp_schedule_t* s);
+const int32_t* tasp_schedule_in_mapping(const tasp_schedule_t* s);
+/* Sec. 3.2.2, Fig. 4.  arrival[s*(N-1) + i] = rank at which the sub-chunk t[i, .] that this rank
+ * holds on ring i at step s started; row 0 is the rank itself. */
+const int32_t* tasp_schedule_arrival(const tasp_schedule_t* s);
+
+/* Sec. 3.2.3.  Global token ranges [start, end) of sub-chunk t[ring, src_rank]:
+ *   TASP_MASK_FULL           one range: piece `ring` of the contiguous chunk of eq. (3);
+ *   TASP_MASK_ZIGZAG_CAUSAL  two ranges: piece `ring` of half-chunk src_rank (eq. (5)) and its
+ *                            mirror image in half-chunk 2N-1-src_rank (eq. (6)).
+ * Piece i of a block of `len` tokens is [i*len/(N-1), (i+1)*len/(N-1)) with integer division.
+ * ranges (host, 4 entries) receives start0,end0[,start1,end1]; *n_ranges receives 1 or 2.
+ * S must be a positive multiple of N (FULL) or 2N (ZIGZAG_CAUSAL). */
+int tasp_subchunk_ranges(const tasp_schedule_t* s, int64_t S, int32_t mask_mode, int32_t ring,
+                         int32_t src_rank, int64_t ranges[4], int32_t* n_ranges);
+
+/* The KV segments one block of local query rows attends to at one step, in concatenation order
+ * (ring order, Algorithm 3), after dropping what the causal mask hides completely (the load-balance
+ * argument of Sec. 3.2.3) and after joining neighbours that are contiguous in the sequence.
+ *   q_block  0: all local rows (FULL), or the first half-chunk's rows (ZIGZAG_CAUSAL);
+ *            1: the second half-chunk's rows (ZIGZAG_CAUSAL only).
+ *   order    TASP_ORDER_TASP: the multi-ring arrival order; TASP_ORDER_RING: plain Ring /
+ *            Zig-zag Ring Attention, one whole chunk per step from rank (r - step) mod N.
+ * seg (host, 2*cap entries) receives start,end pairs; diag (host, cap entries) is 1 where the
+ * segment straddles the causal diagonal of the block (needs an element-wise mask), else 0.
+ * *n_seg receives the count; TASP_EINVAL if cap is too small. */
+int tasp_step_segments(const tasp_schedule_t* s, int64_t S, int32_t mask_mode, int32_t order,
+                       int32_t step, int32_t q_block, int64_t* seg, int32_t* diag, int32_t cap,
+                       int32_t* n_seg);
+
+/* ------------------------------------------------------------------------------------------------
+ * tasp_chunk_attn: the forward pass of Algorithm 3 for one rank.                  [device work]
+ *
+ *   q, out   device, [L, Hq, d]   rank-local rows, L = S/N.  ZIGZAG_CAUSAL: local row l < H = S/(2N)
+ *                                  is global position r*H + l, row l >= H is S - (r+1)*H + (l-H)
+ *                                  (eq. (4)).  FULL: local row l is global r*L + l (eq. (3)).
+ *   k, v     device, [S, Hkv, d]  the whole sequence in natural token order; a sub-chunk is a row
+ *                                  range of these (the stand-in for the receive buffers of Alg. 3).
+ *   lse      device, [L, Hq] fp32 natural-log sum-exp of the scaled scores.
+ *   dtype    element type of q, k, v, out (fp32, or bf16 with fp32 accumulation).
+ *   Query head h reads KV head h*Hkv/Hq.  Causal: key t is visible to query p iff t <= p.
+ *   softmax_scale 0 means 1/sqrt(d).
+ *   fuse_merge 0: every step writes a partial (out_s, lse_s) and tasp_lse_merge's kernel folds it in
+ *                 (update_out_lse of Algorithm 3);  1: the attention kernel folds it in itself.
+ *   workspace device, >= tasp_chunk_attn_workspace_bytes() bytes, 256-byte aligned, caller-owned,
+ *             contents undefined on entry and exit.
+ * Supported: d in {64, 128}; S < 2^31; for bf16, N <= 32.  All device pointers 16-byte aligned.
+ * The call only enqueues work on `hip_stream` (a hipStream_t, NULL = default stream); results are
+ * valid once the stream has been synchronised.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct tasp_attn_args {
+  const void* q;
+  const void* k;
+  const void* v;
+  void*       out;
+  float*      lse;
+  void*       workspace;
+  size_t      workspace_bytes;
+  int64_t     S;
+  int32_t     Hq, Hkv, d;
+  int32_t     dtype;
+  int32_t     mask_mode;
+  int32_t     order;          /* TASP_ORDER_TASP or TASP_ORDER_RING */
+  int32_t     fuse_merge;
+  float       softmax_scale;
+} tasp_attn_args;
+
+size_t tasp_chunk_attn_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_args* a);
+int    tasp_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream);
+
+/* One step of the same pass: the partial (out_s, lse_s) of step `step` alone, before any merge.
+ * o_part device [L, Hq, d] fp32, lse_part device [L, Hq] fp32.  Rows that see no key at this step
+ * get out = 0, lse = -inf.  a->out, a->lse, a->workspace are not used. */
+int tasp_step_attn(const tasp_schedule_t* s, const tasp_attn_args* a, int32_t step,
+                   float* o_part, float* lse_part, void* hip_stream);
+
+/* update_out_lse of Algorithm 3, in place on the running pair:
+ *   lse' = log(exp(lse_acc) + exp(lse_part))
+ *   o'   = exp(lse_acc - lse') * o_acc + exp(lse_part - lse') * o_part
+ * o_* device [rows, heads, d] fp32 (16-byte aligned), lse_* device [rows, heads] fp32; d a power of
+ * two in [4, 256] (anything else: TASP_EUNSUPPORTED_SHAPE).  A side with
+ * lse = -inf contributes nothing; if both are -inf the result is o = 0, lse = -inf. */
+int tasp_lse_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
+                   int64_t rows, int32_t heads, int32_t d, void* hip_stream);
+
+/* Algorithmic work of one tasp_chunk_attn call: 4*d*Hq*(visible (query,key) pairs). */
+double tasp_chunk_attn_flops(const tasp_schedule_t* s, const tasp_attn_args* a);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TASP_H */

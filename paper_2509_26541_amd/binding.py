@@ -1,0 +1,215 @@
+"""ctypes binding of libtasp.so: same names as include/tasp.h, argument marshalling only.
+
+PyTorch supplies device memory and the HIP stream; every step of the path runs inside the library.
+There is no fallback: if the library has not been built (python paper_2509_26541_amd/build.py, or
+__graft_entry__.build()) importing this module raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtasp.so")
+
+MASK_FULL, MASK_ZIGZAG_CAUSAL = 0, 1
+DTYPE_FP32, DTYPE_BF16 = 0, 1
+ORDER_TASP, ORDER_RING = 0, 1
+
+OK, EINVAL, EUNSUPPORTED_N, EUNSUPPORTED_SHAPE, EALIGN, EWORKSPACE, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
+
+# every symbol include/tasp.h declares
+EXPORTS = [
+    "tasp_strerror", "tasp_schedule_create", "tasp_schedule_destroy", "tasp_schedule_n_ranks",
+    "tasp_schedule_rank", "tasp_schedule_n_rings", "tasp_schedule_max_arc_load", "tasp_schedule_rings",
+    "tasp_schedule_out_mapping", "tasp_schedule_in_mapping", "tasp_schedule_arrival", "tasp_subchunk_ranges",
+    "tasp_step_segments", "tasp_chunk_attn_workspace_bytes", "tasp_chunk_attn", "tasp_step_attn",
+    "tasp_lse_merge", "tasp_chunk_attn_flops",
+]
+
+
+class TaspError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, strerror(status), status))
+
+
+class AttnArgs(C.Structure):
+    _fields_ = [
+        ("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p), ("out", C.c_void_p), ("lse", C.c_void_p),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("S", C.c_int64),
+        ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32), ("dtype", C.c_int32),
+        ("mask_mode", C.c_int32), ("order", C.c_int32), ("fuse_merge", C.c_int32), ("softmax_scale", C.c_float),
+    ]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libtasp.so is not built: run `python paper_2509_26541_amd/build.py` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    p32 = C.POINTER(C.c_int32)
+    lib.tasp_strerror.restype = C.c_char_p
+    lib.tasp_strerror.argtypes = [C.c_int]
+    lib.tasp_schedule_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+    lib.tasp_schedule_destroy.argtypes = [C.c_void_p]
+    lib.tasp_schedule_destroy.restype = None
+    for name in ("n_ranks", "rank", "n_rings", "max_arc_load"):
+        f = getattr(lib, "tasp_schedule_" + name)
+        f.argtypes = [C.c_void_p]
+        f.restype = C.c_int32
+    for name in ("rings", "out_mapping", "in_mapping", "arrival"):
+        f = getattr(lib, "tasp_schedule_" + name)
+        f.argtypes = [C.c_void_p]
+        f.restype = p32
+    lib.tasp_subchunk_ranges.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                         C.POINTER(C.c_int64), p32]
+    lib.tasp_step_segments.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                       C.POINTER(C.c_int64), p32, C.c_int32, p32]
+    lib.tasp_chunk_attn_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(AttnArgs)]
+    lib.tasp_chunk_attn_workspace_bytes.restype = C.c_size_t
+    lib.tasp_chunk_attn.argtypes = [C.c_void_p, C.POINTER(AttnArgs), C.c_void_p]
+    lib.tasp_step_attn.argtypes = [C.c_void_p, C.POINTER(AttnArgs), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.tasp_lse_merge.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                   C.c_int32, C.c_void_p]
+    lib.tasp_chunk_attn_flops.argtypes = [C.c_void_p, C.POINTER(AttnArgs)]
+    lib.tasp_chunk_attn_flops.restype = C.c_double
+    return lib
+
+
+lib = _load()
+
+
+def strerror(status):
+    return lib.tasp_strerror(int(status)).decode()
+
+
+def _check(status, where):
+    if status != OK:
+        raise TaspError(status, where)
+
+
+class Schedule:
+    """tasp_schedule(N, rank): owns a tasp_schedule_t; arrays are copied out as numpy int32."""
+
+    def __init__(self, n_ranks, rank):
+        self._h = C.c_void_p()
+        _check(lib.tasp_schedule_create(n_ranks, rank, C.byref(self._h)), "tasp_schedule_create")
+        n = lib.tasp_schedule_n_ranks(self._h)
+        m = lib.tasp_schedule_n_rings(self._h)
+        self.n_ranks, self.rank, self.n_rings = n, lib.tasp_schedule_rank(self._h), m
+        self.max_arc_load = lib.tasp_schedule_max_arc_load(self._h)
+        self.rings = np.ctypeslib.as_array(lib.tasp_schedule_rings(self._h), (m, n)).copy()
+        self.out_mapping = np.ctypeslib.as_array(lib.tasp_schedule_out_mapping(self._h), (n, n)).copy()
+        self.in_mapping = np.ctypeslib.as_array(lib.tasp_schedule_in_mapping(self._h), (n, n)).copy()
+        self.arrival = np.ctypeslib.as_array(lib.tasp_schedule_arrival(self._h), (n, m)).copy()
+
+    @property
+    def handle(self):
+        return self._h
+
+    def subchunk_ranges(self, S, mask_mode, ring, src_rank):
+        r = (C.c_int64 * 4)()
+        cnt = C.c_int32()
+        _check(lib.tasp_subchunk_ranges(self._h, S, mask_mode, ring, src_rank, r, C.byref(cnt)),
+               "tasp_subchunk_ranges")
+        return [(r[2 * i], r[2 * i + 1]) for i in range(cnt.value)]
+
+    def step_segments(self, S, mask_mode, step, q_block, order=ORDER_TASP, cap=256):
+        seg = (C.c_int64 * (2 * cap))()
+        diag = (C.c_int32 * cap)()
+        cnt = C.c_int32()
+        _check(lib.tasp_step_segments(self._h, S, mask_mode, order, step, q_block, seg, diag, cap, C.byref(cnt)),
+               "tasp_step_segments")
+        return [(seg[2 * i], seg[2 * i + 1], diag[i]) for i in range(cnt.value)]
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h:
+            lib.tasp_schedule_destroy(h)
+
+
+def tasp_schedule(n_ranks, rank):
+    return Schedule(n_ranks, rank)
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _args(q, k, v, mask_mode, order, fuse_merge, softmax_scale):
+    torch = _torch()
+    if not (q.is_cuda and k.is_cuda and v.is_cuda):
+        raise ValueError("q, k, v must be device tensors")
+    if not (q.is_contiguous() and k.is_contiguous() and v.is_contiguous()):
+        raise ValueError("q, k, v must be contiguous")
+    if q.dtype != k.dtype or q.dtype != v.dtype or q.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("q, k, v must share dtype float32 or bfloat16")
+    if q.dim() != 3 or k.dim() != 3 or v.shape != k.shape or q.shape[2] != k.shape[2]:
+        raise ValueError("expected q [L, Hq, d] and k, v [S, Hkv, d]")
+    a = AttnArgs()
+    a.q, a.k, a.v = q.data_ptr(), k.data_ptr(), v.data_ptr()
+    a.S, a.Hq, a.Hkv, a.d = k.shape[0], q.shape[1], k.shape[1], q.shape[2]
+    a.dtype = DTYPE_FP32 if q.dtype == torch.float32 else DTYPE_BF16
+    a.mask_mode, a.order, a.fuse_merge, a.softmax_scale = mask_mode, order, int(bool(fuse_merge)), softmax_scale
+    return a
+
+
+class ChunkAttnPlan:
+    """Buffers of one tasp_chunk_attn shape (out, lse, workspace), so that repeated calls allocate nothing."""
+
+    def __init__(self, schedule, q, k, v, mask_mode, order=ORDER_TASP, fuse_merge=False, softmax_scale=0.0):
+        torch = _torch()
+        self.schedule = schedule
+        self.args = _args(q, k, v, mask_mode, order, fuse_merge, softmax_scale)
+        if q.shape[0] * schedule.n_ranks != k.shape[0]:
+            raise ValueError("q must hold S / N local rows")
+        self.out = torch.empty_like(q)
+        self.lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+        nbytes = lib.tasp_chunk_attn_workspace_bytes(schedule.handle, C.byref(self.args))
+        self.workspace = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=q.device)
+        self.args.out, self.args.lse = self.out.data_ptr(), self.lse.data_ptr()
+        self.args.workspace, self.args.workspace_bytes = self.workspace.data_ptr(), nbytes
+        self._keep = (q, k, v)
+
+    def run(self, stream=None):
+        torch = _torch()
+        s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        _check(lib.tasp_chunk_attn(self.schedule.handle, C.byref(self.args), C.c_void_p(s)), "tasp_chunk_attn")
+        return self.out, self.lse
+
+    def flops(self):
+        return lib.tasp_chunk_attn_flops(self.schedule.handle, C.byref(self.args))
+
+
+def tasp_chunk_attn(q, k, v, schedule, mask_mode, order=ORDER_TASP, fuse_merge=False, softmax_scale=0.0):
+    """One rank's forward pass (Algorithm 3).  Returns (out [L, Hq, d] in q's dtype, lse [L, Hq] fp32)."""
+    return ChunkAttnPlan(schedule, q, k, v, mask_mode, order, fuse_merge, softmax_scale).run()
+
+
+def tasp_step_attn(q, k, v, schedule, mask_mode, step, order=ORDER_TASP, softmax_scale=0.0):
+    """Partial (out_s fp32, lse_s fp32) of one step, before any merge."""
+    torch = _torch()
+    a = _args(q, k, v, mask_mode, order, False, softmax_scale)
+    o = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+    s = torch.cuda.current_stream().cuda_stream
+    _check(lib.tasp_step_attn(schedule.handle, C.byref(a), step, o.data_ptr(), lse.data_ptr(), C.c_void_p(s)),
+           "tasp_step_attn")
+    return o, lse
+
+
+def tasp_lse_merge(o_acc, lse_acc, o_part, lse_part):
+    """update_out_lse in place on (o_acc, lse_acc); all fp32 device tensors [rows, heads, d] / [rows, heads]."""
+    torch = _torch()
+    for t in (o_acc, lse_acc, o_part, lse_part):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32):
+            raise ValueError("fp32 contiguous device tensors expected")
+    rows, heads, d = o_acc.shape
+    if o_part.shape != o_acc.shape or lse_acc.shape != (rows, heads) or lse_part.shape != (rows, heads):
+        raise ValueError("shape mismatch")
+    s = torch.cuda.current_stream().cuda_stream
+    _check(lib.tasp_lse_merge(o_acc.data_ptr(), lse_acc.data_ptr(), o_part.data_ptr(), lse_part.data_ptr(),
+                              rows, heads, d, C.c_void_p(s)), "tasp_lse_merge")
+    return o_acc, lse_acc

@@ -1,0 +1,199 @@
+// Host orchestration of one rank's forward pass (Algorithm 3): N steps, each one attention launch
+// over the sub-chunks the schedule delivers at that step, followed by update_out_lse.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <vector>
+
+#include "internal.hpp"
+#include "schedule.hpp"
+#include "tasp.h"
+
+namespace {
+
+using tasp::AttnLaunch;
+using tasp::AttnTask;
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Shape {
+  int64_t L;            // local rows
+  size_t o_bytes;       // fp32 [L, Hq, d]
+  size_t lse_bytes;     // fp32 [L, Hq]
+};
+
+int validate(const tasp_schedule_t* s, const tasp_attn_args* a, Shape* sh) {
+  if (s == nullptr || a == nullptr) return TASP_EINVAL;
+  if (a->q == nullptr || a->k == nullptr || a->v == nullptr) return TASP_EINVAL;
+  int st = tasp::check_sequence(*s, a->S, a->mask_mode);
+  if (st != TASP_OK) return st;
+  if (a->Hq <= 0 || a->Hkv <= 0 || a->Hq % a->Hkv != 0) return TASP_EINVAL;
+  if (a->order != TASP_ORDER_TASP && a->order != TASP_ORDER_RING) return TASP_EINVAL;
+  if (!(a->softmax_scale >= 0.f) || !std::isfinite(a->softmax_scale)) return TASP_EINVAL;
+  if (a->dtype != TASP_DTYPE_FP32 && a->dtype != TASP_DTYPE_BF16) return TASP_EUNSUPPORTED_SHAPE;
+  if (a->d != 64 && a->d != 128) return TASP_EUNSUPPORTED_SHAPE;
+  if (a->S >= (int64_t{1} << 31) - 4096) return TASP_EUNSUPPORTED_SHAPE;
+  if (2 * (s->n - 1) > tasp::kMaxSeg) return TASP_EUNSUPPORTED_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(a->q) | reinterpret_cast<uintptr_t>(a->k) | reinterpret_cast<uintptr_t>(a->v)) & 15)
+    return TASP_EALIGN;
+  sh->L = a->S / s->n;
+  sh->o_bytes = static_cast<size_t>(sh->L) * a->Hq * a->d * sizeof(float);
+  sh->lse_bytes = static_cast<size_t>(sh->L) * a->Hq * sizeof(float);
+  return TASP_OK;
+}
+
+// Builds the launch descriptor of one step; `empty` receives the query blocks that see no key.
+int build_step(const tasp_schedule_t* s, const tasp_attn_args* a, int step, AttnLaunch* lp,
+               std::vector<tasp::QueryBlock>* empty) {
+  lp->q = a->q; lp->k = a->k; lp->v = a->v;
+  lp->Hq = a->Hq; lp->Hkv = a->Hkv;
+  lp->causal = a->mask_mode == TASP_MASK_ZIGZAG_CAUSAL ? 1 : 0;
+  lp->scale = a->softmax_scale > 0.f ? a->softmax_scale : 1.0f / std::sqrt(static_cast<float>(a->d));
+  lp->n_tasks = 0;
+  int64_t keys[tasp::kMaxTasks] = {0, 0};
+  std::vector<tasp::Segment> segs;
+  for (int qb = 0; qb < tasp::n_query_blocks(a->mask_mode); ++qb) {
+    tasp::QueryBlock blk;
+    int st = tasp::query_block(*s, a->S, a->mask_mode, qb, &blk);
+    if (st != TASP_OK) return st;
+    st = tasp::step_segments(*s, a->S, a->mask_mode, a->order, step, qb, &segs);
+    if (st != TASP_OK) return st;
+    if (segs.empty()) { empty->push_back(blk); continue; }
+    if (segs.size() > static_cast<size_t>(tasp::kMaxSeg)) return TASP_EUNSUPPORTED_SHAPE;
+    AttnTask& t = lp->task[lp->n_tasks];
+    t.q_row0 = static_cast<int32_t>(blk.local_row0);
+    t.n_q = static_cast<int32_t>(blk.rows);
+    t.q_pos0 = static_cast<int32_t>(blk.pos0);
+    t.n_seg = static_cast<int32_t>(segs.size());
+    int64_t total = 0;
+    for (size_t i = 0; i < segs.size(); ++i) {
+      t.seg_start[i] = static_cast<int32_t>(segs[i].start);
+      t.seg_end[i] = static_cast<int32_t>(segs[i].end);
+      total += segs[i].end - segs[i].start;
+    }
+    keys[lp->n_tasks++] = total;
+  }
+  // the block with more keys goes first so that its workgroups are not the tail of the launch
+  if (lp->n_tasks == 2 && keys[1] > keys[0]) std::swap(lp->task[0], lp->task[1]);
+  return TASP_OK;
+}
+
+hipError_t launch_attn(const AttnLaunch& lp, const tasp_attn_args* a, hipStream_t stream) {
+  if (lp.n_tasks == 0) return hipSuccess;
+  return a->dtype == TASP_DTYPE_BF16 ? tasp::launch_attn_bf16(lp, a->d, stream)
+                                     : tasp::launch_attn_fp32(lp, a->d, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t tasp_chunk_attn_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_args* a) {
+  if (s == nullptr || a == nullptr || a->S <= 0 || a->Hq <= 0 || a->d <= 0 || s->n <= 0) return 0;
+  const int64_t L = a->S / s->n;
+  const size_t o_bytes = align_up(static_cast<size_t>(L) * a->Hq * a->d * sizeof(float));
+  const size_t lse_bytes = align_up(static_cast<size_t>(L) * a->Hq * sizeof(float));
+  size_t total = 0;
+  if (a->dtype == TASP_DTYPE_BF16) total += o_bytes;              // running fp32 output
+  if (!a->fuse_merge) total += o_bytes + lse_bytes;               // partial (out_s, lse_s) of a step
+  return total;
+}
+
+double tasp_chunk_attn_flops(const tasp_schedule_t* s, const tasp_attn_args* a) {
+  if (s == nullptr || a == nullptr) return 0.0;
+  if (tasp::check_sequence(*s, a->S, a->mask_mode) != TASP_OK) return 0.0;
+  double pairs = 0.0;
+  for (int qb = 0; qb < tasp::n_query_blocks(a->mask_mode); ++qb) {
+    tasp::QueryBlock blk;
+    if (tasp::query_block(*s, a->S, a->mask_mode, qb, &blk) != TASP_OK) return 0.0;
+    const double rows = static_cast<double>(blk.rows);
+    if (a->mask_mode == TASP_MASK_FULL) pairs += rows * static_cast<double>(a->S);
+    else pairs += rows * static_cast<double>(blk.pos0) + rows * (rows + 1.0) / 2.0;   // sum of (p + 1)
+  }
+  return 4.0 * a->d * a->Hq * pairs;
+}
+
+int tasp_step_attn(const tasp_schedule_t* s, const tasp_attn_args* a, int32_t step, float* o_part,
+                   float* lse_part, void* hip_stream) {
+  Shape sh;
+  int st = validate(s, a, &sh);
+  if (st != TASP_OK) return st;
+  if (o_part == nullptr || lse_part == nullptr || step < 0 || step >= s->n) return TASP_EINVAL;
+  if (reinterpret_cast<uintptr_t>(o_part) & 15) return TASP_EALIGN;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  try {
+    AttnLaunch lp{};
+    std::vector<tasp::QueryBlock> empty;
+    st = build_step(s, a, step, &lp, &empty);
+    if (st != TASP_OK) return st;
+    lp.o_dst = o_part; lp.lse_dst = lse_part; lp.merge = 0;
+    if (launch_attn(lp, a, stream) != hipSuccess) return TASP_EHIP;
+    for (const auto& blk : empty)
+      if (tasp::launch_fill_empty(o_part, lse_part, blk.local_row0, blk.rows, a->Hq, a->d, stream) != hipSuccess)
+        return TASP_EHIP;
+  } catch (...) {
+    return TASP_ENOMEM;
+  }
+  return TASP_OK;
+}
+
+int tasp_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream) {
+  Shape sh;
+  int st = validate(s, a, &sh);
+  if (st != TASP_OK) return st;
+  if (a->out == nullptr || a->lse == nullptr) return TASP_EINVAL;
+  if (reinterpret_cast<uintptr_t>(a->out) & 15) return TASP_EALIGN;
+  const size_t need = tasp_chunk_attn_workspace_bytes(s, a);
+  if (need > 0) {
+    if (a->workspace == nullptr || a->workspace_bytes < need) return TASP_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(a->workspace) & (kAlign - 1)) return TASP_EALIGN;
+  }
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+  unsigned char* ws = static_cast<unsigned char*>(a->workspace);
+  float* o_run = static_cast<float*>(a->out);           // fp32: the output itself is the running sum
+  if (a->dtype == TASP_DTYPE_BF16) { o_run = reinterpret_cast<float*>(ws); ws += align_up(sh.o_bytes); }
+  float* o_part = nullptr;
+  float* lse_part = nullptr;
+  if (!a->fuse_merge) {
+    o_part = reinterpret_cast<float*>(ws); ws += align_up(sh.o_bytes);
+    lse_part = reinterpret_cast<float*>(ws);
+  }
+
+  try {
+    std::vector<tasp::QueryBlock> empty;
+    for (int step = 0; step < s->n; ++step) {
+      AttnLaunch lp{};
+      empty.clear();
+      st = build_step(s, a, step, &lp, &empty);
+      if (st != TASP_OK) return st;
+      if (step == 0) {
+        lp.o_dst = o_run; lp.lse_dst = a->lse; lp.merge = 0;
+        if (launch_attn(lp, a, stream) != hipSuccess) return TASP_EHIP;
+        for (const auto& blk : empty)      // cannot happen with the placements of Sec. 3.2.3; kept for safety
+          if (tasp::launch_fill_empty(o_run, a->lse, blk.local_row0, blk.rows, a->Hq, a->d, stream) != hipSuccess)
+            return TASP_EHIP;
+      } else if (a->fuse_merge) {
+        lp.o_dst = o_run; lp.lse_dst = a->lse; lp.merge = 1;
+        if (launch_attn(lp, a, stream) != hipSuccess) return TASP_EHIP;
+      } else {
+        lp.o_dst = o_part; lp.lse_dst = lse_part; lp.merge = 0;
+        if (launch_attn(lp, a, stream) != hipSuccess) return TASP_EHIP;
+        // rows that saw no key at this step have nothing to fold in
+        for (int t = 0; t < lp.n_tasks; ++t)
+          if (tasp::launch_merge(o_run, a->lse, o_part, lse_part, lp.task[t].q_row0, lp.task[t].n_q, a->Hq, a->d,
+                                 stream) != hipSuccess)
+            return TASP_EHIP;
+      }
+    }
+    if (a->dtype == TASP_DTYPE_BF16)
+      if (tasp::launch_cast_bf16(o_run, a->out, sh.L * a->Hq * a->d, stream) != hipSuccess) return TASP_EHIP;
+  } catch (...) {
+    return TASP_ENOMEM;
+  }
+  return TASP_OK;
+}
+
+}  // extern "C"

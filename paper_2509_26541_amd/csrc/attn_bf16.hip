@@ -1,0 +1,372 @@
+// Blockwise attention of one step of Algorithm 3 on gfx950: bf16 inputs, fp32 scores/softmax/output.
+//
+// The paper concatenates the N-1 sub-chunks of a step and calls a flash-attention library on the
+// copy (Algorithm 3; Sec. 5.4 puts the cost of that copy at 1-5 % of the compute time).  Here the
+// kernel walks the *virtual* concatenation instead: a workgroup owns 128 query rows of one head and
+// streams 64-key tiles whose rows are gathered from the K/V segments of the step, so sub-chunk
+// lengths that are no tile multiple cost nothing and nothing is copied.
+//
+// Per wave (32 query rows):  S^T = K Q^T  and  O^T = V^T P^T  with v_mfma_f32_32x32x16_bf16.
+// Computing the transposed products puts one query in one lane column, so the row max / row sum of
+// the online softmax are in-lane reductions over 32 registers plus one exchange between the two
+// lane halves, the rescale factor is a per-lane scalar, and the fp32 -> bf16 P tile is already in
+// the B-operand layout of the second product.  K tiles are read from LDS with 16-byte reads, V
+// tiles with the transposing LDS read (ds_read_b64_tr_b16); both tiles are XOR-swizzled in 16-byte
+// units so that neither the fills nor the reads conflict on banks.
+#include <hip/hip_runtime.h>
+
+#include <climits>
+
+#include "internal.hpp"
+
+namespace tasp {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
+
+constexpr int BM = 128;          // query rows per workgroup (4 waves x 32)
+constexpr int BN = 64;           // keys per tile
+constexpr int NTHREADS = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kRescaleGap = 8.0f;   // the running max is only raised when it grew by more than 2^8
+constexpr float kNegBig = -1.0e30f;
+
+template <int D>
+struct Cfg {
+  static constexpr int UNITS = D / 8;                 // 16-byte units per row
+  static constexpr int RPP = NTHREADS / UNITS;        // rows filled per pass of the workgroup
+  static constexpr int PASSES = BN / RPP;
+  static constexpr int ROWS_PER_LINE = 16 / UNITS;    // rows per 256-byte bank line (1 or 2)
+  static constexpr int TILE_BYTES = BN * D * 2;
+  static constexpr int KV_BYTES = 4 * TILE_BYTES;     // K and V, double buffered
+  static constexpr int OROW = D + 4;                  // padded fp32 row of the epilogue staging
+  static constexpr int EPI_BYTES = 4 * 32 * OROW * 4;
+  static constexpr int SMEM = KV_BYTES > EPI_BYTES ? KV_BYTES : EPI_BYTES;
+  __device__ static int swz_k(int row, int unit) { return unit ^ ((row / ROWS_PER_LINE) % UNITS); }
+  __device__ static int swz_v(int row, int unit) { return unit ^ (4 * ((row / ROWS_PER_LINE) % (UNITS / 4))); }
+};
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int D>
+__global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(const AttnLaunch p) {
+  using C = Cfg<D>;
+  constexpr int KS = D / 16;     // contraction steps of K Q^T
+  constexpr int DB = D / 32;     // 32-row blocks of O^T
+
+  __shared__ __attribute__((aligned(16))) unsigned char smem[C::SMEM];
+  __shared__ __attribute__((aligned(16))) int s_tok[2][BN];           // global position of every key row of a tile (INT_MAX: none)
+  __shared__ int s_flag[2][BN];          // 1: the row needs the element-wise mask
+  __shared__ int e_vbeg[2 * kMaxSeg + 1];  // effective segments: start in the virtual concatenation
+  __shared__ int e_goff[2 * kMaxSeg];      //   global position minus virtual position
+  __shared__ int e_diag[2 * kMaxSeg];      //   straddles the diagonal of this query tile
+  __shared__ int e_n;
+  __shared__ float s_lse[4][32];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int h = lane >> 5;       // lane half
+  const int lq = lane & 31;      // query column inside the wave
+
+  // ---- which (KV head, task, query tile, query head) this workgroup owns.  Workgroups are dealt
+  // round-robin to the 8 XCDs; the index is remapped so that each XCD gets a contiguous run of work
+  // ordered KV-head-major: the workgroups of one XCD then stream the same K/V through its L2.
+  const int G = p.Hq / p.Hkv;
+  const int tiles0 = (p.task[0].n_q + BM - 1) / BM;
+  const int tiles1 = p.n_tasks > 1 ? (p.task[1].n_q + BM - 1) / BM : 0;
+  const int per_g = (tiles0 + tiles1) * G;
+  const int nblocks = gridDim.x;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int q8 = nblocks >> 3, r8 = nblocks & 7;
+  const int w = xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
+  const int g = w / per_g;
+  int rem = w - g * per_g;
+  const int tsk = rem >= tiles0 * G ? 1 : 0;
+  if (tsk) rem -= tiles0 * G;
+  const int tile_q = rem / G;
+  const int hq = g * G + rem % G;
+  const AttnTask& T = p.task[tsk];
+  const int q_tile_row0 = tile_q * BM;                        // relative to the task
+  const int q_rows_here = min(BM, T.n_q - q_tile_row0);
+  const int qa = T.q_pos0 + q_tile_row0;                      // first and last position of the tile
+  const int qb = qa + q_rows_here - 1;
+
+  // ---- effective segment list of this query tile: drop what the causal mask hides from every
+  // row, split the rest into a part every row sees and a part that straddles the diagonal.
+  if (tid == 0) {
+    int n = 0, vpos = 0;
+    for (int s = 0; s < T.n_seg; ++s) {
+      const int a = T.seg_start[s], b = T.seg_end[s];
+      if (!p.causal) {
+        e_vbeg[n] = vpos; e_goff[n] = a - vpos; e_diag[n] = 0; vpos += b - a; ++n;
+        continue;
+      }
+      if (a > qb) continue;
+      const int b_vis = min(b, qb + 1);
+      const int full_end = min(b_vis, qa + 1);
+      if (a < full_end) { e_vbeg[n] = vpos; e_goff[n] = a - vpos; e_diag[n] = 0; vpos += full_end - a; ++n; }
+      const int ds = max(a, full_end);
+      if (ds < b_vis) { e_vbeg[n] = vpos; e_goff[n] = ds - vpos; e_diag[n] = 1; vpos += b_vis - ds; ++n; }
+    }
+    e_vbeg[n] = vpos;
+    e_n = n;
+  }
+  __syncthreads();
+  const int n_eff = e_n;
+  const int total_keys = e_vbeg[n_eff];
+  const int n_tiles = (total_keys + BN - 1) / BN;
+
+  // ---- Q fragments (B operand of K Q^T): lane holds query lq, d = 16 ks + 8 h .. +8
+  const __bf16* Qg = static_cast<const __bf16*>(p.q);
+  const __bf16* Kg = static_cast<const __bf16*>(p.k);
+  const __bf16* Vg = static_cast<const __bf16*>(p.v);
+  const int my_q = q_tile_row0 + wave * 32 + lq;              // row inside the task
+  const bool q_valid = my_q < T.n_q;
+  const int64_t q_row = T.q_row0 + (q_valid ? my_q : T.n_q - 1);
+  bf16x8 qf[KS];
+  {
+    const __bf16* src = Qg + (q_row * p.Hq + hq) * D + 8 * h;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
+  }
+  const int q_pos = p.causal ? T.q_pos0 + my_q : INT_MAX - 1;
+
+  // ---- loader state: this thread fills rows fr + RPP*i, unit fu of every K and V tile
+  const int fr = tid / C::UNITS, fu = tid % C::UNITS;
+  const int64_t kv_head_off = static_cast<int64_t>(g) * D + fu * 8;
+  const int64_t kv_row_stride = static_cast<int64_t>(p.Hkv) * D;
+  int cur = 0;                                                // effective segment of the tile's first row
+  int cur_vend = n_eff > 0 ? e_vbeg[1] : 0;
+  int cur_goff = n_eff > 0 ? e_goff[0] : 0;
+  int cur_diag = n_eff > 0 ? e_diag[0] : 0;
+  uint4 kreg[C::PASSES], vreg[C::PASSES];
+  int tokreg[C::PASSES], flagreg[C::PASSES];
+
+  auto issue_loads = [&](int t) {
+    const int v0 = t * BN;
+    while (cur < n_eff && v0 >= cur_vend) {                   // move to the segment holding row v0
+      ++cur;
+      if (cur < n_eff) { cur_vend = e_vbeg[cur + 1]; cur_goff = e_goff[cur]; cur_diag = e_diag[cur]; }
+    }
+    const bool one_segment = cur < n_eff && v0 + BN <= cur_vend;
+#pragma unroll
+    for (int i = 0; i < C::PASSES; ++i) {
+      const int v = v0 + fr + C::RPP * i;
+      int tok, flag;
+      if (one_segment) {
+        tok = v + cur_goff; flag = cur_diag;
+      } else {
+        int j = cur, vend = cur_vend, goff = cur_goff, dg = cur_diag;
+        while (j < n_eff && v >= vend) {
+          ++j;
+          if (j < n_eff) { vend = e_vbeg[j + 1]; goff = e_goff[j]; dg = e_diag[j]; }
+        }
+        if (j < n_eff) { tok = v + goff; flag = dg; } else { tok = INT_MAX; flag = 1; }
+      }
+      const int64_t row = (tok == INT_MAX) ? 0 : tok;         // rows past the end read token 0, masked later
+      const int64_t off = row * kv_row_stride + kv_head_off;
+      kreg[i] = *reinterpret_cast<const uint4*>(Kg + off);
+      vreg[i] = *reinterpret_cast<const uint4*>(Vg + off);
+      tokreg[i] = tok; flagreg[i] = flag;
+    }
+  };
+  auto store_tile = [&](int buf) {
+    unsigned char* kbase = smem + buf * 2 * C::TILE_BYTES;
+    unsigned char* vbase = kbase + C::TILE_BYTES;
+#pragma unroll
+    for (int i = 0; i < C::PASSES; ++i) {
+      const int row = fr + C::RPP * i;
+      *reinterpret_cast<uint4*>(kbase + (row * C::UNITS + C::swz_k(row, fu)) * 16) = kreg[i];
+      *reinterpret_cast<uint4*>(vbase + (row * C::UNITS + C::swz_v(row, fu)) * 16) = vreg[i];
+      if (fu == 0) { s_tok[buf][row] = tokreg[i]; s_flag[buf][row] = flagreg[i]; }
+    }
+  };
+
+  // ---- per-lane LDS read offsets (loop invariant)
+  int koff[KS];       // K: row lq (+32 kb), unit 2 ks + h
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = (lq * C::UNITS + C::swz_k(lq, 2 * ks + h)) * 16;
+  // V^T through the transposing read: 16-lane group a = lane/16 serves d columns 16 (a%2) .. +16 of
+  // a 32-wide block for lane half h = a/2; lane jj of the group points at key 4 h + jj/4, 4 d values.
+  const int ga = lane >> 4, jj = lane & 15;
+  const int vrow = 4 * (ga >> 1) + (jj >> 2);                 // key row inside a 16-key block (+8 second read)
+  int voff[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    const int unit = 4 * db + 2 * (ga & 1) + ((jj & 3) >> 1);
+    voff[db] = (vrow * C::UNITS + C::swz_v(vrow, unit)) * 16 + 8 * (jj & 1);
+  }
+
+  // ---- running state
+  f32x16 o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+  float m_run = kNegBig;        // running max in the exp2 domain (scaled scores times log2 e)
+  float l_run = 0.f;            // this lane's share of the running sum
+  const float c = p.scale * kLog2e;
+
+  if (n_tiles > 0) {
+    issue_loads(0);
+    store_tile(0);
+  }
+  __syncthreads();
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < n_tiles) issue_loads(t + 1);
+
+    const unsigned char* kbase = smem + buf * 2 * C::TILE_BYTES;
+    const unsigned char* vbase = kbase + C::TILE_BYTES;
+
+    // S^T = K Q^T : two 32-key blocks
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * D * 2 + koff[ks]);
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
+      }
+    }
+
+    // element-wise mask, only for tiles that touch the diagonal or run past the last key
+    if (__builtin_amdgcn_ballot_w64(s_flag[buf][lane] != 0) != 0) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const i32x4 tk = *reinterpret_cast<const i32x4*>(&s_tok[buf][32 * kb + 8 * i4 + 4 * h]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (tk[e] > q_pos) s[kb][4 * i4 + e] = -__builtin_inff();
+        }
+    }
+
+    // online softmax (exp2 domain)
+    float mx = s[0][0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[0][i]);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_cand = fmaxf(m_run, mx * c);
+    if (__builtin_amdgcn_ballot_w64(m_cand > m_run + kRescaleGap) != 0) {
+      const float alpha = fast_exp2(m_run - m_cand);
+      m_run = m_cand;
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    }
+    bf16x8 pf[2][2];
+    float lsum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float pv = fast_exp2(__builtin_fmaf(s[kb][i], c, -m_run));
+        lsum += pv;
+        pf[kb][i >> 3][i & 7] = static_cast<__bf16>(pv);
+      }
+    l_run += lsum;
+
+    // O^T += V^T P^T : per 16-key block, DB blocks of 32 output rows
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const unsigned char* vb = vbase + (32 * kb + 16 * j) * D * 2;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(vb + voff[db]));
+          const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(vb + 8 * D * 2 + voff[db]));
+          const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kb][j], o[db], 0, 0, 0);
+        }
+      }
+
+    if (t + 1 < n_tiles) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: normalise, transpose through LDS, store rows coalesced (and fold into dst)
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const bool seen = l_tot > 0.f;
+  const float inv = seen ? 1.f / l_tot : 0.f;
+  const float lse_mine = seen ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -__builtin_inff();
+  float* ostage = reinterpret_cast<float*>(smem) + wave * 32 * C::OROW;
+  // (the last loop iteration ended with a barrier, so K/V tiles are no longer read)
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      f32x4 val;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) val[e] = o[db][4 * i4 + e] * inv;
+      *reinterpret_cast<f32x4*>(ostage + lq * C::OROW + 32 * db + 8 * i4 + 4 * h) = val;
+    }
+  if (h == 0) s_lse[wave][lq] = lse_mine;
+  __syncthreads();
+
+  constexpr int LPR = D / 4;                 // lanes per output row (16-byte pieces)
+  constexpr int RPI = 64 / LPR;              // rows per iteration of a wave
+  const int sub = lane / LPR, piece = lane % LPR;
+  for (int r0 = 0; r0 < 32; r0 += RPI) {
+    const int r = r0 + sub;
+    const int row_in_task = q_tile_row0 + wave * 32 + r;
+    if (row_in_task >= T.n_q) continue;
+    const int64_t grow = T.q_row0 + row_in_task;
+    float* od = p.o_dst + (grow * p.Hq + hq) * D + 4 * piece;
+    float* ld = p.lse_dst + grow * p.Hq + hq;
+    f32x4 val = *reinterpret_cast<const f32x4*>(ostage + r * C::OROW + 4 * piece);
+    float lse_new = s_lse[wave][r];
+    if (p.merge) {
+      // update_out_lse of Algorithm 3 folded into the store
+      const float lse_old = *ld;
+      const f32x4 old = *reinterpret_cast<const f32x4*>(od);
+      const float mxl = fmaxf(lse_old, lse_new);
+      if (mxl == -__builtin_inff()) {
+        val = f32x4{0.f, 0.f, 0.f, 0.f};
+      } else {
+        const float wa = __expf(lse_old - mxl), wb = __expf(lse_new - mxl);
+        const float den = wa + wb, rden = 1.f / den;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) val[e] = (wa * old[e] + wb * val[e]) * rden;
+        lse_new = mxl + __logf(den);
+      }
+    }
+    *reinterpret_cast<f32x4*>(od) = val;
+    if (piece == 0) *ld = lse_new;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_attn_bf16(const AttnLaunch& p, int d, hipStream_t stream) {
+  int tiles = 0;
+  for (int t = 0; t < p.n_tasks; ++t) tiles += (p.task[t].n_q + BM - 1) / BM;
+  const int64_t blocks = static_cast<int64_t>(tiles) * p.Hq;
+  if (blocks == 0) return hipSuccess;
+  if (blocks > INT_MAX) return hipErrorInvalidValue;
+  dim3 grid(static_cast<unsigned>(blocks)), block(NTHREADS);
+  if (d == 128) hipLaunchKernelGGL(attn_bf16_kernel<128>, grid, block, 0, stream, p);
+  else if (d == 64) hipLaunchKernelGGL(attn_bf16_kernel<64>, grid, block, 0, stream, p);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+}  // namespace tasp

@@ -1,0 +1,46 @@
+// Launch descriptors shared by the host orchestration and the kernels of this library.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace tasp {
+
+constexpr int kMaxSeg = 64;      // KV segments one query block can see in one step (2(N-1) for zig-zag)
+constexpr int kMaxTasks = 2;     // query blocks per step (the two half-chunks of the zig-zag layout)
+
+// One query block of one step: rows [q_row0, q_row0 + n_q) of the local Q, contiguous in the
+// sequence from q_pos0, attending to the concatenation of seg[0..n_seg).
+struct AttnTask {
+  int32_t q_row0;
+  int32_t n_q;
+  int32_t q_pos0;
+  int32_t n_seg;
+  int32_t seg_start[kMaxSeg];
+  int32_t seg_end[kMaxSeg];
+};
+
+struct AttnLaunch {
+  const void* q;      // [L, Hq, d]
+  const void* k;      // [S, Hkv, d]
+  const void* v;      // [S, Hkv, d]
+  float* o_dst;       // [L, Hq, d] fp32
+  float* lse_dst;     // [L, Hq]    fp32
+  int32_t Hq, Hkv;
+  int32_t causal;     // key t visible to query p iff t <= p
+  int32_t merge;      // 0: dst = partial of this step; 1: dst = update_out_lse(dst, partial)
+  float scale;        // softmax scale (natural units)
+  int32_t n_tasks;
+  AttnTask task[kMaxTasks];
+};
+
+// Implemented in attn_bf16.hip / attn_fp32.hip / merge.hip.  Each returns a hipError_t from the launch.
+hipError_t launch_attn_bf16(const AttnLaunch& p, int d, hipStream_t stream);
+hipError_t launch_attn_fp32(const AttnLaunch& p, int d, hipStream_t stream);
+hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
+                        int64_t row0, int64_t rows, int32_t heads, int32_t d, hipStream_t stream);
+hipError_t launch_fill_empty(float* o, float* lse, int64_t row0, int64_t rows, int32_t heads, int32_t d,
+                             hipStream_t stream);
+hipError_t launch_cast_bf16(const float* src, void* dst, int64_t n, hipStream_t stream);
+
+}  // namespace tasp

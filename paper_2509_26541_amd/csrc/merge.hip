@@ -1,0 +1,119 @@
+// update_out_lse of Algorithm 3 as a streaming kernel, plus the two small helpers around it
+// (mark rows that saw no key; cast the fp32 result to bf16).  All three are bound by HBM traffic:
+// every thread moves 16-byte pieces, consecutive lanes touch consecutive addresses.
+#include <hip/hip_runtime.h>
+
+#include "internal.hpp"
+#include "tasp.h"
+
+namespace tasp {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+constexpr int MERGE_THREADS = 256;
+
+// One thread per 4 output columns of one (row, head).  n4 = rows*heads*d/4, pieces = d/4.
+__global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(float* __restrict__ o_acc, float* __restrict__ lse_acc,
+                                                             const float* __restrict__ o_part,
+                                                             const float* __restrict__ lse_part, int64_t n4,
+                                                             int32_t pieces) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * MERGE_THREADS;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * MERGE_THREADS + threadIdx.x; i < n4; i += stride) {
+    const int64_t rh = i / pieces;
+    const float la = lse_acc[rh], lb = lse_part[rh];
+    const f32x4 a = reinterpret_cast<const f32x4*>(o_acc)[i];
+    const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(o_part) + i);
+    const float mx = fmaxf(la, lb);
+    f32x4 r;
+    float lnew;
+    if (mx == -__builtin_inff()) {
+      r = f32x4{0.f, 0.f, 0.f, 0.f};
+      lnew = mx;
+    } else {
+      const float ea = __expf(la - mx), eb = __expf(lb - mx);
+      const float den = ea + eb, rden = 1.f / den;
+      const float wa = ea * rden, wb = eb * rden;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r[e] = wa * a[e] + wb * b[e];
+      lnew = mx + __logf(den);
+    }
+    reinterpret_cast<f32x4*>(o_acc)[i] = r;
+    // d/4 divides 64, so all pieces of a (row, head) sit in one wavefront: its load of la above
+    // was issued for every lane before this store
+    if (i - rh * pieces == 0) lse_acc[rh] = lnew;
+  }
+}
+
+__global__ __launch_bounds__(MERGE_THREADS) void fill_empty_kernel(float* __restrict__ o, float* __restrict__ lse,
+                                                                  int64_t n4, int32_t pieces) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * MERGE_THREADS;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * MERGE_THREADS + threadIdx.x; i < n4; i += stride) {
+    reinterpret_cast<f32x4*>(o)[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (i % pieces == 0) lse[i / pieces] = -__builtin_inff();
+  }
+}
+
+__global__ __launch_bounds__(MERGE_THREADS) void cast_bf16_kernel(const float* __restrict__ src, __bf16* __restrict__ dst,
+                                                                 int64_t n4) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * MERGE_THREADS;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * MERGE_THREADS + threadIdx.x; i < n4; i += stride) {
+    const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src) + i);
+    bf16x4 r;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = static_cast<__bf16>(a[e]);   // round to nearest even
+    reinterpret_cast<bf16x4*>(dst)[i] = r;
+  }
+}
+
+unsigned grid_for(int64_t n_items) {
+  const int64_t want = (n_items + MERGE_THREADS - 1) / MERGE_THREADS;
+  const int64_t cap = 256 * 32;                     // 32 resident workgroups' worth per CU is plenty
+  return static_cast<unsigned>(want < 1 ? 1 : (want > cap ? cap : want));
+}
+
+}  // namespace
+
+hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
+                        int64_t row0, int64_t rows, int32_t heads, int32_t d, hipStream_t stream) {
+  if (rows <= 0) return hipSuccess;
+  const int64_t off = row0 * heads;
+  const int64_t n4 = rows * heads * (d / 4);
+  hipLaunchKernelGGL(merge_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), 0, stream, o_acc + off * d,
+                     lse_acc + off, o_part + off * d, lse_part + off, n4, d / 4);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_empty(float* o, float* lse, int64_t row0, int64_t rows, int32_t heads, int32_t d,
+                             hipStream_t stream) {
+  if (rows <= 0) return hipSuccess;
+  const int64_t off = row0 * heads;
+  const int64_t n4 = rows * heads * (d / 4);
+  hipLaunchKernelGGL(fill_empty_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), 0, stream, o + off * d,
+                     lse + off, n4, d / 4);
+  return hipGetLastError();
+}
+
+hipError_t launch_cast_bf16(const float* src, void* dst, int64_t n, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  const int64_t n4 = n / 4;
+  hipLaunchKernelGGL(cast_bf16_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), 0, stream, src,
+                     static_cast<__bf16*>(dst), n4);
+  return hipGetLastError();
+}
+
+}  // namespace tasp
+
+extern "C" int tasp_lse_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
+                              int64_t rows, int32_t heads, int32_t d, void* hip_stream) {
+  if (rows < 0 || heads <= 0 || d <= 0) return TASP_EINVAL;
+  if (d < 4 || d > 256 || (d & (d - 1)) != 0) return TASP_EUNSUPPORTED_SHAPE;
+  if (rows == 0) return TASP_OK;
+  if (o_acc == nullptr || lse_acc == nullptr || o_part == nullptr || lse_part == nullptr) return TASP_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(o_acc) | reinterpret_cast<uintptr_t>(o_part)) & 15) return TASP_EALIGN;
+  if ((reinterpret_cast<uintptr_t>(lse_acc) | reinterpret_cast<uintptr_t>(lse_part)) & 3) return TASP_EALIGN;
+  const hipError_t e = tasp::launch_merge(o_acc, lse_acc, o_part, lse_part, 0, rows, heads, d,
+                                          static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? TASP_OK : TASP_EHIP;
+}

@@ -1,0 +1,185 @@
+"""Parity of the HIP path (through the C ABI) with the fp64 oracle on the same seeded inputs.
+
+Tolerances (max-abs): fp32 inputs 1e-4 on out and lse; bf16 inputs 2e-2 on out, 1e-3 on lse."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as att
+from oracle import schedule as sch
+from paper_2509_26541_amd import workloads as wl
+from tests.helpers import max_abs, oracle_rows
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": (1e-4, 1e-4), "bf16": (2e-2, 1e-3)}
+
+
+@pytest.fixture(scope="module")
+def tb():
+    assert torch.cuda.is_available(), "GPU tests need an MI355X"
+    from paper_2509_26541_amd import binding
+    return binding
+
+
+def run_gpu(tb, w, q, k, v, **kw):
+    s = tb.tasp_schedule(w.n_ranks, w.rank)
+    out, lse = tb.tasp_chunk_attn(q.cuda(), k.cuda(), v.cuda(), s, w.mask_mode, **kw)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy(), lse.cpu().numpy()
+
+
+def check(w, out, lse, ref_o, ref_l, rows, heads=None):
+    heads = list(range(w.Hq)) if heads is None else heads
+    tol_o, tol_l = TOL[w.dtype]
+    eo = max_abs(out[np.ix_(rows, heads)], ref_o)
+    el = max_abs(lse[np.ix_(rows, heads)], ref_l)
+    assert np.all(np.isfinite(lse[np.ix_(rows, heads)]))
+    assert eo <= tol_o and el <= tol_l, "%s: out err %.3e (tol %g), lse err %.3e (tol %g)" % (w.name, eo, tol_o, el, tol_l)
+    return eo, el
+
+
+# ------------------------------------------------------------------ config 1: every row, fp32
+@pytest.mark.parametrize("fuse", [False, True])
+def test_cfg1_fp32_all_rows(tb, fuse):
+    w = wl.CONFIGS[0]
+    q, k, v = wl.make_qkv(w)
+    out, lse = run_gpu(tb, w, q, k, v, fuse_merge=fuse)
+    rows = list(range(w.L))
+    ref_o, ref_l = oracle_rows(w, q, k, v, rows)
+    check(w, out, lse, ref_o, ref_l, rows)
+
+
+# ------------------------------------------------------------------ small cases, every row
+SMALL = [
+    # name, base config index, N, rank, S, Hq, Hkv, d
+    ("bf16_zz_n8", 1, 8, 3, 4096, 8, 2, 128),
+    ("bf16_zz_n8_ragged", 1, 8, 6, 8 * 2 * 200, 4, 2, 128),     # H = 200: ragged query and key tiles
+    ("bf16_zz_n8_tiny", 1, 8, 0, 112, 2, 1, 128),               # sub-chunks of 1 token
+    ("bf16_full_n8", 2, 8, 0, 8 * 331, 4, 4, 128),              # L = 331, pieces of 47/48
+    ("bf16_full_n4", 2, 4, 2, 4 * 512, 4, 1, 128),
+    ("bf16_zz_n16", 3, 16, 5, 16 * 2 * 96, 8, 1, 128),
+    ("bf16_zz_n8_outliers", 4, 8, 7, 4096, 4, 2, 128),
+    ("bf16_zz_d64", 1, 8, 2, 4096, 4, 2, 64),
+    ("bf16_full_d64", 2, 8, 5, 8 * 200, 2, 2, 64),
+    ("fp32_zz_n8", 0, 8, 4, 8 * 2 * 40, 2, 2, 64),
+    ("fp32_full_d128", 0, 4, 1, 4 * 70, 2, 1, 128),
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+@pytest.mark.parametrize("fuse", [False, True])
+def test_small_all_rows(tb, case, fuse):
+    name, base, n, rank, S, Hq, Hkv, d = case
+    b = wl.CONFIGS[base]
+    w = wl.Workload(name, n, rank, S, Hq, Hkv, d, "fp32" if name.startswith("fp32") else "bf16",
+                    wl.ZIGZAG_CAUSAL if "_zz_" in name else wl.FULL, k_scale=b.k_scale,
+                    outlier_frac=0.05 if "outliers" in name else 0.0, seed=b.seed + 100)
+    q, k, v = wl.make_qkv(w)
+    out, lse = run_gpu(tb, w, q, k, v, fuse_merge=fuse)
+    rows = list(range(w.L))
+    ref_o, ref_l = oracle_rows(w, q, k, v, rows)
+    check(w, out, lse, ref_o, ref_l, rows)
+
+
+def test_ring_order_gives_the_same_result(tb):
+    w = wl.Workload("ring", 8, 3, 4096, 8, 2, 128, "bf16", wl.ZIGZAG_CAUSAL, seed=wl.BASE_SEED + 77)
+    q, k, v = wl.make_qkv(w)
+    out, lse = run_gpu(tb, w, q, k, v, order=tb.ORDER_RING)
+    rows = list(range(w.L))
+    ref_o, ref_l = oracle_rows(w, q, k, v, rows)
+    check(w, out, lse, ref_o, ref_l, rows)
+
+
+# ------------------------------------------------------------------ one step at a time
+@pytest.mark.parametrize("mode", [wl.FULL, wl.ZIGZAG_CAUSAL])
+def test_step_partials_match_algorithm_3(tb, mode):
+    """tasp_step_attn against the oracle's per-step partial (out_s, lse_s), including rows that see
+    nothing at a step (lse = -inf, out = 0)."""
+    # rank 0: every remote sub-chunk comes from a higher rank, so the first half-chunk's rows see
+    # nothing after step 0 in the zig-zag layout
+    w = wl.Workload("steps", 8, 0, 8 * 2 * 72, 4, 2, 128, "bf16", mode, seed=wl.BASE_SEED + 55)
+    q, k, v = wl.make_qkv(w)
+    s = tb.tasp_schedule(w.n_ranks, w.rank)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    pos = sch.local_positions(w.n_ranks, w.rank, w.S, mode)
+    rows = list(range(0, w.L, 5))
+    h = 3
+    g = h * w.Hkv // w.Hq
+    _, _, partials = att.stepwise_rows(q[rows, h].double().numpy(), [pos[r] for r in rows], k[:, g].double().numpy(),
+                                       v[:, g].double().numpy(), w.n_ranks, w.rank, mode)
+    saw_empty = False
+    for step in range(w.n_ranks):
+        o, l = tb.tasp_step_attn(qd, kd, vd, s, mode, step)
+        torch.cuda.synchronize()
+        o, l = o.cpu().numpy()[rows, h], l.cpu().numpy()[rows, h]
+        ref_o, ref_l = partials[step]
+        assert np.array_equal(np.isneginf(l), np.isneginf(ref_l))
+        saw_empty |= bool(np.any(np.isneginf(ref_l)))
+        assert max_abs(l, ref_l) <= 1e-3 and max_abs(o, ref_o) <= 2e-2
+        assert np.all(o[np.isneginf(l)] == 0)
+    assert saw_empty == (mode == wl.ZIGZAG_CAUSAL)
+
+
+# ------------------------------------------------------------------ update_out_lse kernel
+def test_lse_merge_kernel(tb):
+    rng = np.random.default_rng(11)
+    rows, heads, d = 777, 5, 128
+    oa, ob = rng.standard_normal((rows, heads, d)), rng.standard_normal((rows, heads, d))
+    la, lb = rng.standard_normal((rows, heads)) * 6, rng.standard_normal((rows, heads)) * 6
+    la[::7] = -np.inf
+    lb[::5] = -np.inf                      # every 35th row: both empty
+    oa[np.isneginf(la)] = 0
+    ob[np.isneginf(lb)] = 0
+    la[3, 1], lb[3, 1] = 50.0, -60.0       # huge gap
+    t = [torch.tensor(x, dtype=torch.float32).cuda() for x in (oa, la, ob, lb)]
+    ref_o, ref_l = att.lse_merge(t[0].cpu().double().numpy(), t[1].cpu().double().numpy(),
+                                 t[2].cpu().double().numpy(), t[3].cpu().double().numpy())
+    tb.tasp_lse_merge(*t)
+    torch.cuda.synchronize()
+    got_o, got_l = t[0].cpu().numpy(), t[1].cpu().numpy()
+    assert np.array_equal(np.isneginf(got_l), np.isneginf(ref_l))
+    assert max_abs(got_l, ref_l) <= 1e-5 and max_abs(got_o, ref_o) <= 1e-5
+    assert np.all(got_o[np.isneginf(got_l)] == 0)
+    # d = 64 and a ragged count
+    t = [torch.tensor(x[:33, :3, :64] if x.ndim == 3 else x[:33, :3], dtype=torch.float32).contiguous().cuda()
+         for x in (oa, la, ob, lb)]
+    ref_o, ref_l = att.lse_merge(*[x.cpu().double().numpy() for x in (t[0], t[1], t[2], t[3])])
+    tb.tasp_lse_merge(*t)
+    torch.cuda.synchronize()
+    assert max_abs(t[1].cpu().numpy(), ref_l) <= 1e-5 and max_abs(t[0].cpu().numpy(), ref_o) <= 1e-5
+
+
+# ------------------------------------------------------------------ full-size configs, sampled rows
+FULL_SIZE = [(1, 24, 96), (2, 16, 48), (3, 12, 32), (4, 8, 24)]
+
+
+@pytest.mark.parametrize("idx,n_all_heads,n_one_head", FULL_SIZE, ids=[wl.CONFIGS[i[0]].name for i in FULL_SIZE])
+def test_full_size_sampled_rows(tb, idx, n_all_heads, n_one_head):
+    """The launch configuration the benchmark times, checked on sampled rows the oracle computes one
+    by one: tile-edge and half-chunk-edge rows plus seeded random rows; every head on the first set,
+    one head per KV group on a larger set."""
+    w = wl.CONFIGS[idx]
+    q, k, v = wl.make_qkv(w)
+    s = tb.tasp_schedule(w.n_ranks, w.rank)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    results = {}
+    for fuse in (False, True):
+        out, lse = tb.tasp_chunk_attn(qd, kd, vd, s, w.mask_mode, fuse_merge=fuse)
+        torch.cuda.synchronize()
+        results[fuse] = (out.float().cpu().numpy(), lse.cpu().numpy())
+    del qd, kd, vd
+    torch.cuda.empty_cache()
+    rows_a = wl.sample_rows(w, n_all_heads)[: n_all_heads + 8]
+    rows_b = wl.sample_rows(w, n_one_head, seed_offset=1)
+    G = w.Hq // w.Hkv
+    heads_b = [g * G + (g % G) for g in range(w.Hkv)]
+    ref_a = oracle_rows(w, q, k, v, rows_a)
+    ref_b = oracle_rows(w, q, k, v, rows_b, heads_b)
+    for fuse, (out, lse) in results.items():
+        check(w, out, lse, ref_a[0], ref_a[1], rows_a)
+        check(w, out, lse, ref_b[0], ref_b[1], rows_b, heads_b)
+    # properties that hold at any size: finite everywhere, the two merge paths agree closely
+    for out, lse in results.values():
+        assert np.all(np.isfinite(lse)) and np.all(np.isfinite(out))
+    assert max_abs(results[False][1], results[True][1]) <= 1e-4
