@@ -1,0 +1,157 @@
+"""Benchmark of one rank's TASP-ordered chunked attention on one MI355X.
+
+A "step" is one whole tasp_chunk_attn call (all N steps of Algorithm 3: step attention over the
+arriving sub-chunks, update_out_lse, final cast) over one batch of seeded synthetic input that is
+already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--fuse-merge 0|1]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3        # MI355X fp32 vector
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(w, q, k, v, budget_s=15.0):
+    """The oracle, as it stands, on a bounded sample of the same workload: dense fp64 attention of
+    sampled local rows for all heads of one KV group, sized by a short calibration to ~budget_s."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+
+    from oracle import attention as att
+    from oracle import schedule as sch
+    from paper_2509_26541_amd import workloads as wl
+    from tests.helpers import oracle_rows
+
+    G = w.Hq // w.Hkv
+    heads = list(range(G))                       # the query heads of KV head 0
+    pos = np.asarray(sch.local_positions(w.n_ranks, w.rank, w.S, w.mask_mode), dtype=np.int64)
+    causal = w.mask_mode == sch.ZIGZAG_CAUSAL
+
+    def run(rows):
+        t0 = time.perf_counter()
+        oracle_rows(w, q, k, v, rows, heads)
+        dt = time.perf_counter() - t0
+        pairs = float(np.sum(pos[rows] + 1)) if causal else float(len(rows)) * w.S
+        return dt, 4.0 * w.d * len(heads) * pairs
+
+    all_rows = wl.sample_rows(w, 4096)
+    probe = all_rows[:: max(1, len(all_rows) // 8)][:8]
+    dt, _ = run(probe)
+    n = int(max(8, min(len(all_rows), budget_s / max(dt / len(probe), 1e-6))))
+    rows = all_rows[:: max(1, len(all_rows) // n)][:n]
+    dt, flops = run(rows)
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+        "sample": "%d sampled local rows x %d query heads (KV head 0), dense fp64 over all %d keys, %.1f s; "
+                  "host has %d cores" % (len(rows), len(heads), w.S, dt, len(os.sched_getaffinity(0))),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="1..5, the workload list of BASELINE.json")
+    ap.add_argument("--fuse-merge", type=int, default=0)
+    ap.add_argument("--order", choices=["tasp", "ring"], default="tasp")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one rank's share on ONE GPU; --gpus N > 1 is not part of this build "
+              "(no collectives, no sharding).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2509_26541_amd import binding as tb
+    from paper_2509_26541_amd import workloads as wl
+
+    w = wl.CONFIGS[args.config - 1]
+    q, k, v = wl.make_qkv(w)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    sched = tb.tasp_schedule(w.n_ranks, w.rank)
+    order = tb.ORDER_TASP if args.order == "tasp" else tb.ORDER_RING
+    plan = tb.ChunkAttnPlan(sched, qd, kd, vd, w.mask_mode, order=order, fuse_merge=bool(args.fuse_merge))
+    flops = plan.flops()
+
+    for _ in range(args.warmup):
+        plan.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        plan.run()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-kernel durations, HIP events around every launch on the launch stream (same work again)
+    n_prof = max(1, min(args.steps, 5))
+    attn_ms = merge_ms = other_ms = 0.0
+    attn_n = merge_n = 0
+    for _ in range(n_prof):
+        pr = plan.profile()
+        attn_ms += pr.attn_ms
+        merge_ms += pr.merge_ms
+        other_ms += pr.other_ms
+        attn_n += pr.attn_launches
+        merge_n += pr.merge_launches
+    is_bf16 = w.dtype == "bf16"
+    peak = PEAK_BF16_TFLOPS if is_bf16 else PEAK_FP32_TFLOPS
+    attn_avg_ms = attn_ms / max(attn_n, 1)
+    flops_per_launch = flops / w.n_ranks                     # a launch = one step of Algorithm 3
+    achieved = flops_per_launch / (attn_avg_ms * 1e-3) / 1e12
+    roofline = {
+        "bound": "mfma" if is_bf16 else "alu", "kernel": "attn_bf16_kernel" if is_bf16 else "attn_fp32_kernel",
+        "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+        "avg_launch_ms": attn_avg_ms, "launches_per_call": attn_n // n_prof,
+    }
+    merge = None
+    if merge_n:
+        # update_out_lse: per (row, head) read 2(4d+4) and write 4d+4 bytes; rows merged per call =
+        # all rows of every task of steps 1..N-1
+        bytes_per_rh = 3 * (4 * w.d + 4)
+        rows_heads = 0
+        for step in range(1, w.n_ranks):
+            for qb in range(2 if w.mask_mode == wl.ZIGZAG_CAUSAL else 1):
+                if sched.step_segments(w.S, w.mask_mode, step, qb, order=order):
+                    rows_heads += (w.L // (2 if w.mask_mode == wl.ZIGZAG_CAUSAL else 1)) * w.Hq
+        gbs = rows_heads * bytes_per_rh / (merge_ms / n_prof * 1e-3) / 1e9
+        merge = {"bound": "hbm", "kernel": "merge_kernel", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                 "frac": gbs / PEAK_HBM_GBS, "ms_per_call": merge_ms / n_prof, "launches_per_call": merge_n // n_prof}
+
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    line = {
+        "metric": "per-rank chunked-attention TFLOP/s on 1 MI355X", "value": value, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if is_bf16 else "f32", "data": "synthetic",
+        "frac_of_bf16_mfma_peak": value / PEAK_BF16_TFLOPS if is_bf16 else None,
+        "config": {"workload": w.name, "n_ranks": w.n_ranks, "rank": w.rank, "S": w.S, "L": w.L, "Hq": w.Hq,
+                   "Hkv": w.Hkv, "d": w.d, "mask": "zigzag_causal" if w.mask_mode else "full",
+                   "order": args.order, "fuse_merge": int(args.fuse_merge), "flops_per_call": flops},
+        "roofline": roofline,
+        "merge": merge,
+        "ms_breakdown": {"attn": attn_ms / n_prof, "merge": merge_ms / n_prof, "cast": other_ms / n_prof},
+    }
+    if not args.no_cpu_baseline:
+        del plan, qd, kd, vd
+        torch.cuda.empty_cache()
+        line["cpu_baseline"] = cpu_baseline(w, q, k, v)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

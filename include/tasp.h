@@ -142,6 +142,16 @@ typedef struct tasp_attn_args {
 size_t tasp_chunk_attn_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_args* a);
 int    tasp_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream);
 
+/* The same call with every kernel launch bracketed by HIP events on `hip_stream`, for measurement.
+ * Synchronises the stream before returning.  Times are sums over launches, in milliseconds:
+ * attn = step-attention kernels, merge = update_out_lse kernels, other = the final bf16 cast. */
+typedef struct tasp_profile {
+  double  attn_ms, merge_ms, other_ms;
+  int32_t attn_launches, merge_launches, other_launches;
+} tasp_profile;
+int tasp_chunk_attn_profile(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream,
+                            tasp_profile* out);
+
 /* One step of the same pass: the partial (out_s, lse_s) of step `step` alone, before any merge.
  * o_part device [L, Hq, d] fp32, lse_part device [L, Hq] fp32.  Rows that see no key at this step
  * get out = 0, lse = -inf.  a->out, a->lse, a->workspace are not used. */

@@ -24,7 +24,7 @@ EXPORTS = [
     "tasp_schedule_rank", "tasp_schedule_n_rings", "tasp_schedule_max_arc_load", "tasp_schedule_rings",
     "tasp_schedule_out_mapping", "tasp_schedule_in_mapping", "tasp_schedule_arrival", "tasp_subchunk_ranges",
     "tasp_step_segments", "tasp_chunk_attn_workspace_bytes", "tasp_chunk_attn", "tasp_step_attn",
-    "tasp_lse_merge", "tasp_chunk_attn_flops",
+    "tasp_lse_merge", "tasp_chunk_attn_flops", "tasp_chunk_attn_profile",
 ]
 
 
@@ -41,6 +41,11 @@ class AttnArgs(C.Structure):
         ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32), ("dtype", C.c_int32),
         ("mask_mode", C.c_int32), ("order", C.c_int32), ("fuse_merge", C.c_int32), ("softmax_scale", C.c_float),
     ]
+
+
+class Profile(C.Structure):
+    _fields_ = [("attn_ms", C.c_double), ("merge_ms", C.c_double), ("other_ms", C.c_double),
+                ("attn_launches", C.c_int32), ("merge_launches", C.c_int32), ("other_launches", C.c_int32)]
 
 
 def _load():
@@ -69,6 +74,7 @@ def _load():
     lib.tasp_chunk_attn_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(AttnArgs)]
     lib.tasp_chunk_attn_workspace_bytes.restype = C.c_size_t
     lib.tasp_chunk_attn.argtypes = [C.c_void_p, C.POINTER(AttnArgs), C.c_void_p]
+    lib.tasp_chunk_attn_profile.argtypes = [C.c_void_p, C.POINTER(AttnArgs), C.c_void_p, C.POINTER(Profile)]
     lib.tasp_step_attn.argtypes = [C.c_void_p, C.POINTER(AttnArgs), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.tasp_lse_merge.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                    C.c_int32, C.c_void_p]
@@ -178,6 +184,15 @@ class ChunkAttnPlan:
         s = torch.cuda.current_stream().cuda_stream if stream is None else stream
         _check(lib.tasp_chunk_attn(self.schedule.handle, C.byref(self.args), C.c_void_p(s)), "tasp_chunk_attn")
         return self.out, self.lse
+
+    def profile(self, stream=None):
+        """Runs the call once with per-launch HIP-event timing; returns a Profile (milliseconds)."""
+        torch = _torch()
+        s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        prof = Profile()
+        _check(lib.tasp_chunk_attn_profile(self.schedule.handle, C.byref(self.args), C.c_void_p(s), C.byref(prof)),
+               "tasp_chunk_attn_profile")
+        return prof
 
     def flops(self):
         return lib.tasp_chunk_attn_flops(self.schedule.handle, C.byref(self.args))

@@ -80,6 +80,36 @@ int build_step(const tasp_schedule_t* s, const tasp_attn_args* a, int step, Attn
   return TASP_OK;
 }
 
+// Optional per-launch timing with HIP events on the caller's stream (tasp_chunk_attn_profile).
+struct Profiler {
+  enum Kind { kAttn = 0, kMerge = 1, kOther = 2 };
+  struct Span { int kind; hipEvent_t beg, end; };
+  std::vector<Span> spans;
+  hipStream_t stream = nullptr;
+  bool failed = false;
+  void begin(int kind) {
+    Span sp{kind, nullptr, nullptr};
+    if (hipEventCreate(&sp.beg) != hipSuccess || hipEventCreate(&sp.end) != hipSuccess) { failed = true; return; }
+    if (hipEventRecord(sp.beg, stream) != hipSuccess) failed = true;
+    spans.push_back(sp);
+  }
+  void end() {
+    if (spans.empty() || failed) return;
+    if (hipEventRecord(spans.back().end, stream) != hipSuccess) failed = true;
+  }
+  ~Profiler() {
+    for (auto& sp : spans) {
+      if (sp.beg) (void)hipEventDestroy(sp.beg);
+      if (sp.end) (void)hipEventDestroy(sp.end);
+    }
+  }
+};
+struct Scope {
+  Profiler* p;
+  Scope(Profiler* prof, int kind) : p(prof) { if (p) p->begin(kind); }
+  ~Scope() { if (p) p->end(); }
+};
+
 hipError_t launch_attn(const AttnLaunch& lp, const tasp_attn_args* a, hipStream_t stream) {
   if (lp.n_tasks == 0) return hipSuccess;
   return a->dtype == TASP_DTYPE_BF16 ? tasp::launch_attn_bf16(lp, a->d, stream)
@@ -139,7 +169,7 @@ int tasp_step_attn(const tasp_schedule_t* s, const tasp_attn_args* a, int32_t st
   return TASP_OK;
 }
 
-int tasp_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream) {
+static int run_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream, Profiler* prof) {
   Shape sh;
   int st = validate(s, a, &sh);
   if (st != TASP_OK) return st;
@@ -171,25 +201,64 @@ int tasp_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip
       if (st != TASP_OK) return st;
       if (step == 0) {
         lp.o_dst = o_run; lp.lse_dst = a->lse; lp.merge = 0;
-        if (launch_attn(lp, a, stream) != hipSuccess) return TASP_EHIP;
+        {
+          Scope sc(prof, Profiler::kAttn);
+          if (launch_attn(lp, a, stream) != hipSuccess) return TASP_EHIP;
+        }
         for (const auto& blk : empty)      // cannot happen with the placements of Sec. 3.2.3; kept for safety
           if (tasp::launch_fill_empty(o_run, a->lse, blk.local_row0, blk.rows, a->Hq, a->d, stream) != hipSuccess)
             return TASP_EHIP;
       } else if (a->fuse_merge) {
         lp.o_dst = o_run; lp.lse_dst = a->lse; lp.merge = 1;
+        Scope sc(prof, Profiler::kAttn);
         if (launch_attn(lp, a, stream) != hipSuccess) return TASP_EHIP;
       } else {
         lp.o_dst = o_part; lp.lse_dst = lse_part; lp.merge = 0;
-        if (launch_attn(lp, a, stream) != hipSuccess) return TASP_EHIP;
+        {
+          Scope sc(prof, Profiler::kAttn);
+          if (launch_attn(lp, a, stream) != hipSuccess) return TASP_EHIP;
+        }
         // rows that saw no key at this step have nothing to fold in
-        for (int t = 0; t < lp.n_tasks; ++t)
+        for (int t = 0; t < lp.n_tasks; ++t) {
+          Scope sc(prof, Profiler::kMerge);
           if (tasp::launch_merge(o_run, a->lse, o_part, lse_part, lp.task[t].q_row0, lp.task[t].n_q, a->Hq, a->d,
                                  stream) != hipSuccess)
             return TASP_EHIP;
+        }
       }
     }
-    if (a->dtype == TASP_DTYPE_BF16)
+    if (a->dtype == TASP_DTYPE_BF16) {
+      Scope sc(prof, Profiler::kOther);
       if (tasp::launch_cast_bf16(o_run, a->out, sh.L * a->Hq * a->d, stream) != hipSuccess) return TASP_EHIP;
+    }
+  } catch (...) {
+    return TASP_ENOMEM;
+  }
+  return TASP_OK;
+}
+
+int tasp_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream) {
+  return run_chunk_attn(s, a, hip_stream, nullptr);
+}
+
+int tasp_chunk_attn_profile(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream,
+                            tasp_profile* out) {
+  if (out == nullptr) return TASP_EINVAL;
+  *out = tasp_profile{};
+  try {
+    Profiler prof;
+    prof.stream = static_cast<hipStream_t>(hip_stream);
+    const int st = run_chunk_attn(s, a, hip_stream, &prof);
+    if (hipStreamSynchronize(prof.stream) != hipSuccess) return TASP_EHIP;
+    if (st != TASP_OK) return st;
+    if (prof.failed) return TASP_EHIP;
+    for (const auto& sp : prof.spans) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, sp.beg, sp.end) != hipSuccess) return TASP_EHIP;
+      if (sp.kind == Profiler::kAttn) { out->attn_ms += ms; ++out->attn_launches; }
+      else if (sp.kind == Profiler::kMerge) { out->merge_ms += ms; ++out->merge_launches; }
+      else { out->other_ms += ms; ++out->other_launches; }
+    }
   } catch (...) {
     return TASP_ENOMEM;
   }

@@ -154,15 +154,19 @@ def test_lse_merge_kernel(tb):
 FULL_SIZE = [(1, 24, 96), (2, 16, 48), (3, 12, 32), (4, 8, 24)]
 
 
+@pytest.mark.timeout(900)
 @pytest.mark.parametrize("idx,n_all_heads,n_one_head", FULL_SIZE, ids=[wl.CONFIGS[i[0]].name for i in FULL_SIZE])
 def test_full_size_sampled_rows(tb, idx, n_all_heads, n_one_head):
     """The launch configuration the benchmark times, checked on sampled rows the oracle computes one
     by one: tile-edge and half-chunk-edge rows plus seeded random rows; every head on the first set,
     one head per KV group on a larger set."""
     w = wl.CONFIGS[idx]
+    say = lambda msg: print("[%s] %s" % (w.name, msg), flush=True)
+    say("generating inputs")
     q, k, v = wl.make_qkv(w)
     s = tb.tasp_schedule(w.n_ranks, w.rank)
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    say("running tasp_chunk_attn (merge kernel, then fused merge)")
     results = {}
     for fuse in (False, True):
         out, lse = tb.tasp_chunk_attn(qd, kd, vd, s, w.mask_mode, fuse_merge=fuse)
@@ -174,8 +178,11 @@ def test_full_size_sampled_rows(tb, idx, n_all_heads, n_one_head):
     rows_b = wl.sample_rows(w, n_one_head, seed_offset=1)
     G = w.Hq // w.Hkv
     heads_b = [g * G + (g % G) for g in range(w.Hkv)]
+    say("oracle: %d rows x all heads" % len(rows_a))
     ref_a = oracle_rows(w, q, k, v, rows_a)
+    say("oracle: %d rows x %d heads" % (len(rows_b), len(heads_b)))
     ref_b = oracle_rows(w, q, k, v, rows_b, heads_b)
+    say("comparing")
     for fuse, (out, lse) in results.items():
         check(w, out, lse, ref_a[0], ref_a[1], rows_a)
         check(w, out, lse, ref_b[0], ref_b[1], rows_b, heads_b)
