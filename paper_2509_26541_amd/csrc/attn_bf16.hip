@@ -29,6 +29,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
 
 constexpr int BM = 128;          // query rows per workgroup (4 waves x 32)
@@ -148,45 +149,50 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(const AttnLaunch
   int cur_vend = n_eff > 0 ? e_vbeg[1] : 0;
   int cur_goff = n_eff > 0 ? e_goff[0] : 0;
   int cur_diag = n_eff > 0 ? e_diag[0] : 0;
-  uint4 kreg[C::PASSES], vreg[C::PASSES];
+  u32x4 kreg[C::PASSES], vreg[C::PASSES];
   int tokreg[C::PASSES], flagreg[C::PASSES];
 
-  auto issue_loads = [&](int t) {
+  auto issue_loads = [&](int t) __attribute__((always_inline)) {
     const int v0 = t * BN;
     while (cur < n_eff && v0 >= cur_vend) {                   // move to the segment holding row v0
       ++cur;
       if (cur < n_eff) { cur_vend = e_vbeg[cur + 1]; cur_goff = e_goff[cur]; cur_diag = e_diag[cur]; }
     }
-    const bool one_segment = cur < n_eff && v0 + BN <= cur_vend;
+    if (cur < n_eff && v0 + BN <= cur_vend) {                 // the whole tile lies in one segment
 #pragma unroll
-    for (int i = 0; i < C::PASSES; ++i) {
-      const int v = v0 + fr + C::RPP * i;
-      int tok, flag;
-      if (one_segment) {
-        tok = v + cur_goff; flag = cur_diag;
-      } else {
-        int j = cur, vend = cur_vend, goff = cur_goff, dg = cur_diag;
-        while (j < n_eff && v >= vend) {
+      for (int i = 0; i < C::PASSES; ++i) { tokreg[i] = v0 + fr + C::RPP * i + cur_goff; flagreg[i] = cur_diag; }
+    } else {
+      int j = cur, vend = cur_vend, goff = cur_goff, dg = cur_diag;
+      auto locate = [&](int v, int& tok, int& flag) __attribute__((always_inline)) {
+        while (j < n_eff && v >= vend) {                      // rows ascend, so j only moves forward
           ++j;
           if (j < n_eff) { vend = e_vbeg[j + 1]; goff = e_goff[j]; dg = e_diag[j]; }
         }
-        if (j < n_eff) { tok = v + goff; flag = dg; } else { tok = INT_MAX; flag = 1; }
-      }
-      const int64_t row = (tok == INT_MAX) ? 0 : tok;         // rows past the end read token 0, masked later
+        tok = j < n_eff ? v + goff : INT_MAX;
+        flag = j < n_eff ? dg : 1;
+      };
+      locate(v0 + fr, tokreg[0], flagreg[0]);
+      if constexpr (C::PASSES > 1) locate(v0 + fr + C::RPP, tokreg[1], flagreg[1]);
+      if constexpr (C::PASSES > 2) locate(v0 + fr + 2 * C::RPP, tokreg[2], flagreg[2]);
+      if constexpr (C::PASSES > 3) locate(v0 + fr + 3 * C::RPP, tokreg[3], flagreg[3]);
+      static_assert(C::PASSES <= 4, "loader handles at most 4 passes");
+    }
+#pragma unroll
+    for (int i = 0; i < C::PASSES; ++i) {
+      const int64_t row = (tokreg[i] == INT_MAX) ? 0 : tokreg[i];   // rows past the end read token 0, masked later
       const int64_t off = row * kv_row_stride + kv_head_off;
-      kreg[i] = *reinterpret_cast<const uint4*>(Kg + off);
-      vreg[i] = *reinterpret_cast<const uint4*>(Vg + off);
-      tokreg[i] = tok; flagreg[i] = flag;
+      kreg[i] = *reinterpret_cast<const u32x4*>(Kg + off);
+      vreg[i] = *reinterpret_cast<const u32x4*>(Vg + off);
     }
   };
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](int buf) __attribute__((always_inline)) {
     unsigned char* kbase = smem + buf * 2 * C::TILE_BYTES;
     unsigned char* vbase = kbase + C::TILE_BYTES;
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
       const int row = fr + C::RPP * i;
-      *reinterpret_cast<uint4*>(kbase + (row * C::UNITS + C::swz_k(row, fu)) * 16) = kreg[i];
-      *reinterpret_cast<uint4*>(vbase + (row * C::UNITS + C::swz_v(row, fu)) * 16) = vreg[i];
+      *reinterpret_cast<u32x4*>(kbase + (row * C::UNITS + C::swz_k(row, fu)) * 16) = kreg[i];
+      *reinterpret_cast<u32x4*>(vbase + (row * C::UNITS + C::swz_v(row, fu)) * 16) = vreg[i];
       if (fu == 0) { s_tok[buf][row] = tokreg[i]; s_flag[buf][row] = flagreg[i]; }
     }
   };
