@@ -2,7 +2,7 @@
 //
 // The paper concatenates the N-1 sub-chunks of a step and calls a flash-attention library on the
 // copy (Algorithm 3; Sec. 5.4 puts the cost of that copy at 1-5 % of the compute time).  Here the
-// kernel walks the *virtual* concatenation instead: a workgroup owns 128 query rows of one head and
+// kernel walks the *virtual* concatenation instead: a workgroup owns 32 x NWAVES query rows of one head and
 // streams 64-key tiles whose rows are gathered from the K/V segments of the step, so sub-chunk
 // lengths that are no tile multiple cost nothing and nothing is copied.
 //
@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include <climits>
+#include <cstdlib>
 
 #include "internal.hpp"
 
@@ -32,34 +33,32 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
 
-constexpr int BM = 128;          // query rows per workgroup (4 waves x 32)
 constexpr int BN = 64;           // keys per tile
-constexpr int NTHREADS = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kRescaleGap = 8.0f;   // the running max is only raised when it grew by more than 2^8
 constexpr float kNegBig = -1.0e30f;
 
-template <int D>
+template <int D, int NWAVES>
 struct Cfg {
+  static constexpr int NTHREADS = 64 * NWAVES;
+  static constexpr int BM = 32 * NWAVES;              // query rows per workgroup
   static constexpr int UNITS = D / 8;                 // 16-byte units per row
-  static constexpr int RPP = NTHREADS / UNITS;        // rows filled per pass of the workgroup
+  static constexpr int RPP = NTHREADS / UNITS < BN ? NTHREADS / UNITS : BN;   // rows filled per pass
   static constexpr int PASSES = BN / RPP;
   static constexpr int ROWS_PER_LINE = 16 / UNITS;    // rows per 256-byte bank line (1 or 2)
   static constexpr int TILE_BYTES = BN * D * 2;
-  static constexpr int KV_BYTES = 4 * TILE_BYTES;     // K and V, double buffered
-  static constexpr int OROW = D + 4;                  // padded fp32 row of the epilogue staging
-  static constexpr int EPI_BYTES = 4 * 32 * OROW * 4;
-  static constexpr int SMEM = KV_BYTES > EPI_BYTES ? KV_BYTES : EPI_BYTES;
+  static constexpr int SMEM = 4 * TILE_BYTES;         // K and V, double buffered
   __device__ static int swz_k(int row, int unit) { return unit ^ ((row / ROWS_PER_LINE) % UNITS); }
   __device__ static int swz_v(int row, int unit) { return unit ^ (4 * ((row / ROWS_PER_LINE) % (UNITS / 4))); }
 };
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <int D>
-__global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(const AttnLaunch p) {
-  using C = Cfg<D>;
+template <int D, int NWAVES>
+__global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLaunch p) {
+  using C = Cfg<D, NWAVES>;
+  constexpr int BM = C::BM;
   constexpr int KS = D / 16;     // contraction steps of K Q^T
   constexpr int DB = D / 32;     // 32-row blocks of O^T
 
@@ -70,7 +69,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(const AttnLaunch
   __shared__ int e_goff[2 * kMaxSeg];      //   global position minus virtual position
   __shared__ int e_diag[2 * kMaxSeg];      //   straddles the diagonal of this query tile
   __shared__ int e_n;
-  __shared__ float s_lse[4][32];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -139,10 +137,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(const AttnLaunch
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
   }
+  // Land the Q fragments now (vmcnt(0)); otherwise their pending loads make the compiler wait on
+  // the K/V prefetch of each iteration in front of the first products that read qf.
+  __builtin_amdgcn_s_waitcnt(0x0F70);
   const int q_pos = p.causal ? T.q_pos0 + my_q : INT_MAX - 1;
 
   // ---- loader state: this thread fills rows fr + RPP*i, unit fu of every K and V tile
-  const int fr = tid / C::UNITS, fu = tid % C::UNITS;
+  const int fr = tid / C::UNITS, fu = tid % C::UNITS;   // RPP = NTHREADS / UNITS rows per pass
   const int64_t kv_head_off = static_cast<int64_t>(g) * D + fu * 8;
   const int64_t kv_row_stride = static_cast<int64_t>(p.Hkv) * D;
   int cur = 0;                                                // effective segment of the tile's first row
@@ -309,70 +310,71 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_bf16_kernel(const AttnLaunch
     __syncthreads();
   }
 
-  // ---- epilogue: normalise, transpose through LDS, store rows coalesced (and fold into dst)
+  // ---- epilogue: normalise and store.  A lane owns one query row; per (db, i4) it holds 4
+  // consecutive output columns, and its partner lane (+32) the next 4, so a wavefront writes
+  // 32-byte pieces of 32 rows per store and the 16 stores of a lane complete its 512-byte row.
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const bool seen = l_tot > 0.f;
   const float inv = seen ? 1.f / l_tot : 0.f;
-  const float lse_mine = seen ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -__builtin_inff();
-  float* ostage = reinterpret_cast<float*>(smem) + wave * 32 * C::OROW;
-  // (the last loop iteration ended with a barrier, so K/V tiles are no longer read)
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      f32x4 val;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) val[e] = o[db][4 * i4 + e] * inv;
-      *reinterpret_cast<f32x4*>(ostage + lq * C::OROW + 32 * db + 8 * i4 + 4 * h) = val;
-    }
-  if (h == 0) s_lse[wave][lq] = lse_mine;
-  __syncthreads();
-
-  constexpr int LPR = D / 4;                 // lanes per output row (16-byte pieces)
-  constexpr int RPI = 64 / LPR;              // rows per iteration of a wave
-  const int sub = lane / LPR, piece = lane % LPR;
-  for (int r0 = 0; r0 < 32; r0 += RPI) {
-    const int r = r0 + sub;
-    const int row_in_task = q_tile_row0 + wave * 32 + r;
-    if (row_in_task >= T.n_q) continue;
-    const int64_t grow = T.q_row0 + row_in_task;
-    float* od = p.o_dst + (grow * p.Hq + hq) * D + 4 * piece;
+  float lse_new = seen ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -__builtin_inff();
+  if (q_valid) {
+    const int64_t grow = T.q_row0 + my_q;
+    float* od = p.o_dst + (grow * p.Hq + hq) * D + 4 * h;
     float* ld = p.lse_dst + grow * p.Hq + hq;
-    f32x4 val = *reinterpret_cast<const f32x4*>(ostage + r * C::OROW + 4 * piece);
-    float lse_new = s_lse[wave][r];
+    float wa = 0.f, wb = inv;
     if (p.merge) {
       // update_out_lse of Algorithm 3 folded into the store
       const float lse_old = *ld;
-      const f32x4 old = *reinterpret_cast<const f32x4*>(od);
       const float mxl = fmaxf(lse_old, lse_new);
       if (mxl == -__builtin_inff()) {
-        val = f32x4{0.f, 0.f, 0.f, 0.f};
+        wb = 0.f;
       } else {
-        const float wa = __expf(lse_old - mxl), wb = __expf(lse_new - mxl);
-        const float den = wa + wb, rden = 1.f / den;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) val[e] = (wa * old[e] + wb * val[e]) * rden;
-        lse_new = mxl + __logf(den);
+        const float ea = __expf(lse_old - mxl), eb = __expf(lse_new - mxl);
+        const float rden = 1.f / (ea + eb);
+        wa = ea * rden;
+        wb = eb * rden * inv;
+        lse_new = mxl + __logf(ea + eb);
       }
     }
-    *reinterpret_cast<f32x4*>(od) = val;
-    if (piece == 0) *ld = lse_new;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        f32x4* dst = reinterpret_cast<f32x4*>(od + 32 * db + 8 * i4);
+        f32x4 val;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) val[e] = o[db][4 * i4 + e] * wb;
+        if (p.merge) {
+          const f32x4 old = *dst;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) val[e] = __builtin_fmaf(wa, old[e], val[e]);
+        }
+        *dst = val;
+      }
+    if (h == 0) *ld = lse_new;
   }
+}
+
+template <int D, int NWAVES>
+hipError_t launch_variant(const AttnLaunch& p, hipStream_t stream) {
+  constexpr int BM = Cfg<D, NWAVES>::BM;
+  int64_t tiles = 0;
+  for (int t = 0; t < p.n_tasks; ++t) tiles += (p.task[t].n_q + BM - 1) / BM;
+  const int64_t blocks = tiles * p.Hq;
+  if (blocks == 0) return hipSuccess;
+  if (blocks > INT_MAX) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((attn_bf16_kernel<D, NWAVES>), dim3(static_cast<unsigned>(blocks)), dim3(64 * NWAVES), 0,
+                     stream, p);
+  return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_attn_bf16(const AttnLaunch& p, int d, hipStream_t stream) {
-  int tiles = 0;
-  for (int t = 0; t < p.n_tasks; ++t) tiles += (p.task[t].n_q + BM - 1) / BM;
-  const int64_t blocks = static_cast<int64_t>(tiles) * p.Hq;
-  if (blocks == 0) return hipSuccess;
-  if (blocks > INT_MAX) return hipErrorInvalidValue;
-  dim3 grid(static_cast<unsigned>(blocks)), block(NTHREADS);
-  if (d == 128) hipLaunchKernelGGL(attn_bf16_kernel<128>, grid, block, 0, stream, p);
-  else if (d == 64) hipLaunchKernelGGL(attn_bf16_kernel<64>, grid, block, 0, stream, p);
-  else return hipErrorInvalidValue;
-  return hipGetLastError();
+  static const int waves = [] { const char* e = getenv("TASP_ATTN_WAVES"); return e ? atoi(e) : 8; }();
+  if (d == 128) return waves == 4 ? launch_variant<128, 4>(p, stream) : launch_variant<128, 8>(p, stream);
+  if (d == 64) return waves == 4 ? launch_variant<64, 4>(p, stream) : launch_variant<64, 8>(p, stream);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace tasp
