@@ -43,6 +43,9 @@ enum { TASP_ORDER_TASP = 0, TASP_ORDER_RING = 1 };
 
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* tasp_strerror(int status);
+/* After TASP_EHIP: the HIP runtime's text for the last HIP error the calling thread met inside this
+ * library ("no error" if none so far).  Static storage owned by the HIP runtime. */
+const char* tasp_last_hip_error(void);
 
 /* ------------------------------------------------------------------------------------------------
  * tasp_schedule(N, rank): ring decomposition, routing tables and arrival order.      [host only]

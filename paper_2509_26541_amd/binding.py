@@ -24,14 +24,15 @@ EXPORTS = [
     "tasp_schedule_rank", "tasp_schedule_n_rings", "tasp_schedule_max_arc_load", "tasp_schedule_rings",
     "tasp_schedule_out_mapping", "tasp_schedule_in_mapping", "tasp_schedule_arrival", "tasp_subchunk_ranges",
     "tasp_step_segments", "tasp_chunk_attn_workspace_bytes", "tasp_chunk_attn", "tasp_step_attn",
-    "tasp_lse_merge", "tasp_chunk_attn_flops", "tasp_chunk_attn_profile",
+    "tasp_lse_merge", "tasp_chunk_attn_flops", "tasp_chunk_attn_profile", "tasp_last_hip_error",
 ]
 
 
 class TaspError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
-        super().__init__("%s: %s (status %d)" % (where, strerror(status), status))
+        detail = " [HIP: %s]" % lib.tasp_last_hip_error().decode() if status == EHIP else ""
+        super().__init__("%s: %s (status %d)%s" % (where, strerror(status), status, detail))
 
 
 class AttnArgs(C.Structure):
@@ -52,10 +53,16 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError("libtasp.so is not built: run `python paper_2509_26541_amd/build.py` "
                           "(there is no CPU fallback)")
+    # PyTorch's ROCm wheel ships its own HIP runtime.  Importing torch first makes libtasp.so bind to
+    # that same runtime; loaded the other way round the process ends up with two runtimes and the
+    # library's launches fail with "no ROCm-capable device is detected".
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     p32 = C.POINTER(C.c_int32)
     lib.tasp_strerror.restype = C.c_char_p
     lib.tasp_strerror.argtypes = [C.c_int]
+    lib.tasp_last_hip_error.restype = C.c_char_p
+    lib.tasp_last_hip_error.argtypes = []
     lib.tasp_schedule_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
     lib.tasp_schedule_destroy.argtypes = [C.c_void_p]
     lib.tasp_schedule_destroy.restype = None
@@ -131,7 +138,7 @@ class Schedule:
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h:
+        if h and lib is not None:            # module globals may already be gone at interpreter exit
             lib.tasp_schedule_destroy(h)
 
 

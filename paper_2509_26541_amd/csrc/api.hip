@@ -118,7 +118,13 @@ hipError_t launch_attn(const AttnLaunch& lp, const tasp_attn_args* a, hipStream_
 
 }  // namespace
 
+namespace tasp {
+thread_local hipError_t g_last_hip_error = hipSuccess;
+}
+
 extern "C" {
+
+const char* tasp_last_hip_error(void) { return hipGetErrorString(tasp::g_last_hip_error); }
 
 size_t tasp_chunk_attn_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_args* a) {
   if (s == nullptr || a == nullptr || a->S <= 0 || a->Hq <= 0 || a->d <= 0 || s->n <= 0) return 0;
@@ -249,7 +255,7 @@ int tasp_chunk_attn_profile(const tasp_schedule_t* s, const tasp_attn_args* a, v
     Profiler prof;
     prof.stream = static_cast<hipStream_t>(hip_stream);
     const int st = run_chunk_attn(s, a, hip_stream, &prof);
-    if (hipStreamSynchronize(prof.stream) != hipSuccess) return TASP_EHIP;
+    if (tasp::note_hip(hipStreamSynchronize(prof.stream)) != hipSuccess) return TASP_EHIP;
     if (st != TASP_OK) return st;
     if (prof.failed) return TASP_EHIP;
     for (const auto& sp : prof.spans) {

@@ -48,12 +48,25 @@ struct Cfg {
   static constexpr int PASSES = BN / RPP;
   static constexpr int ROWS_PER_LINE = 16 / UNITS;    // rows per 256-byte bank line (1 or 2)
   static constexpr int TILE_BYTES = BN * D * 2;
-  static constexpr int SMEM = 4 * TILE_BYTES;         // K and V, double buffered
+  static constexpr int STAGES = 3;
+  static constexpr int SMEM = STAGES * 2 * TILE_BYTES;   // ring of (K tile, V tile)
   __device__ static int swz_k(int row, int unit) { return unit ^ ((row / ROWS_PER_LINE) % UNITS); }
   __device__ static int swz_v(int row, int unit) { return unit ^ (4 * ((row / ROWS_PER_LINE) % (UNITS / 4))); }
 };
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+#ifdef TASP_PHASE_TIMING
+// Development aid: cycles per phase of the main loop, summed over wave 0 of every workgroup.
+__device__ unsigned long long g_phase_cycles[8];
+#define PHASE_DECL unsigned long long ph_t0 = clock64(), ph_acc[6] = {0, 0, 0, 0, 0, 0};
+#define PHASE_MARK(i) { const unsigned long long ph_t1 = clock64(); ph_acc[i] += ph_t1 - ph_t0; ph_t0 = ph_t1; }
+#define PHASE_FLUSH if (tid == 0) { for (int i = 0; i < 6; ++i) atomicAdd(&g_phase_cycles[i], ph_acc[i]); atomicAdd(&g_phase_cycles[7], 1ull); }
+#else
+#define PHASE_DECL
+#define PHASE_MARK(i)
+#define PHASE_FLUSH
+#endif
 
 template <int D, int NWAVES>
 __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLaunch p) {
@@ -62,9 +75,9 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   constexpr int KS = D / 16;     // contraction steps of K Q^T
   constexpr int DB = D / 32;     // 32-row blocks of O^T
 
-  __shared__ __attribute__((aligned(16))) unsigned char smem[C::SMEM];
-  __shared__ __attribute__((aligned(16))) int s_tok[2][BN];           // global position of every key row of a tile (INT_MAX: none)
-  __shared__ int s_flag[2][BN];          // 1: the row needs the element-wise mask
+  __shared__ __attribute__((aligned(16))) unsigned char smem[C::SMEM];   // ring of stages, each a K tile then a V tile
+  __shared__ __attribute__((aligned(16))) int s_tok[C::STAGES][BN];   // global position of every key row of a tile (INT_MAX: none)
+  __shared__ int s_flag[C::STAGES][BN];          // 1: the row needs the element-wise mask
   __shared__ int e_vbeg[2 * kMaxSeg + 1];  // effective segments: start in the virtual concatenation
   __shared__ int e_goff[2 * kMaxSeg];      //   global position minus virtual position
   __shared__ int e_diag[2 * kMaxSeg];      //   straddles the diagonal of this query tile
@@ -125,15 +138,12 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   const int n_tiles = (total_keys + BN - 1) / BN;
 
   // ---- Q fragments (B operand of K Q^T): lane holds query lq, d = 16 ks + 8 h .. +8
-  const __bf16* Qg = static_cast<const __bf16*>(p.q);
-  const __bf16* Kg = static_cast<const __bf16*>(p.k);
-  const __bf16* Vg = static_cast<const __bf16*>(p.v);
   const int my_q = q_tile_row0 + wave * 32 + lq;              // row inside the task
   const bool q_valid = my_q < T.n_q;
   const int64_t q_row = T.q_row0 + (q_valid ? my_q : T.n_q - 1);
   bf16x8 qf[KS];
   {
-    const __bf16* src = Qg + (q_row * p.Hq + hq) * D + 8 * h;
+    const __bf16* src = static_cast<const __bf16*>(p.q) + (q_row * p.Hq + hq) * D + 8 * h;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
   }
@@ -142,18 +152,21 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   __builtin_amdgcn_s_waitcnt(0x0F70);
   const int q_pos = p.causal ? T.q_pos0 + my_q : INT_MAX - 1;
 
-  // ---- loader state: this thread fills rows fr + RPP*i, unit fu of every K and V tile
-  const int fr = tid / C::UNITS, fu = tid % C::UNITS;   // RPP = NTHREADS / UNITS rows per pass
-  const int64_t kv_head_off = static_cast<int64_t>(g) * D + fu * 8;
-  const int64_t kv_row_stride = static_cast<int64_t>(p.Hkv) * D;
+  // ---- loader: this thread fills rows fr + RPP*i, unit fu of every K and V tile.  Byte offsets
+  // into K and V fit 32 bits (checked on the host).
+  const int fr = tid / C::UNITS, fu = tid % C::UNITS;
+  const unsigned char* Kb = static_cast<const unsigned char*>(p.k) + (static_cast<size_t>(g) * D + fu * 8) * 2;
+  const unsigned char* Vb = static_cast<const unsigned char*>(p.v) + (static_cast<size_t>(g) * D + fu * 8) * 2;
+  const unsigned row_bytes = static_cast<unsigned>(p.Hkv) * D * 2;
   int cur = 0;                                                // effective segment of the tile's first row
   int cur_vend = n_eff > 0 ? e_vbeg[1] : 0;
   int cur_goff = n_eff > 0 ? e_goff[0] : 0;
   int cur_diag = n_eff > 0 ? e_diag[0] : 0;
-  u32x4 kreg[C::PASSES], vreg[C::PASSES];
-  int tokreg[C::PASSES], flagreg[C::PASSES];
+  u32x4 kreg[C::PASSES], vreg[C::PASSES];                     // the tile in flight between HBM/L2 and LDS
+  int tokk[C::PASSES], flagk[C::PASSES];
 
-  auto issue_loads = [&](int t) __attribute__((always_inline)) {
+  // tokens of tile t (tiles must be asked for in ascending order)
+  auto locate = [&](int t) __attribute__((always_inline)) {
     const int v0 = t * BN;
     while (cur < n_eff && v0 >= cur_vend) {                   // move to the segment holding row v0
       ++cur;
@@ -161,40 +174,54 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
     }
     if (cur < n_eff && v0 + BN <= cur_vend) {                 // the whole tile lies in one segment
 #pragma unroll
-      for (int i = 0; i < C::PASSES; ++i) { tokreg[i] = v0 + fr + C::RPP * i + cur_goff; flagreg[i] = cur_diag; }
+      for (int i = 0; i < C::PASSES; ++i) { tokk[i] = v0 + fr + C::RPP * i + cur_goff; flagk[i] = cur_diag; }
     } else {
       int j = cur, vend = cur_vend, goff = cur_goff, dg = cur_diag;
-      auto locate = [&](int v, int& tok, int& flag) __attribute__((always_inline)) {
+      auto one = [&](int v, int& tok, int& flag) __attribute__((always_inline)) {
         while (j < n_eff && v >= vend) {                      // rows ascend, so j only moves forward
           ++j;
           if (j < n_eff) { vend = e_vbeg[j + 1]; goff = e_goff[j]; dg = e_diag[j]; }
         }
-        tok = j < n_eff ? v + goff : INT_MAX;
+        tok = j < n_eff ? v + goff : INT_MAX;                 // past the last key: no row
         flag = j < n_eff ? dg : 1;
       };
-      locate(v0 + fr, tokreg[0], flagreg[0]);
-      if constexpr (C::PASSES > 1) locate(v0 + fr + C::RPP, tokreg[1], flagreg[1]);
-      if constexpr (C::PASSES > 2) locate(v0 + fr + 2 * C::RPP, tokreg[2], flagreg[2]);
-      if constexpr (C::PASSES > 3) locate(v0 + fr + 3 * C::RPP, tokreg[3], flagreg[3]);
+      one(v0 + fr, tokk[0], flagk[0]);
+      if constexpr (C::PASSES > 1) one(v0 + fr + C::RPP, tokk[1], flagk[1]);
+      if constexpr (C::PASSES > 2) one(v0 + fr + 2 * C::RPP, tokk[2], flagk[2]);
+      if constexpr (C::PASSES > 3) one(v0 + fr + 3 * C::RPP, tokk[3], flagk[3]);
       static_assert(C::PASSES <= 4, "loader handles at most 4 passes");
     }
+  };
+  // start fetching tile t into registers; tiles past the end fetch token 0 and are never used
+  auto fetch = [&](int t) __attribute__((always_inline)) {
+#ifdef ABL_NO_LOAD
+    return;
+#endif
+#ifdef TASP_EXP_SIMPLELOC
+    for (int i = 0; i < C::PASSES; ++i) { tokk[i] = (t * BN + fr + C::RPP * i) & 0xFFFF; flagk[i] = 0; }
+#else
+    locate(t);
+#endif
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
-      const int64_t row = (tokreg[i] == INT_MAX) ? 0 : tokreg[i];   // rows past the end read token 0, masked later
-      const int64_t off = row * kv_row_stride + kv_head_off;
-      kreg[i] = *reinterpret_cast<const u32x4*>(Kg + off);
-      vreg[i] = *reinterpret_cast<const u32x4*>(Vg + off);
+      const unsigned off = (tokk[i] == INT_MAX ? 0u : static_cast<unsigned>(tokk[i])) * row_bytes;
+      kreg[i] = *reinterpret_cast<const u32x4*>(Kb + off);
+      vreg[i] = *reinterpret_cast<const u32x4*>(Vb + off);
     }
   };
-  auto store_tile = [&](int buf) __attribute__((always_inline)) {
-    unsigned char* kbase = smem + buf * 2 * C::TILE_BYTES;
+  // put the fetched tile into ring stage `stage`
+  auto commit = [&](int stage) __attribute__((always_inline)) {
+#ifdef ABL_NO_LOAD
+    return;
+#endif
+    unsigned char* kbase = smem + stage * 2 * C::TILE_BYTES;
     unsigned char* vbase = kbase + C::TILE_BYTES;
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
       const int row = fr + C::RPP * i;
       *reinterpret_cast<u32x4*>(kbase + (row * C::UNITS + C::swz_k(row, fu)) * 16) = kreg[i];
       *reinterpret_cast<u32x4*>(vbase + (row * C::UNITS + C::swz_v(row, fu)) * 16) = vreg[i];
-      if (fu == 0) { s_tok[buf][row] = tokreg[i]; s_flag[buf][row] = flagreg[i]; }
+      if (fu == 0) { s_tok[stage][row] = tokk[i]; s_flag[stage][row] = flagk[i]; }
     }
   };
 
@@ -213,6 +240,26 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
     voff[db] = (vrow * C::UNITS + C::swz_v(vrow, unit)) * 16 + 8 * (jj & 1);
   }
 
+  // S^T = K Q^T for the K tile in `kslot`: two 32-key blocks, the two accumulation chains interleaved
+  auto scores = [&](int stage, f32x16 (&s)[2]) __attribute__((always_inline)) {
+#ifdef ABL_NO_QK
+    for (int kb = 0; kb < 2; ++kb) for (int i = 0; i < 16; ++i) s[kb][i] = 0.01f * (i + lane + stage);
+    return;
+#endif
+    const unsigned char* kbase = smem + stage * 2 * C::TILE_BYTES;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * D * 2 + koff[ks]);
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
+      }
+  };
+
   // ---- running state
   f32x16 o[DB];
 #pragma unroll
@@ -223,46 +270,28 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   float l_run = 0.f;            // this lane's share of the running sum
   const float c = p.scale * kLog2e;
 
-  if (n_tiles > 0) {
-    issue_loads(0);
-    store_tile(0);
-  }
-  __syncthreads();
-
-  for (int t = 0; t < n_tiles; ++t) {
-    const int buf = t & 1;
-    if (t + 1 < n_tiles) issue_loads(t + 1);
-
-    const unsigned char* kbase = smem + buf * 2 * C::TILE_BYTES;
-    const unsigned char* vbase = kbase + C::TILE_BYTES;
-
-    // S^T = K Q^T : two 32-key blocks
-    f32x16 s[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * D * 2 + koff[ks]);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
-      }
-    }
-
-    // element-wise mask, only for tiles that touch the diagonal or run past the last key
-    if (__builtin_amdgcn_ballot_w64(s_flag[buf][lane] != 0) != 0) {
+  // ---- the three phases of a tile, for one wave
+  // element-wise mask, only for tiles that touch the diagonal or run past the last key
+  auto mask = [&](int stage, f32x16 (&s)[2]) __attribute__((always_inline)) {
+    if (__builtin_amdgcn_ballot_w64(s_flag[stage][lane] != 0) != 0) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          const i32x4 tk = *reinterpret_cast<const i32x4*>(&s_tok[buf][32 * kb + 8 * i4 + 4 * h]);
+          const i32x4 tk = *reinterpret_cast<const i32x4*>(&s_tok[stage][32 * kb + 8 * i4 + 4 * h]);
 #pragma unroll
           for (int e = 0; e < 4; ++e)
             if (tk[e] > q_pos) s[kb][4 * i4 + e] = -__builtin_inff();
         }
     }
-
-    // online softmax (exp2 domain)
+  };
+  // online softmax (exp2 domain): raises the running max lazily, returns P as bf16 B-operand fragments
+  auto softmax = [&](f32x16 (&s)[2], bf16x8 (&pf)[2][2]) __attribute__((always_inline)) {
+#ifdef ABL_NO_SOFTMAX
+    for (int kb = 0; kb < 2; ++kb) for (int j = 0; j < 2; ++j) for (int e = 0; e < 8; ++e) pf[kb][j][e] = static_cast<__bf16>(s[kb][8 * j + e]);
+    l_run += s[0][0];
+    return;
+#endif
     float mx = s[0][0];
 #pragma unroll
     for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[0][i]);
@@ -279,7 +308,6 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
     }
-    bf16x8 pf[2][2];
     float lsum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -290,8 +318,14 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
         pf[kb][i >> 3][i & 7] = static_cast<__bf16>(pv);
       }
     l_run += lsum;
-
-    // O^T += V^T P^T : per 16-key block, DB blocks of 32 output rows
+  };
+  // O^T += V^T P^T : per 16-key block, DB blocks of 32 output rows
+  auto accumulate = [&](int stage, const bf16x8 (&pf)[2][2]) __attribute__((always_inline)) {
+#ifdef ABL_NO_PV
+    for (int kb = 0; kb < 2; ++kb) for (int j = 0; j < 2; ++j) o[kb * 2 + j][0] += static_cast<float>(pf[kb][j][0]) + static_cast<float>(pf[kb][j][7]);
+    return;
+#endif
+    const unsigned char* vbase = smem + (stage * 2 + 1) * C::TILE_BYTES;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -305,11 +339,61 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kb][j], o[db], 0, 0, 0);
         }
       }
+  };
 
-    if (t + 1 < n_tiles) store_tile(buf ^ 1);
-    __syncthreads();
+  // ---- main loop over 64-key tiles.  Ring of three LDS stages: at the barrier that opens iteration
+  // t, tiles t and t+1 are complete; during the iteration every thread commits its share of tile
+  // t+2 (fetched one iteration earlier) into the stage tile t-1 has left, and starts fetching t+3.
+  //
+  // The two wavefronts that share a SIMD run the same phases half an iteration apart: the first
+  // (waves 0..NWAVES/2-1) goes  scores(t) -> softmax -> accumulate(t),  the second
+  // softmax -> accumulate(t) -> scores(t+1).  After each barrier one of them is in a matrix phase
+  // while the other is in its vector phase, so the matrix and vector pipes overlap instead of
+  // taking turns.
+  if (n_tiles > 0) {
+    fetch(0);
+    commit(0);
+    fetch(1);
+    commit(1);
+    fetch(2);
+  }
+  __syncthreads();
+
+  int stage = 0;                 // ring stage of tile t
+  PHASE_DECL
+  if (__builtin_amdgcn_readfirstlane(wave) < NWAVES / 2) {
+    for (int t = 0; t < n_tiles; ++t) {
+      const int stage2 = stage == 0 ? 2 : stage - 1;            // (t + 2) mod 3
+      commit(stage2);
+      fetch(t + 3);
+      f32x16 s[2];
+      bf16x8 pf[2][2];
+      scores(stage, s);
+      mask(stage, s);
+      softmax(s, pf);
+      accumulate(stage, pf);
+      __syncthreads();
+      stage = stage == 2 ? 0 : stage + 1;
+    }
+  } else {
+    f32x16 s[2];
+    if (n_tiles > 0) scores(0, s);
+    for (int t = 0; t < n_tiles; ++t) {
+      const int stage1 = stage == 2 ? 0 : stage + 1;
+      const int stage2 = stage == 0 ? 2 : stage - 1;
+      commit(stage2);
+      fetch(t + 3);
+      bf16x8 pf[2][2];
+      mask(stage, s);
+      softmax(s, pf);
+      accumulate(stage, pf);
+      scores(stage1, s);         // tile t+1; past the last tile this reads a committed dummy tile and is dropped
+      __syncthreads();
+      stage = stage1;
+    }
   }
 
+  PHASE_FLUSH
   // ---- epilogue: normalise and store.  A lane owns one query row; per (db, i4) it holds 4
   // consecutive output columns, and its partner lane (+32) the next 4, so a wavefront writes
   // 32-byte pieces of 32 rows per store and the 16 stores of a lane complete its 512-byte row.
@@ -363,12 +447,18 @@ hipError_t launch_variant(const AttnLaunch& p, hipStream_t stream) {
   const int64_t blocks = tiles * p.Hq;
   if (blocks == 0) return hipSuccess;
   if (blocks > INT_MAX) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((attn_bf16_kernel<D, NWAVES>), dim3(static_cast<unsigned>(blocks)), dim3(64 * NWAVES), 0,
-                     stream, p);
-  return hipGetLastError();
+  return TASP_LAUNCH((attn_bf16_kernel<D, NWAVES>), dim3(static_cast<unsigned>(blocks)), dim3(64 * NWAVES), stream, p);
 }
 
 }  // namespace
+
+#ifdef TASP_PHASE_TIMING
+extern "C" int tasp_debug_phase_cycles(unsigned long long out[8], int reset) {
+  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_cycles), 64) != hipSuccess) return -1;
+  if (reset) { unsigned long long z[8] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), z, 64) != hipSuccess) return -1; }
+  return 0;
+}
+#endif
 
 hipError_t launch_attn_bf16(const AttnLaunch& p, int d, hipStream_t stream) {
   static const int waves = [] { const char* e = getenv("TASP_ATTN_WAVES"); return e ? atoi(e) : 8; }();

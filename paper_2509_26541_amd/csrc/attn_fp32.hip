@@ -127,10 +127,9 @@ hipError_t launch_attn_fp32(const AttnLaunch& p, int d, hipStream_t stream) {
   const int64_t blocks = (items + WAVES - 1) / WAVES;
   if (blocks > 0x7fffffff) return hipErrorInvalidValue;
   dim3 grid(static_cast<unsigned>(blocks)), block(WAVES * 64);
-  if (d == 64) hipLaunchKernelGGL(attn_fp32_kernel<64>, grid, block, 0, stream, p);
-  else if (d == 128) hipLaunchKernelGGL(attn_fp32_kernel<128>, grid, block, 0, stream, p);
-  else return hipErrorInvalidValue;
-  return hipGetLastError();
+  if (d == 64) return TASP_LAUNCH(attn_fp32_kernel<64>, grid, block, stream, p);
+  if (d == 128) return TASP_LAUNCH(attn_fp32_kernel<128>, grid, block, stream, p);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace tasp

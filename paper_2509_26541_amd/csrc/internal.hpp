@@ -34,6 +34,22 @@ struct AttnLaunch {
   AttnTask task[kMaxTasks];
 };
 
+// Last HIP error this thread saw inside the library (hipSuccess if none); see tasp_last_hip_error().
+extern thread_local hipError_t g_last_hip_error;
+inline hipError_t note_hip(hipError_t e) {
+  if (e != hipSuccess) g_last_hip_error = e;
+  return e;
+}
+
+// Launch with a clean error slot: an error left behind by an earlier, unrelated HIP call in this
+// thread must not be mistaken for a failure of this launch.
+#define TASP_LAUNCH(kernel, grid, block, stream, ...)                         \
+  ({                                                                          \
+    (void)hipGetLastError();                                                  \
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);          \
+    ::tasp::note_hip(hipGetLastError());                                      \
+  })
+
 // Implemented in attn_bf16.hip / attn_fp32.hip / merge.hip.  Each returns a hipError_t from the launch.
 hipError_t launch_attn_bf16(const AttnLaunch& p, int d, hipStream_t stream);
 hipError_t launch_attn_fp32(const AttnLaunch& p, int d, hipStream_t stream);

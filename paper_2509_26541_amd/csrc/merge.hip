@@ -80,9 +80,8 @@ hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const
   if (rows <= 0) return hipSuccess;
   const int64_t off = row0 * heads;
   const int64_t n4 = rows * heads * (d / 4);
-  hipLaunchKernelGGL(merge_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), 0, stream, o_acc + off * d,
-                     lse_acc + off, o_part + off * d, lse_part + off, n4, d / 4);
-  return hipGetLastError();
+  return TASP_LAUNCH(merge_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), stream, o_acc + off * d, lse_acc + off,
+                     o_part + off * d, lse_part + off, n4, d / 4);
 }
 
 hipError_t launch_fill_empty(float* o, float* lse, int64_t row0, int64_t rows, int32_t heads, int32_t d,
@@ -90,17 +89,15 @@ hipError_t launch_fill_empty(float* o, float* lse, int64_t row0, int64_t rows, i
   if (rows <= 0) return hipSuccess;
   const int64_t off = row0 * heads;
   const int64_t n4 = rows * heads * (d / 4);
-  hipLaunchKernelGGL(fill_empty_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), 0, stream, o + off * d,
-                     lse + off, n4, d / 4);
-  return hipGetLastError();
+  return TASP_LAUNCH(fill_empty_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), stream, o + off * d, lse + off,
+                     n4, d / 4);
 }
 
 hipError_t launch_cast_bf16(const float* src, void* dst, int64_t n, hipStream_t stream) {
   if (n <= 0) return hipSuccess;
   const int64_t n4 = n / 4;
-  hipLaunchKernelGGL(cast_bf16_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), 0, stream, src,
+  return TASP_LAUNCH(cast_bf16_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), stream, src,
                      static_cast<__bf16*>(dst), n4);
-  return hipGetLastError();
 }
 
 }  // namespace tasp
