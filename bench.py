@@ -21,7 +21,7 @@ PEAK_FP32_TFLOPS = 157.3        # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0
 
 
-def cpu_baseline(w, q, k, v, budget_s=15.0):
+def cpu_baseline(w, q, k, v, budget_s=18.0):
     """The oracle, as it stands, on a bounded sample of the same workload: dense fp64 attention of
     sampled local rows for all heads of one KV group, sized by a short calibration to ~budget_s."""
     import numpy as np
@@ -44,10 +44,15 @@ def cpu_baseline(w, q, k, v, budget_s=15.0):
         pairs = float(np.sum(pos[rows] + 1)) if causal else float(len(rows)) * w.S
         return dt, 4.0 * w.d * len(heads) * pairs
 
-    all_rows = wl.sample_rows(w, 4096)
-    probe = all_rows[:: max(1, len(all_rows) // 8)][:8]
-    dt, _ = run(probe)
-    n = int(max(8, min(len(all_rows), budget_s / max(dt / len(probe), 1e-6))))
+    all_rows = wl.sample_rows(w, 16384)
+    # two probes separate the fixed cost (casting one KV head to fp64) from the cost per row
+    p8 = all_rows[:: max(1, len(all_rows) // 8)][:8]
+    p64 = all_rows[:: max(1, len(all_rows) // 64)][:64]
+    t8, _ = run(p8)
+    t64, _ = run(p64)
+    per_row = max((t64 - t8) / max(len(p64) - len(p8), 1), 1e-6)
+    fixed = max(t8 - per_row * len(p8), 0.0)
+    n = int(max(8, min(len(all_rows), (budget_s - fixed) / per_row)))
     rows = all_rows[:: max(1, len(all_rows) // n)][:n]
     dt, flops = run(rows)
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
@@ -67,6 +72,8 @@ def main():
     ap.add_argument("--fuse-merge", type=int, default=0)
     ap.add_argument("--order", choices=["tasp", "ring"], default="tasp")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 256 MiB copy with the library's copy kernel (scales profiler traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one rank's share on ONE GPU; --gpus N > 1 is not part of this build "
@@ -87,6 +94,13 @@ def main():
     order = tb.ORDER_TASP if args.order == "tasp" else tb.ORDER_RING
     plan = tb.ChunkAttnPlan(sched, qd, kd, vd, w.mask_mode, order=order, fuse_merge=bool(args.fuse_merge))
     flops = plan.flops()
+
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        tb.tasp_calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         plan.run()
@@ -113,9 +127,16 @@ def main():
     attn_avg_ms = attn_ms / max(attn_n, 1)
     flops_per_launch = flops / w.n_ranks                     # a launch = one step of Algorithm 3
     achieved = flops_per_launch / (attn_avg_ms * 1e-3) / 1e12
+    # HBM bytes per attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
+    # the copy-kernel calibration); the figures live in profiles/traffic.json next to their summaries
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get(w.name, {}).get("attn_bytes_per_launch")
     roofline = {
         "bound": "mfma" if is_bf16 else "alu", "kernel": "attn_bf16_kernel" if is_bf16 else "attn_fp32_kernel",
-        "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+        "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
         "avg_launch_ms": attn_avg_ms, "launches_per_call": attn_n // n_prof,
     }
     merge = None
@@ -132,6 +153,18 @@ def main():
         merge = {"bound": "hbm", "kernel": "merge_kernel", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                  "frac": gbs / PEAK_HBM_GBS, "ms_per_call": merge_ms / n_prof, "launches_per_call": merge_n // n_prof}
 
+    # the same call with update_out_lse folded into the attention epilogue (no partial buffers)
+    alt = tb.ChunkAttnPlan(sched, qd, kd, vd, w.mask_mode, order=order, fuse_merge=not bool(args.fuse_merge))
+    for _ in range(max(1, args.warmup)):
+        alt.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        alt.run()
+    torch.cuda.synchronize()
+    alt_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    del alt
+
     value = flops / (ms_per_step * 1e-3) / 1e12
     line = {
         "metric": "per-rank chunked-attention TFLOP/s on 1 MI355X", "value": value, "unit": "TFLOP/s",
@@ -145,6 +178,8 @@ def main():
         "roofline": roofline,
         "merge": merge,
         "ms_breakdown": {"attn": attn_ms / n_prof, "merge": merge_ms / n_prof, "cast": other_ms / n_prof},
+        "other_merge_mode": {"fuse_merge": int(not bool(args.fuse_merge)), "ms_per_step": alt_ms,
+                             "value": flops / (alt_ms * 1e-3) / 1e12},
     }
     if not args.no_cpu_baseline:
         del plan, qd, kd, vd

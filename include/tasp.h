@@ -170,6 +170,11 @@ int tasp_step_attn(const tasp_schedule_t* s, const tasp_attn_args* a, int32_t st
 int tasp_lse_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
                    int64_t rows, int32_t heads, int32_t d, void* hip_stream);
 
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned) by
+ * a streaming kernel of this library.  Not part of the method: it gives profilers a transfer of
+ * known size with which to scale their HBM traffic counters. */
+int tasp_calibration_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
 /* Algorithmic work of one tasp_chunk_attn call: 4*d*Hq*(visible (query,key) pairs). */
 double tasp_chunk_attn_flops(const tasp_schedule_t* s, const tasp_attn_args* a);
 

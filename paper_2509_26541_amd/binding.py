@@ -24,7 +24,7 @@ EXPORTS = [
     "tasp_schedule_rank", "tasp_schedule_n_rings", "tasp_schedule_max_arc_load", "tasp_schedule_rings",
     "tasp_schedule_out_mapping", "tasp_schedule_in_mapping", "tasp_schedule_arrival", "tasp_subchunk_ranges",
     "tasp_step_segments", "tasp_chunk_attn_workspace_bytes", "tasp_chunk_attn", "tasp_step_attn",
-    "tasp_lse_merge", "tasp_chunk_attn_flops", "tasp_chunk_attn_profile", "tasp_last_hip_error",
+    "tasp_lse_merge", "tasp_chunk_attn_flops", "tasp_chunk_attn_profile", "tasp_last_hip_error", "tasp_calibration_copy",
 ]
 
 
@@ -85,6 +85,7 @@ def _load():
     lib.tasp_step_attn.argtypes = [C.c_void_p, C.POINTER(AttnArgs), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.tasp_lse_merge.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                    C.c_int32, C.c_void_p]
+    lib.tasp_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.tasp_chunk_attn_flops.argtypes = [C.c_void_p, C.POINTER(AttnArgs)]
     lib.tasp_chunk_attn_flops.restype = C.c_double
     return lib
@@ -220,6 +221,17 @@ def tasp_step_attn(q, k, v, schedule, mask_mode, step, order=ORDER_TASP, softmax
     _check(lib.tasp_step_attn(schedule.handle, C.byref(a), step, o.data_ptr(), lse.data_ptr(), C.c_void_p(s)),
            "tasp_step_attn")
     return o, lse
+
+
+def tasp_calibration_copy(dst, src):
+    """Streams src into dst (same-size contiguous device tensors) with the library's copy kernel."""
+    torch = _torch()
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (src.is_cuda and dst.is_cuda):
+        raise ValueError("device tensors of equal byte size expected")
+    s = torch.cuda.current_stream().cuda_stream
+    _check(lib.tasp_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, C.c_void_p(s)), "tasp_calibration_copy")
+    return dst
 
 
 def tasp_lse_merge(o_acc, lse_acc, o_part, lse_part):

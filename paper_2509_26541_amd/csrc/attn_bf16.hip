@@ -16,7 +16,6 @@
 #include <hip/hip_runtime.h>
 
 #include <climits>
-#include <cstdlib>
 
 #include "internal.hpp"
 
@@ -461,9 +460,8 @@ extern "C" int tasp_debug_phase_cycles(unsigned long long out[8], int reset) {
 #endif
 
 hipError_t launch_attn_bf16(const AttnLaunch& p, int d, hipStream_t stream) {
-  static const int waves = [] { const char* e = getenv("TASP_ATTN_WAVES"); return e ? atoi(e) : 8; }();
-  if (d == 128) return waves == 4 ? launch_variant<128, 4>(p, stream) : launch_variant<128, 8>(p, stream);
-  if (d == 64) return waves == 4 ? launch_variant<64, 4>(p, stream) : launch_variant<64, 8>(p, stream);
+  if (d == 128) return launch_variant<128, 8>(p, stream);
+  if (d == 64) return launch_variant<64, 8>(p, stream);
   return hipErrorInvalidValue;
 }
 

@@ -7,7 +7,7 @@
 #include "tasp.h"
 
 namespace tasp {
-namespace {
+inline namespace merge_detail {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -67,13 +67,21 @@ __global__ __launch_bounds__(MERGE_THREADS) void cast_bf16_kernel(const float* _
   }
 }
 
+// Plain 16-byte copy, used to calibrate the HBM traffic counters against a transfer of known size.
+__global__ __launch_bounds__(MERGE_THREADS) void copy_kernel(const f32x4* __restrict__ src, f32x4* __restrict__ dst,
+                                                            int64_t n4) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * MERGE_THREADS;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * MERGE_THREADS + threadIdx.x; i < n4; i += stride)
+    dst[i] = __builtin_nontemporal_load(src + i);
+}
+
 unsigned grid_for(int64_t n_items) {
   const int64_t want = (n_items + MERGE_THREADS - 1) / MERGE_THREADS;
   const int64_t cap = 256 * 32;                     // 32 resident workgroups' worth per CU is plenty
   return static_cast<unsigned>(want < 1 ? 1 : (want > cap ? cap : want));
 }
 
-}  // namespace
+}  // namespace merge_detail
 
 hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
                         int64_t row0, int64_t rows, int32_t heads, int32_t d, hipStream_t stream) {
@@ -101,6 +109,17 @@ hipError_t launch_cast_bf16(const float* src, void* dst, int64_t n, hipStream_t 
 }
 
 }  // namespace tasp
+
+extern "C" int tasp_calibration_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  if (bytes == 0) return TASP_OK;
+  if (dst == nullptr || src == nullptr || bytes % 16 != 0) return TASP_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15) return TASP_EALIGN;
+  const int64_t n4 = static_cast<int64_t>(bytes / 16);
+  const hipError_t e = TASP_LAUNCH(tasp::copy_kernel, dim3(tasp::grid_for(n4)), dim3(tasp::MERGE_THREADS),
+                                   static_cast<hipStream_t>(hip_stream), static_cast<const tasp::f32x4*>(src),
+                                   static_cast<tasp::f32x4*>(dst), n4);
+  return e == hipSuccess ? TASP_OK : TASP_EHIP;
+}
 
 extern "C" int tasp_lse_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
                               int64_t rows, int32_t heads, int32_t d, void* hip_stream) {
