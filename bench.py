@@ -21,7 +21,7 @@ PEAK_FP32_TFLOPS = 157.3        # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0
 
 
-def cpu_baseline(w, q, k, v, budget_s=18.0):
+def cpu_baseline(w, q, k, v, budget_s=12.0):
     """The oracle, as it stands, on a bounded sample of the same workload: dense fp64 attention of
     sampled local rows for all heads of one KV group, sized by a short calibration to ~budget_s."""
     import numpy as np
