@@ -380,12 +380,12 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
     for (int t = 0; t < n_tiles; ++t) {
       const int stage1 = stage == 2 ? 0 : stage + 1;
       const int stage2 = stage == 0 ? 2 : stage - 1;
-      commit(stage2);
-      fetch(t + 3);
       bf16x8 pf[2][2];
       mask(stage, s);
       softmax(s, pf);
       accumulate(stage, pf);
+      commit(stage2);            // the loader work of this wave falls into the other wave's matrix phase
+      fetch(t + 3);
       scores(stage1, s);         // tile t+1; past the last tile this reads a committed dummy tile and is dropped
       __syncthreads();
       stage = stage1;
