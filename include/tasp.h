@@ -121,7 +121,8 @@ int tasp_step_segments(const tasp_schedule_t* s, int64_t S, int32_t mask_mode, i
  *                 (update_out_lse of Algorithm 3);  1: the attention kernel folds it in itself.
  *   workspace device, >= tasp_chunk_attn_workspace_bytes() bytes, 256-byte aligned, caller-owned,
  *             contents undefined on entry and exit.
- * Supported: d in {64, 128}; S < 2^31; for bf16, N <= 32.  All device pointers 16-byte aligned.
+ * Supported: d in {64, 128}; N <= 32; S < 2^31; for bf16 also S < 2^24 and S*Hkv*d*2 <= 2^32 bytes
+ * (K and V are addressed with 32-bit offsets).  All device pointers 16-byte aligned.
  * The call only enqueues work on `hip_stream` (a hipStream_t, NULL = default stream); results are
  * valid once the stream has been synchronised.
  * ---------------------------------------------------------------------------------------------- */

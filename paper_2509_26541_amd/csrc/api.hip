@@ -35,6 +35,12 @@ int validate(const tasp_schedule_t* s, const tasp_attn_args* a, Shape* sh) {
   if (a->dtype != TASP_DTYPE_FP32 && a->dtype != TASP_DTYPE_BF16) return TASP_EUNSUPPORTED_SHAPE;
   if (a->d != 64 && a->d != 128) return TASP_EUNSUPPORTED_SHAPE;
   if (a->S >= (int64_t{1} << 31) - 4096) return TASP_EUNSUPPORTED_SHAPE;
+  if (a->dtype == TASP_DTYPE_BF16) {
+    // the bf16 kernel addresses K and V with 32-bit byte offsets formed by a 24-bit multiply
+    const int64_t row_bytes = static_cast<int64_t>(a->Hkv) * a->d * 2;
+    if (a->S >= (1 << 24) || row_bytes >= (1 << 24) || a->S * row_bytes > (int64_t{1} << 32))
+      return TASP_EUNSUPPORTED_SHAPE;
+  }
   if (2 * (s->n - 1) > tasp::kMaxSeg) return TASP_EUNSUPPORTED_SHAPE;
   if ((reinterpret_cast<uintptr_t>(a->q) | reinterpret_cast<uintptr_t>(a->k) | reinterpret_cast<uintptr_t>(a->v)) & 15)
     return TASP_EALIGN;

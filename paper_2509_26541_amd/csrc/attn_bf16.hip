@@ -55,18 +55,6 @@ struct Cfg {
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-#ifdef TASP_PHASE_TIMING
-// Development aid: cycles per phase of the main loop, summed over wave 0 of every workgroup.
-__device__ unsigned long long g_phase_cycles[8];
-#define PHASE_DECL unsigned long long ph_t0 = clock64(), ph_acc[6] = {0, 0, 0, 0, 0, 0};
-#define PHASE_MARK(i) { const unsigned long long ph_t1 = clock64(); ph_acc[i] += ph_t1 - ph_t0; ph_t0 = ph_t1; }
-#define PHASE_FLUSH if (tid == 0) { for (int i = 0; i < 6; ++i) atomicAdd(&g_phase_cycles[i], ph_acc[i]); atomicAdd(&g_phase_cycles[7], 1ull); }
-#else
-#define PHASE_DECL
-#define PHASE_MARK(i)
-#define PHASE_FLUSH
-#endif
-
 template <int D, int NWAVES>
 __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLaunch p) {
   using C = Cfg<D, NWAVES>;
@@ -193,26 +181,16 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   };
   // start fetching tile t into registers; tiles past the end fetch token 0 and are never used
   auto fetch = [&](int t) __attribute__((always_inline)) {
-#ifdef ABL_NO_LOAD
-    return;
-#endif
-#ifdef TASP_EXP_SIMPLELOC
-    for (int i = 0; i < C::PASSES; ++i) { tokk[i] = (t * BN + fr + C::RPP * i) & 0xFFFF; flagk[i] = 0; }
-#else
     locate(t);
-#endif
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
-      const unsigned off = (tokk[i] == INT_MAX ? 0u : static_cast<unsigned>(tokk[i])) * row_bytes;
+      const unsigned off = __umul24(tokk[i] == INT_MAX ? 0u : static_cast<unsigned>(tokk[i]), row_bytes);   // both below 2^24 (host check)
       kreg[i] = *reinterpret_cast<const u32x4*>(Kb + off);
       vreg[i] = *reinterpret_cast<const u32x4*>(Vb + off);
     }
   };
   // put the fetched tile into ring stage `stage`
   auto commit = [&](int stage) __attribute__((always_inline)) {
-#ifdef ABL_NO_LOAD
-    return;
-#endif
     unsigned char* kbase = smem + stage * 2 * C::TILE_BYTES;
     unsigned char* vbase = kbase + C::TILE_BYTES;
 #pragma unroll
@@ -241,10 +219,6 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
 
   // S^T = K Q^T for the K tile in `kslot`: two 32-key blocks, the two accumulation chains interleaved
   auto scores = [&](int stage, f32x16 (&s)[2]) __attribute__((always_inline)) {
-#ifdef ABL_NO_QK
-    for (int kb = 0; kb < 2; ++kb) for (int i = 0; i < 16; ++i) s[kb][i] = 0.01f * (i + lane + stage);
-    return;
-#endif
     const unsigned char* kbase = smem + stage * 2 * C::TILE_BYTES;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -286,11 +260,6 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   };
   // online softmax (exp2 domain): raises the running max lazily, returns P as bf16 B-operand fragments
   auto softmax = [&](f32x16 (&s)[2], bf16x8 (&pf)[2][2]) __attribute__((always_inline)) {
-#ifdef ABL_NO_SOFTMAX
-    for (int kb = 0; kb < 2; ++kb) for (int j = 0; j < 2; ++j) for (int e = 0; e < 8; ++e) pf[kb][j][e] = static_cast<__bf16>(s[kb][8 * j + e]);
-    l_run += s[0][0];
-    return;
-#endif
     float mx = s[0][0];
 #pragma unroll
     for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[0][i]);
@@ -320,10 +289,6 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   };
   // O^T += V^T P^T : per 16-key block, DB blocks of 32 output rows
   auto accumulate = [&](int stage, const bf16x8 (&pf)[2][2]) __attribute__((always_inline)) {
-#ifdef ABL_NO_PV
-    for (int kb = 0; kb < 2; ++kb) for (int j = 0; j < 2; ++j) o[kb * 2 + j][0] += static_cast<float>(pf[kb][j][0]) + static_cast<float>(pf[kb][j][7]);
-    return;
-#endif
     const unsigned char* vbase = smem + (stage * 2 + 1) * C::TILE_BYTES;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -359,7 +324,6 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   __syncthreads();
 
   int stage = 0;                 // ring stage of tile t
-  PHASE_DECL
   if (__builtin_amdgcn_readfirstlane(wave) < NWAVES / 2) {
     for (int t = 0; t < n_tiles; ++t) {
       const int stage2 = stage == 0 ? 2 : stage - 1;            // (t + 2) mod 3
@@ -391,8 +355,6 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
       stage = stage1;
     }
   }
-
-  PHASE_FLUSH
   // ---- epilogue: normalise and store.  A lane owns one query row; per (db, i4) it holds 4
   // consecutive output columns, and its partner lane (+32) the next 4, so a wavefront writes
   // 32-byte pieces of 32 rows per store and the 16 stores of a lane complete its 512-byte row.
@@ -450,14 +412,6 @@ hipError_t launch_variant(const AttnLaunch& p, hipStream_t stream) {
 }
 
 }  // namespace
-
-#ifdef TASP_PHASE_TIMING
-extern "C" int tasp_debug_phase_cycles(unsigned long long out[8], int reset) {
-  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_cycles), 64) != hipSuccess) return -1;
-  if (reset) { unsigned long long z[8] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), z, 64) != hipSuccess) return -1; }
-  return 0;
-}
-#endif
 
 hipError_t launch_attn_bf16(const AttnLaunch& p, int d, hipStream_t stream) {
   if (d == 128) return launch_variant<128, 8>(p, stream);
