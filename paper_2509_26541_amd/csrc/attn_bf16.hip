@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include <climits>
+#include <type_traits>
 
 #include "internal.hpp"
 
@@ -31,6 +32,8 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
 
 constexpr int BN = 64;           // keys per tile
 constexpr float kLog2e = 1.4426950408889634f;
@@ -43,17 +46,30 @@ struct Cfg {
   static constexpr int NTHREADS = 64 * NWAVES;
   static constexpr int BM = 32 * NWAVES;              // query rows per workgroup
   static constexpr int UNITS = D / 8;                 // 16-byte units per row
-  static constexpr int RPP = NTHREADS / UNITS < BN ? NTHREADS / UNITS : BN;   // rows filled per pass
+  static constexpr int LOADERS = 64 * (NWAVES / 2);   // threads that fetch tiles: the first half of the waves
+  static constexpr int RPP = LOADERS / UNITS < BN ? LOADERS / UNITS : BN;   // rows filled per pass
   static constexpr int PASSES = BN / RPP;
   static constexpr int ROWS_PER_LINE = 16 / UNITS;    // rows per 256-byte bank line (1 or 2)
   static constexpr int TILE_BYTES = BN * D * 2;
-  static constexpr int STAGES = 3;
+  static constexpr int STAGES = 4;
   static constexpr int SMEM = STAGES * 2 * TILE_BYTES;   // ring of (K tile, V tile)
   __device__ static int swz_k(int row, int unit) { return unit ^ ((row / ROWS_PER_LINE) % UNITS); }
   __device__ static int swz_v(int row, int unit) { return unit ^ (4 * ((row / ROWS_PER_LINE) % (UNITS / 4))); }
 };
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// One direct global->LDS load of 16 bytes per lane: lane l's bytes land at lds_base + 16 l.  Written
+// as inline assembly so that the wait for it is placed by hand (s_waitcnt vmcnt before the barrier
+// that publishes the tile) instead of in front of the next LDS read; no other vector memory
+// instruction is in flight while these are.
+__device__ inline void dma16(const unsigned char* src, unsigned char* lds_base) {
+  const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)lds_base));
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(lds_addr), "v"(src)
+               : "memory");
+}
 
 template <int D, int NWAVES>
 __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLaunch p) {
@@ -142,64 +158,63 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   // ---- loader: this thread fills rows fr + RPP*i, unit fu of every K and V tile.  Byte offsets
   // into K and V fit 32 bits (checked on the host).
   const int fr = tid / C::UNITS, fu = tid % C::UNITS;
-  const unsigned char* Kb = static_cast<const unsigned char*>(p.k) + (static_cast<size_t>(g) * D + fu * 8) * 2;
-  const unsigned char* Vb = static_cast<const unsigned char*>(p.v) + (static_cast<size_t>(g) * D + fu * 8) * 2;
   const unsigned row_bytes = static_cast<unsigned>(p.Hkv) * D * 2;
-  int cur = 0;                                                // effective segment of the tile's first row
-  int cur_vend = n_eff > 0 ? e_vbeg[1] : 0;
-  int cur_goff = n_eff > 0 ? e_goff[0] : 0;
-  int cur_diag = n_eff > 0 ? e_diag[0] : 0;
-  u32x4 kreg[C::PASSES], vreg[C::PASSES];                     // the tile in flight between HBM/L2 and LDS
-  int tokk[C::PASSES], flagk[C::PASSES];
-
-  // tokens of tile t (tiles must be asked for in ascending order)
+  // Row bookkeeping of the loader.  Each thread follows its PASSES rows through the virtual
+  // concatenation: from one tile to the next a row moves 64 keys on and normally stays inside its
+  // effective segment (token += 64); only when it runs off the end of the segment is the segment
+  // list searched again.  tokk = global position (INT_MAX: past the last key), flagk = the row
+  // needs the element-wise mask, lefti = keys from the row to the end of its segment.
+  int tokk[C::PASSES], flagk[C::PASSES], segi[C::PASSES], lefti[C::PASSES];
+  auto relocate = [&](int i, int v) __attribute__((always_inline)) {
+    int j = segi[i];
+    while (j < n_eff && v >= e_vbeg[j + 1]) ++j;              // rows only move forward
+    segi[i] = j;
+    if (j < n_eff) { tokk[i] = v + e_goff[j]; flagk[i] = e_diag[j]; lefti[i] = e_vbeg[j + 1] - v; }
+    else { tokk[i] = INT_MAX; flagk[i] = 1; lefti[i] = 1 << 30; }
+  };
+  // rows of tile t; must be called for t = 0, 1, 2, ... in this order
   auto locate = [&](int t) __attribute__((always_inline)) {
-    const int v0 = t * BN;
-    while (cur < n_eff && v0 >= cur_vend) {                   // move to the segment holding row v0
-      ++cur;
-      if (cur < n_eff) { cur_vend = e_vbeg[cur + 1]; cur_goff = e_goff[cur]; cur_diag = e_diag[cur]; }
-    }
-    if (cur < n_eff && v0 + BN <= cur_vend) {                 // the whole tile lies in one segment
+    if (t == 0) {
 #pragma unroll
-      for (int i = 0; i < C::PASSES; ++i) { tokk[i] = v0 + fr + C::RPP * i + cur_goff; flagk[i] = cur_diag; }
-    } else {
-      int j = cur, vend = cur_vend, goff = cur_goff, dg = cur_diag;
-      auto one = [&](int v, int& tok, int& flag) __attribute__((always_inline)) {
-        while (j < n_eff && v >= vend) {                      // rows ascend, so j only moves forward
-          ++j;
-          if (j < n_eff) { vend = e_vbeg[j + 1]; goff = e_goff[j]; dg = e_diag[j]; }
-        }
-        tok = j < n_eff ? v + goff : INT_MAX;                 // past the last key: no row
-        flag = j < n_eff ? dg : 1;
-      };
-      one(v0 + fr, tokk[0], flagk[0]);
-      if constexpr (C::PASSES > 1) one(v0 + fr + C::RPP, tokk[1], flagk[1]);
-      if constexpr (C::PASSES > 2) one(v0 + fr + 2 * C::RPP, tokk[2], flagk[2]);
-      if constexpr (C::PASSES > 3) one(v0 + fr + 3 * C::RPP, tokk[3], flagk[3]);
-      static_assert(C::PASSES <= 4, "loader handles at most 4 passes");
+      for (int i = 0; i < C::PASSES; ++i) { segi[i] = 0; relocate(i, fr + C::RPP * i); }
+      return;
+    }
+    bool off_end = false;
+#pragma unroll
+    for (int i = 0; i < C::PASSES; ++i) {
+      lefti[i] -= BN;
+      tokk[i] = tokk[i] == INT_MAX ? INT_MAX : tokk[i] + BN;
+      off_end |= lefti[i] <= 0;
+    }
+    if (__builtin_amdgcn_ballot_w64(off_end) != 0) {
+#pragma unroll
+      for (int i = 0; i < C::PASSES; ++i)
+        if (lefti[i] <= 0) relocate(i, t * BN + fr + C::RPP * i);
     }
   };
-  // start fetching tile t into registers; tiles past the end fetch token 0 and are never used
-  auto fetch = [&](int t) __attribute__((always_inline)) {
+  // Fetch tile t straight into ring stage `stage` (global_load_lds: no registers, no LDS write
+  // instructions).  A wavefront's 64 lanes fill 1 KiB of consecutive LDS; the XOR swizzle of the
+  // tile layout is applied on the source side: the lane that owns LDS slot (row, unit) reads the
+  // 16 bytes of column swz(row, unit) of that row.  Rows past the end fetch token 0 and are masked.
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const unsigned char* Kd = static_cast<const unsigned char*>(p.k) + (static_cast<size_t>(g) * D + C::swz_k(fr, fu) * 8) * 2;
+  const unsigned char* Vd = static_cast<const unsigned char*>(p.v) + (static_cast<size_t>(g) * D + C::swz_v(fr, fu) * 8) * 2;
+  static_assert(C::RPP % 16 == 0, "the swizzle of a thread's rows must not depend on the pass");
+  auto fetch = [&](int t, int stage) __attribute__((always_inline)) {
     locate(t);
+    unsigned char* kbase = smem + stage * 2 * C::TILE_BYTES + wave_u * 1024;
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
       const unsigned off = __umul24(tokk[i] == INT_MAX ? 0u : static_cast<unsigned>(tokk[i]), row_bytes);   // both below 2^24 (host check)
-      kreg[i] = *reinterpret_cast<const u32x4*>(Kb + off);
-      vreg[i] = *reinterpret_cast<const u32x4*>(Vb + off);
+      dma16(Kd + off, kbase + i * C::LOADERS * 16);
+      dma16(Vd + off, kbase + C::TILE_BYTES + i * C::LOADERS * 16);
+      if (fu == 0) { s_tok[stage][fr + C::RPP * i] = tokk[i]; s_flag[stage][fr + C::RPP * i] = flagk[i]; }
     }
   };
-  // put the fetched tile into ring stage `stage`
-  auto commit = [&](int stage) __attribute__((always_inline)) {
-    unsigned char* kbase = smem + stage * 2 * C::TILE_BYTES;
-    unsigned char* vbase = kbase + C::TILE_BYTES;
-#pragma unroll
-    for (int i = 0; i < C::PASSES; ++i) {
-      const int row = fr + C::RPP * i;
-      *reinterpret_cast<u32x4*>(kbase + (row * C::UNITS + C::swz_k(row, fu)) * 16) = kreg[i];
-      *reinterpret_cast<u32x4*>(vbase + (row * C::UNITS + C::swz_v(row, fu)) * 16) = vreg[i];
-      if (fu == 0) { s_tok[stage][row] = tokk[i]; s_flag[stage][row] = flagk[i]; }
-    }
+  // wait until at most `newest` of this wave's tile fetches (each 2*PASSES loads) are still in flight
+  auto wait_fetches = [&](auto newest) __attribute__((always_inline)) {
+    constexpr int N = decltype(newest)::value * 2 * C::PASSES;
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
   };
 
   // ---- per-lane LDS read offsets (loop invariant)
@@ -305,56 +320,52 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
       }
   };
 
-  // ---- main loop over 64-key tiles.  Ring of three LDS stages: at the barrier that opens iteration
-  // t, tiles t and t+1 are complete; during the iteration every thread commits its share of tile
-  // t+2 (fetched one iteration earlier) into the stage tile t-1 has left, and starts fetching t+3.
+  // ---- main loop over 64-key tiles.  Ring of four LDS stages filled by direct global->LDS loads:
+  // at the barrier that opens iteration t, tiles t and t+1 are complete, tile t+2 is in flight and
+  // every wave starts the fetch of tile t+3 into the stage tile t-1 has left; before the barrier
+  // that closes the iteration it waits for its own part of tile t+2.
   //
   // The two wavefronts that share a SIMD run the same phases half an iteration apart: the first
-  // (waves 0..NWAVES/2-1) goes  scores(t) -> softmax -> accumulate(t),  the second
-  // softmax -> accumulate(t) -> scores(t+1).  After each barrier one of them is in a matrix phase
-  // while the other is in its vector phase, so the matrix and vector pipes overlap instead of
-  // taking turns.
-  if (n_tiles > 0) {
-    fetch(0);
-    commit(0);
-    fetch(1);
-    commit(1);
-    fetch(2);
+  // (waves 0..NWAVES/2-1) goes  fetch -> scores(t) -> softmax -> accumulate(t),  the second
+  // softmax -> accumulate(t) -> fetch -> scores(t+1).  After each barrier one of them is in a
+  // matrix phase while the other is in its vector or loader phase.
+  constexpr std::integral_constant<int, 1> one_in_flight{};
+  if (n_tiles > 0 && __builtin_amdgcn_readfirstlane(wave) < NWAVES / 2) {
+    fetch(0, 0);
+    fetch(1, 1);
+    fetch(2, 2);
+    wait_fetches(one_in_flight);
   }
   __syncthreads();
 
-  int stage = 0;                 // ring stage of tile t
   if (__builtin_amdgcn_readfirstlane(wave) < NWAVES / 2) {
     for (int t = 0; t < n_tiles; ++t) {
-      const int stage2 = stage == 0 ? 2 : stage - 1;            // (t + 2) mod 3
-      commit(stage2);
-      fetch(t + 3);
+      const int stage = t & 3;
+      fetch(t + 3, (t + 3) & 3);
       f32x16 s[2];
       bf16x8 pf[2][2];
       scores(stage, s);
       mask(stage, s);
       softmax(s, pf);
       accumulate(stage, pf);
+      wait_fetches(one_in_flight);
       __syncthreads();
-      stage = stage == 2 ? 0 : stage + 1;
     }
   } else {
     f32x16 s[2];
     if (n_tiles > 0) scores(0, s);
     for (int t = 0; t < n_tiles; ++t) {
-      const int stage1 = stage == 2 ? 0 : stage + 1;
-      const int stage2 = stage == 0 ? 2 : stage - 1;
+      const int stage = t & 3;
       bf16x8 pf[2][2];
       mask(stage, s);
       softmax(s, pf);
       accumulate(stage, pf);
-      commit(stage2);            // the loader work of this wave falls into the other wave's matrix phase
-      fetch(t + 3);
-      scores(stage1, s);         // tile t+1; past the last tile this reads a committed dummy tile and is dropped
+      scores((t + 1) & 3, s);    // tile t+1; past the last tile this reads a fetched dummy tile and is dropped
       __syncthreads();
-      stage = stage1;
     }
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // no fetch may still be writing LDS when the workgroup ends
+
   // ---- epilogue: normalise and store.  A lane owns one query row; per (db, i4) it holds 4
   // consecutive output columns, and its partner lane (+32) the next 4, so a wavefront writes
   // 32-byte pieces of 32 rows per store and the 16 stores of a lane complete its 512-byte row.
