@@ -62,13 +62,13 @@ __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 // One direct global->LDS load of 16 bytes per lane: lane l's bytes land at lds_base + 16 l.  Written
 // as inline assembly so that the wait for it is placed by hand (s_waitcnt vmcnt before the barrier
 // that publishes the tile) instead of in front of the next LDS read; no other vector memory
-// instruction is in flight while these are.
+// instruction is in flight while these are.  It carries no memory clobber: the stage it fills is
+// not read before the next barrier, and barriers and waits are ordered against volatile assembly.
 __device__ inline void dma16(const unsigned char* src, unsigned char* lds_base) {
   const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)lds_base));
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                :
-               : "s"(lds_addr), "v"(src)
-               : "memory");
+               : "s"(lds_addr), "v"(src));
 }
 
 template <int D, int NWAVES>
@@ -200,16 +200,30 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   const unsigned char* Kd = static_cast<const unsigned char*>(p.k) + (static_cast<size_t>(g) * D + C::swz_k(fr, fu) * 8) * 2;
   const unsigned char* Vd = static_cast<const unsigned char*>(p.v) + (static_cast<size_t>(g) * D + C::swz_v(fr, fu) * 8) * 2;
   static_assert(C::RPP % 16 == 0, "the swizzle of a thread's rows must not depend on the pass");
-  auto fetch = [&](int t, int stage) __attribute__((always_inline)) {
+  // A tile fetch is 2*PASSES loads per thread.  The path from L2 into LDS takes roughly 25 cycles per
+  // wavefront-load and the issuing wave stalls once its queue is full, so the loads are not issued
+  // in one burst: fetch_begin does the bookkeeping, fetch_piece(j) issues load j, and the scores
+  // phase drops one piece between its matrix instructions.
+  unsigned fetch_off[C::PASSES];
+  unsigned char* fetch_dst = smem;
+  auto fetch_begin = [&](int t, int stage) __attribute__((always_inline)) {
     locate(t);
-    unsigned char* kbase = smem + stage * 2 * C::TILE_BYTES + wave_u * 1024;
+    fetch_dst = smem + stage * 2 * C::TILE_BYTES + wave_u * 1024;
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
-      const unsigned off = __umul24(tokk[i] == INT_MAX ? 0u : static_cast<unsigned>(tokk[i]), row_bytes);   // both below 2^24 (host check)
-      dma16(Kd + off, kbase + i * C::LOADERS * 16);
-      dma16(Vd + off, kbase + C::TILE_BYTES + i * C::LOADERS * 16);
+      fetch_off[i] = __umul24(tokk[i] == INT_MAX ? 0u : static_cast<unsigned>(tokk[i]), row_bytes);   // both below 2^24 (host check)
       if (fu == 0) { s_tok[stage][fr + C::RPP * i] = tokk[i]; s_flag[stage][fr + C::RPP * i] = flagk[i]; }
     }
+  };
+  auto fetch_piece = [&](int j) __attribute__((always_inline)) {
+    const int i = j >> 1;
+    if (j & 1) dma16(Vd + fetch_off[i], fetch_dst + C::TILE_BYTES + i * C::LOADERS * 16);
+    else dma16(Kd + fetch_off[i], fetch_dst + i * C::LOADERS * 16);
+  };
+  auto fetch = [&](int t, int stage) __attribute__((always_inline)) {
+    fetch_begin(t, stage);
+#pragma unroll
+    for (int j = 0; j < 2 * C::PASSES; ++j) fetch_piece(j);
   };
   // wait until at most `newest` of this wave's tile fetches (each 2*PASSES loads) are still in flight
   auto wait_fetches = [&](auto newest) __attribute__((always_inline)) {
@@ -233,19 +247,25 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   }
 
   // S^T = K Q^T for the K tile in `kslot`: two 32-key blocks, the two accumulation chains interleaved
-  auto scores = [&](int stage, f32x16 (&s)[2]) __attribute__((always_inline)) {
+  auto scores = [&](int stage, f32x16 (&s)[2], auto with_fetch) __attribute__((always_inline)) {
     const unsigned char* kbase = smem + stage * 2 * C::TILE_BYTES;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
+    for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * D * 2 + koff[ks]);
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
       }
+      if constexpr (decltype(with_fetch)::value) {
+        // 2*PASSES pieces over KS steps
+#pragma unroll
+        for (int j = ks * 2 * C::PASSES / KS; j < (ks + 1) * 2 * C::PASSES / KS; ++j) fetch_piece(j);
+      }
+    }
   };
 
   // ---- running state
@@ -341,10 +361,10 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   if (__builtin_amdgcn_readfirstlane(wave) < NWAVES / 2) {
     for (int t = 0; t < n_tiles; ++t) {
       const int stage = t & 3;
-      fetch(t + 3, (t + 3) & 3);
+      fetch_begin(t + 3, (t + 3) & 3);
       f32x16 s[2];
       bf16x8 pf[2][2];
-      scores(stage, s);
+      scores(stage, s, std::true_type{});
       mask(stage, s);
       softmax(s, pf);
       accumulate(stage, pf);
@@ -353,14 +373,14 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
     }
   } else {
     f32x16 s[2];
-    if (n_tiles > 0) scores(0, s);
+    if (n_tiles > 0) scores(0, s, std::false_type{});
     for (int t = 0; t < n_tiles; ++t) {
       const int stage = t & 3;
       bf16x8 pf[2][2];
       mask(stage, s);
       softmax(s, pf);
       accumulate(stage, pf);
-      scores((t + 1) & 3, s);    // tile t+1; past the last tile this reads a fetched dummy tile and is dropped
+      scores((t + 1) & 3, s, std::false_type{});    // tile t+1; past the last tile this reads a fetched dummy tile and is dropped
       __syncthreads();
     }
   }
