@@ -261,9 +261,9 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
       }
       if constexpr (decltype(with_fetch)::value) {
-        // 2*PASSES pieces over KS steps
+        // the first half of the 2*PASSES pieces, spread over the KS steps
 #pragma unroll
-        for (int j = ks * 2 * C::PASSES / KS; j < (ks + 1) * 2 * C::PASSES / KS; ++j) fetch_piece(j);
+        for (int j = ks * C::PASSES / KS; j < (ks + 1) * C::PASSES / KS; ++j) fetch_piece(j);
       }
     }
   };
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
     l_run += lsum;
   };
   // O^T += V^T P^T : per 16-key block, DB blocks of 32 output rows
-  auto accumulate = [&](int stage, const bf16x8 (&pf)[2][2]) __attribute__((always_inline)) {
+  auto accumulate = [&](int stage, const bf16x8 (&pf)[2][2], auto with_fetch) __attribute__((always_inline)) {
     const unsigned char* vbase = smem + (stage * 2 + 1) * C::TILE_BYTES;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -336,6 +336,13 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
           const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(vb + 8 * D * 2 + voff[db]));
           const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kb][j], o[db], 0, 0, 0);
+        }
+        if constexpr (decltype(with_fetch)::value) {
+          // the second half of the pieces, spread over the four 16-key groups
+          constexpr int G4 = 4;
+          const int grp = 2 * kb + j;
+#pragma unroll
+          for (int q = C::PASSES + grp * C::PASSES / G4; q < C::PASSES + (grp + 1) * C::PASSES / G4; ++q) fetch_piece(q);
         }
       }
   };
@@ -367,7 +374,7 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
       scores(stage, s, std::true_type{});
       mask(stage, s);
       softmax(s, pf);
-      accumulate(stage, pf);
+      accumulate(stage, pf, std::true_type{});
       wait_fetches(one_in_flight);
       __syncthreads();
     }
@@ -379,7 +386,7 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
       bf16x8 pf[2][2];
       mask(stage, s);
       softmax(s, pf);
-      accumulate(stage, pf);
+      accumulate(stage, pf, std::false_type{});
       scores((t + 1) & 3, s, std::false_type{});    // tile t+1; past the last tile this reads a fetched dummy tile and is dropped
       __syncthreads();
     }
