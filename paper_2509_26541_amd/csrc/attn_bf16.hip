@@ -17,6 +17,7 @@
 
 #include <climits>
 #include <type_traits>
+#include <utility>
 
 #include "internal.hpp"
 
@@ -31,6 +32,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(1))) void* global_void_ptr;
@@ -71,6 +73,60 @@ __device__ inline void dma16(const unsigned char* src, unsigned char* lds_base) 
                : "s"(lds_addr), "v"(src));
 }
 
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
+
+// LDS operand reads whose wait is placed by hand.  The compiler puts an LDS read one or two matrix
+// instructions ahead of its use, which leaves most of the LDS latency exposed with two wavefronts
+// per SIMD; here the reads of PD operand fragments are kept in flight.  A read is volatile assembly
+// (issued in program order), and the fragment reaches its matrix instruction only through lds_wait,
+// which waits until at most N younger LDS instructions are outstanding (LDS instructions of a
+// wavefront complete in order, so extra ones the compiler adds only make a wait stricter).
+template <int IMM>
+__device__ __forceinline__ void lds_read_b128(u32x4& d, unsigned addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(IMM));
+}
+template <int IMM>
+__device__ __forceinline__ void lds_read_tr_b64(u32x2& d, unsigned addr) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(IMM));
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x4& f) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x2& a, u32x2& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+// marks a fragment as defined after the preceding (volatile) wait
+__device__ __forceinline__ void after_wait(u32x4& f) { asm volatile("" : "+v"(f)); }
+__device__ __forceinline__ void after_wait(u32x2& a, u32x2& b) { asm volatile("" : "+v"(a), "+v"(b)); }
+
+// Order of the matrix instructions of one loop iteration.  ROLE 0 (first half of the waves):
+// K Q^T of tile t, then V^T P^T of tile t.  ROLE 1: V^T P^T of tile t, then K Q^T of tile t+1.
+template <int D, int ROLE>
+struct Seq {
+  static constexpr int NK = 2 * (D / 16);      // matrix instructions of K Q^T per tile (one 16-byte LDS read each)
+  static constexpr int NV = 4 * (D / 32);      //   and of V^T P^T (two transposing 8-byte reads each)
+  static constexpr int NOPS = NK + NV;
+  static constexpr bool is_k(int pos) { return ROLE == 0 ? pos < NK : pos >= NV; }
+  static constexpr int idx(int pos) { return ROLE == 0 ? (pos < NK ? pos : pos - NK) : (pos < NV ? pos : pos - NV); }
+  static constexpr int tile_off(int pos) { return ROLE == 1 && pos >= NV ? 1 : 0; }
+  // LDS reads issued between the read of position q and its wait when pd fragments are kept ahead (the counter holds 15)
+  static constexpr int younger(int q, int pd) {
+    int n = 0;
+    for (int r = q + 1; r <= q + pd; ++r) n += is_k(r % NOPS) ? 1 : 2;
+    return n < 15 ? n : 15;
+  }
+};
+
 template <int D, int NWAVES>
 __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLaunch p) {
   using C = Cfg<D, NWAVES>;
@@ -80,11 +136,12 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
 
   __shared__ __attribute__((aligned(16))) unsigned char smem[C::SMEM];   // ring of stages, each a K tile then a V tile
   __shared__ __attribute__((aligned(16))) int s_tok[C::STAGES][BN];   // global position of every key row of a tile (INT_MAX: none)
-  __shared__ int s_flag[C::STAGES][BN];          // 1: the row needs the element-wise mask
   __shared__ int e_vbeg[2 * kMaxSeg + 1];  // effective segments: start in the virtual concatenation
   __shared__ int e_goff[2 * kMaxSeg];      //   global position minus virtual position
   __shared__ int e_diag[2 * kMaxSeg];      //   straddles the diagonal of this query tile
   __shared__ int e_n;
+  __shared__ int m_lo[2 * kMaxSeg + 2];    // runs of tiles that need the element-wise mask (sorted, the
+  __shared__ int m_hi[2 * kMaxSeg + 2];    //   last run is open-ended: m_hi = INT_MAX)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -134,6 +191,17 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
     }
     e_vbeg[n] = vpos;
     e_n = n;
+    // tiles that touch a diagonal segment, and everything from the first tile that runs past the last key
+    int mn = 0;
+    for (int j = 0; j < n; ++j) {
+      if (!e_diag[j]) continue;
+      const int lo = e_vbeg[j] / BN, hi = (e_vbeg[j + 1] - 1) / BN;
+      if (mn > 0 && lo <= m_hi[mn - 1]) m_hi[mn - 1] = max(m_hi[mn - 1], hi);
+      else { m_lo[mn] = lo; m_hi[mn] = hi; ++mn; }
+    }
+    const int tail = vpos / BN;
+    if (mn > 0 && tail <= m_hi[mn - 1]) m_hi[mn - 1] = INT_MAX;
+    else { m_lo[mn] = tail; m_hi[mn] = INT_MAX; ++mn; }
   }
   __syncthreads();
   const int n_eff = e_n;
@@ -212,7 +280,7 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
       fetch_off[i] = __umul24(tokk[i] == INT_MAX ? 0u : static_cast<unsigned>(tokk[i]), row_bytes);   // both below 2^24 (host check)
-      if (fu == 0) { s_tok[stage][fr + C::RPP * i] = tokk[i]; s_flag[stage][fr + C::RPP * i] = flagk[i]; }
+      if (fu == 0) s_tok[stage][fr + C::RPP * i] = tokk[i];
     }
   };
   auto fetch_piece = [&](int j) __attribute__((always_inline)) {
@@ -235,6 +303,10 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   int koff[KS];       // K: row lq (+32 kb), unit 2 ks + h
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) koff[ks] = (lq * C::UNITS + C::swz_k(lq, 2 * ks + h)) * 16;
+  const unsigned smem_lds = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)smem));
+  unsigned kadr[KS];  // the same as LDS addresses, stage 0
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) kadr[ks] = smem_lds + koff[ks];
   // V^T through the transposing read: 16-lane group a = lane/16 serves d columns 16 (a%2) .. +16 of
   // a 32-wide block for lane half h = a/2; lane jj of the group points at key 4 h + jj/4, 4 d values.
   const int ga = lane >> 4, jj = lane & 15;
@@ -245,27 +317,24 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
     const int unit = 4 * db + 2 * (ga & 1) + ((jj & 3) >> 1);
     voff[db] = (vrow * C::UNITS + C::swz_v(vrow, unit)) * 16 + 8 * (jj & 1);
   }
+  unsigned vadr[DB];  // LDS addresses inside the V tile of stage 0
+#pragma unroll
+  for (int db = 0; db < DB; ++db) vadr[db] = smem_lds + C::TILE_BYTES + voff[db];
 
-  // S^T = K Q^T for the K tile in `kslot`: two 32-key blocks, the two accumulation chains interleaved
-  auto scores = [&](int stage, f32x16 (&s)[2], auto with_fetch) __attribute__((always_inline)) {
+  // S^T = K Q^T of one K tile, reads left to the compiler (used once, before the loop)
+  auto scores = [&](int stage, f32x16 (&s)[2], auto) __attribute__((always_inline)) {
     const unsigned char* kbase = smem + stage * 2 * C::TILE_BYTES;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * D * 2 + koff[ks]);
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
       }
-      if constexpr (decltype(with_fetch)::value) {
-        // the first half of the 2*PASSES pieces, spread over the KS steps
-#pragma unroll
-        for (int j = ks * C::PASSES / KS; j < (ks + 1) * C::PASSES / KS; ++j) fetch_piece(j);
-      }
-    }
   };
 
   // ---- running state
@@ -280,8 +349,16 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
 
   // ---- the three phases of a tile, for one wave
   // element-wise mask, only for tiles that touch the diagonal or run past the last key
-  auto mask = [&](int stage, f32x16 (&s)[2]) __attribute__((always_inline)) {
-    if (__builtin_amdgcn_ballot_w64(s_flag[stage][lane] != 0) != 0) {
+  int m_idx = 0;
+  int m_cur_lo = __builtin_amdgcn_readfirstlane(m_lo[0]), m_cur_hi = __builtin_amdgcn_readfirstlane(m_hi[0]);
+  auto mask = [&](int t, f32x16 (&s)[2]) __attribute__((always_inline)) {
+    while (t > m_cur_hi) {     // t only grows; the last run never ends
+      ++m_idx;
+      m_cur_lo = __builtin_amdgcn_readfirstlane(m_lo[m_idx]);
+      m_cur_hi = __builtin_amdgcn_readfirstlane(m_hi[m_idx]);
+    }
+    if (t >= m_cur_lo) {
+      const int stage = t & 3;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -300,7 +377,12 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
     for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[0][i]);
 #pragma unroll
     for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    {
+      // the other half of the keys sits in the lane 32 away
+      const unsigned mu = __builtin_bit_cast(unsigned, mx);
+      const u32x2 sw = __builtin_amdgcn_permlane32_swap(mu, mu, false, false);
+      mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
+    }
     const float m_cand = fmaxf(m_run, mx * c);
     if (__builtin_amdgcn_ballot_w64(m_cand > m_run + kRescaleGap) != 0) {
       const float alpha = fast_exp2(m_run - m_cand);
@@ -322,41 +404,81 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
       }
     l_run += lsum;
   };
-  // O^T += V^T P^T : per 16-key block, DB blocks of 32 output rows
-  auto accumulate = [&](int stage, const bf16x8 (&pf)[2][2], auto with_fetch) __attribute__((always_inline)) {
-    const unsigned char* vbase = smem + (stage * 2 + 1) * C::TILE_BYTES;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const unsigned char* vb = vbase + (32 * kb + 16 * j) * D * 2;
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(vb + voff[db]));
-          const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(vb + 8 * D * 2 + voff[db]));
-          const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kb][j], o[db], 0, 0, 0);
-        }
-        if constexpr (decltype(with_fetch)::value) {
-          // the second half of the pieces, spread over the four 16-key groups
-          constexpr int G4 = 4;
-          const int grp = 2 * kb + j;
-#pragma unroll
-          for (int q = C::PASSES + grp * C::PASSES / G4; q < C::PASSES + (grp + 1) * C::PASSES / G4; ++q) fetch_piece(q);
-        }
-      }
+  // ---- the matrix instructions of an iteration as one stream of operand fragments: the LDS reads
+  // of the fragment PD positions ahead are issued right after the matrix instruction of a position, so
+  // the reads run through the phase changes (the first fragments of the second product land while
+  // the softmax runs) and into the first products of the next iteration.
+  constexpr int PD = 8;
+  using SeqA = Seq<D, 0>;
+  constexpr int NK = SeqA::NK, NV = SeqA::NV, NOPS = SeqA::NOPS;
+  static_assert(NOPS % PD == 0 && NK >= PD && NV >= PD, "fragment ring must close over an iteration");
+  u32x4 fk[PD];            // K fragments in flight (ring slot = position % PD)
+  u32x2 fl[PD], fh[PD];    // V^T fragments in flight, low and high half
+  // issue the reads of stream position Q (may lie in the next iteration); base_* = ring stage byte offsets of tiles t, t+1
+  auto issue = [&](auto role, auto qq, unsigned base_cur, unsigned base_next) __attribute__((always_inline)) {
+    using S = Seq<D, decltype(role)::value>;
+    constexpr int Q = decltype(qq)::value;
+    constexpr int pos = Q % NOPS, adv = Q / NOPS + S::tile_off(pos), slot = Q % PD, i = S::idx(pos);
+    static_assert(adv <= 1, "only tiles t and t+1 are read");
+    const unsigned base = adv ? base_next : base_cur;
+    if constexpr (S::is_k(pos)) {
+      constexpr int ks = i / 2, kb = i % 2;
+      lds_read_b128<kb * 32 * D * 2>(fk[slot], kadr[ks] + base);
+    } else {
+      constexpr int g = i / DB, db = i % DB;    // 16-key group, 32-row block of O^T
+      lds_read_tr_b64<g * 16 * D * 2>(fl[slot], vadr[db] + base);
+      lds_read_tr_b64<g * 16 * D * 2 + 8 * D * 2>(fh[slot], vadr[db] + base);
+    }
   };
+  // wait for the fragment of position Q and run its matrix instruction
+  auto exec = [&](auto role, auto qq, f32x16 (&s)[2], const bf16x8 (&pf)[2][2]) __attribute__((always_inline)) {
+    using S = Seq<D, decltype(role)::value>;
+    constexpr int Q = decltype(qq)::value;
+    constexpr int slot = Q % PD, i = S::idx(Q), W = S::younger(Q, PD - 1);
+    if constexpr (S::is_k(Q)) {
+      constexpr int ks = i / 2, kb = i % 2;
+      lds_wait<W>(fk[slot]);
+      const bf16x8 a = __builtin_bit_cast(bf16x8, fk[slot]);
+      if constexpr (ks == 0) {
+        f32x16 z;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) z[e] = 0.f;
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0], z, 0, 0, 0);
+      } else {
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
+      }
+    } else {
+      constexpr int g = i / DB, db = i % DB;
+      lds_wait<W>(fl[slot], fh[slot]);
+      const u32x4 av = {fl[slot][0], fl[slot][1], fh[slot][0], fh[slot][1]};
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pf[g / 2][g % 2], o[db], 0, 0, 0);
+    }
+  };
+  // Fragments that cross the loop edge are waited for before the closing barrier, where the wave
+  // waits anyway: a register copy the compiler may place on the loop edge then copies landed data.
+  auto land_k = [&]() __attribute__((always_inline)) {
+    lds_wait<0>(fk[0]);
+    static_for<PD - 1>([&](auto i) __attribute__((always_inline)) { after_wait(fk[decltype(i)::value + 1]); });
+  };
+  auto land_v = [&]() __attribute__((always_inline)) {
+    lds_wait<0>(fl[0], fh[0]);
+    static_for<PD - 1>([&](auto i) __attribute__((always_inline)) { after_wait(fl[decltype(i)::value + 1], fh[decltype(i)::value + 1]); });
+  };
+  constexpr unsigned STAGE_BYTES = 2 * C::TILE_BYTES;
 
   // ---- main loop over 64-key tiles.  Ring of four LDS stages filled by direct global->LDS loads:
   // at the barrier that opens iteration t, tiles t and t+1 are complete, tile t+2 is in flight and
-  // every wave starts the fetch of tile t+3 into the stage tile t-1 has left; before the barrier
-  // that closes the iteration it waits for its own part of tile t+2.
+  // the first half of the waves starts the fetch of tile t+3 into the stage tile t-1 has left;
+  // before the barrier that closes the iteration they wait for tile t+2.
   //
-  // The two wavefronts that share a SIMD run the same phases half an iteration apart: the first
-  // (waves 0..NWAVES/2-1) goes  fetch -> scores(t) -> softmax -> accumulate(t),  the second
-  // softmax -> accumulate(t) -> fetch -> scores(t+1).  After each barrier one of them is in a
-  // matrix phase while the other is in its vector or loader phase.
+  // The two wavefronts that share a SIMD run half an iteration apart: the first goes
+  // scores(t) -> softmax -> accumulate(t), the second softmax -> accumulate(t) -> scores(t+1), so
+  // that one of them has matrix work while the other is in its vector phase.
   constexpr std::integral_constant<int, 1> one_in_flight{};
+  constexpr std::integral_constant<int, 0> role_a{};
+  constexpr std::integral_constant<int, 1> role_b{};
+  constexpr int OPS_PER_PIECE = NOPS / (2 * C::PASSES);
+  static_assert(NOPS % (2 * C::PASSES) == 0, "fetch pieces are spread evenly over the matrix instructions");
   if (n_tiles > 0 && __builtin_amdgcn_readfirstlane(wave) < NWAVES / 2) {
     fetch(0, 0);
     fetch(1, 1);
@@ -365,30 +487,47 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   }
   __syncthreads();
 
-  if (__builtin_amdgcn_readfirstlane(wave) < NWAVES / 2) {
-    for (int t = 0; t < n_tiles; ++t) {
-      const int stage = t & 3;
-      fetch_begin(t + 3, (t + 3) & 3);
+  if (n_tiles > 0) {
+    if (__builtin_amdgcn_readfirstlane(wave) < NWAVES / 2) {
+      static_for<PD>([&](auto q) __attribute__((always_inline)) { issue(role_a, q, 0u, STAGE_BYTES); });
+      land_k();
+      for (int t = 0; t < n_tiles; ++t) {
+        fetch_begin(t + 3, (t + 3) & 3);
+        f32x16 s[2];
+        bf16x8 pf[2][2];
+        const unsigned base_cur = (t & 3) * STAGE_BYTES, base_next = ((t + 1) & 3) * STAGE_BYTES;
+        static_for<NOPS>([&](auto q) __attribute__((always_inline)) {
+          constexpr int Q = decltype(q)::value;
+          exec(role_a, q, s, pf);
+          issue(role_a, std::integral_constant<int, Q + PD>{}, base_cur, base_next);   // into the ring slot just consumed
+          if constexpr ((Q + 1) % OPS_PER_PIECE == 0) fetch_piece((Q + 1) / OPS_PER_PIECE - 1);
+          if constexpr (Q == NK - 1) {
+            mask(t, s);
+            softmax(s, pf);
+          }
+        });
+        wait_fetches(one_in_flight);
+        land_k();
+        __syncthreads();
+      }
+    } else {
       f32x16 s[2];
-      bf16x8 pf[2][2];
-      scores(stage, s, std::true_type{});
-      mask(stage, s);
-      softmax(s, pf);
-      accumulate(stage, pf, std::true_type{});
-      wait_fetches(one_in_flight);
-      __syncthreads();
-    }
-  } else {
-    f32x16 s[2];
-    if (n_tiles > 0) scores(0, s, std::false_type{});
-    for (int t = 0; t < n_tiles; ++t) {
-      const int stage = t & 3;
-      bf16x8 pf[2][2];
-      mask(stage, s);
-      softmax(s, pf);
-      accumulate(stage, pf, std::false_type{});
-      scores((t + 1) & 3, s, std::false_type{});    // tile t+1; past the last tile this reads a fetched dummy tile and is dropped
-      __syncthreads();
+      scores(0, s, std::false_type{});
+      static_for<PD>([&](auto q) __attribute__((always_inline)) { issue(role_b, q, 0u, STAGE_BYTES); });
+      land_v();
+      for (int t = 0; t < n_tiles; ++t) {
+        bf16x8 pf[2][2];
+        mask(t, s);
+        softmax(s, pf);
+        const unsigned base_cur = (t & 3) * STAGE_BYTES, base_next = ((t + 1) & 3) * STAGE_BYTES;
+        static_for<NOPS>([&](auto q) __attribute__((always_inline)) {
+          constexpr int Q = decltype(q)::value;
+          exec(role_b, q, s, pf);     // tile t+1 for the scores; past the last tile that is a fetched dummy tile and is dropped
+          issue(role_b, std::integral_constant<int, Q + PD>{}, base_cur, base_next);
+        });
+        land_v();
+        __syncthreads();
+      }
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // no fetch may still be writing LDS when the workgroup ends
