@@ -2,17 +2,29 @@
 //
 // The paper concatenates the N-1 sub-chunks of a step and calls a flash-attention library on the
 // copy (Algorithm 3; Sec. 5.4 puts the cost of that copy at 1-5 % of the compute time).  Here the
-// kernel walks the *virtual* concatenation instead: a workgroup owns 32 x NWAVES query rows of one head and
+// kernel walks the *virtual* concatenation instead: a workgroup owns 256 query rows of one head and
 // streams 64-key tiles whose rows are gathered from the K/V segments of the step, so sub-chunk
 // lengths that are no tile multiple cost nothing and nothing is copied.
 //
-// Per wave (32 query rows):  S^T = K Q^T  and  O^T = V^T P^T  with v_mfma_f32_32x32x16_bf16.
+// Per 32-row strip of queries:  S^T = K Q^T  and  O^T = V^T P^T  with v_mfma_f32_32x32x16_bf16.
 // Computing the transposed products puts one query in one lane column, so the row max / row sum of
 // the online softmax are in-lane reductions over 32 registers plus one exchange between the two
 // lane halves, the rescale factor is a per-lane scalar, and the fp32 -> bf16 P tile is already in
 // the B-operand layout of the second product.  K tiles are read from LDS with 16-byte reads, V
 // tiles with the transposing LDS read (ds_read_b64_tr_b16); both tiles are XOR-swizzled in 16-byte
 // units so that neither the fills nor the reads conflict on banks.
+//
+// The loop is software-pipelined by hand inside each wavefront: the scores of tile t+1 and the
+// second product of tile t form one stream of matrix instructions, the softmax arithmetic of tile t
+// and the row maxima of tile t+1 are dealt out between them, operand fragments are read eight
+// ahead.  Matrix instructions and LDS reads are volatile assembly, so their order is the schedule.
+//
+// A wavefront owns NS strips.  NS = 1 (eight wavefronts, two per SIMD) is what the library
+// launches.  With 32 rows per wavefront every matrix instruction needs 1 KiB of operand from LDS,
+// i.e. the LDS has to deliver its full 128 B/clk for the matrix pipe to run at its peak.  NS = 2
+// (each fragment feeds two matrix instructions, O^T and Q in AGPRs, one wavefront per SIMD) halves
+// that traffic, but then one wavefront has to issue every instruction of its SIMD and is bound by
+// that: measured slower, kept as a template parameter.
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -43,13 +55,14 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kRescaleGap = 8.0f;   // the running max is only raised when it grew by more than 2^8
 constexpr float kNegBig = -1.0e30f;
 
-template <int D, int NWAVES>
+template <int D, int NS_>
 struct Cfg {
+  static constexpr int NS = NS_;                      // 32-row query strips per wavefront
+  static constexpr int NWAVES = 8 / NS;               // NS = 1: two wavefronts per SIMD, NS = 2: one
   static constexpr int NTHREADS = 64 * NWAVES;
-  static constexpr int BM = 32 * NWAVES;              // query rows per workgroup
+  static constexpr int BM = 32 * NS * NWAVES;         // query rows per workgroup (256)
   static constexpr int UNITS = D / 8;                 // 16-byte units per row
-  static constexpr int LOADERS = 64 * (NWAVES / 2);   // threads that fetch tiles: the first half of the waves
-  static constexpr int RPP = LOADERS / UNITS < BN ? LOADERS / UNITS : BN;   // rows filled per pass
+  static constexpr int RPP = NTHREADS / UNITS < BN ? NTHREADS / UNITS : BN;   // rows filled per pass
   static constexpr int PASSES = BN / RPP;
   static constexpr int ROWS_PER_LINE = 16 / UNITS;    // rows per 256-byte bank line (1 or 2)
   static constexpr int TILE_BYTES = BN * D * 2;
@@ -60,19 +73,23 @@ struct Cfg {
 };
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// maxima as assembly: the inputs come out of matrix instructions the compiler cannot see, and it
+// would otherwise quiet every one of them first
+__device__ __forceinline__ float max2(float a, float b) { float r; asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+__device__ __forceinline__ float max3(float a, float b, float c) { float r; asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c)); return r; }
 
-// One direct global->LDS load of 16 bytes per lane: lane l's bytes land at lds_base + 16 l.  Written
-// as inline assembly so that the wait for it is placed by hand (s_waitcnt vmcnt before the barrier
-// that publishes the tile) instead of in front of the next LDS read; no other vector memory
-// instruction is in flight while these are.  It carries no memory clobber: the stage it fills is
-// not read before the next barrier, and barriers and waits are ordered against volatile assembly.
-__device__ inline void dma16(const unsigned char* src, unsigned char* lds_base) {
+// One direct global->LDS load of 16 bytes per lane: lane l reads base + off and its bytes land at
+// lds_base + 16 l.  Written as inline assembly so that the wait for it is placed by hand (s_waitcnt
+// vmcnt before the barrier that publishes the tile) instead of in front of the next LDS read; no
+// other vector memory instruction is in flight while these are.  It carries no memory clobber: the
+// stage it fills is not read before the next barrier, and barriers and waits are ordered against
+// volatile assembly.
+__device__ inline void dma16(const unsigned char* base, unsigned off, unsigned char* lds_base) {
   const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)lds_base));
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
-               : "s"(lds_addr), "v"(src));
+               : "s"(lds_addr), "v"(off), "s"(base));
 }
-
 // Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
 template <class F, int... I>
 __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
@@ -83,12 +100,10 @@ __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
 }
 
-// LDS operand reads whose wait is placed by hand.  The compiler puts an LDS read one or two matrix
-// instructions ahead of its use, which leaves most of the LDS latency exposed with two wavefronts
-// per SIMD; here the reads of PD operand fragments are kept in flight.  A read is volatile assembly
-// (issued in program order), and the fragment reaches its matrix instruction only through lds_wait,
-// which waits until at most N younger LDS instructions are outstanding (LDS instructions of a
-// wavefront complete in order, so extra ones the compiler adds only make a wait stricter).
+// LDS operand reads whose wait is placed by hand.  A read is volatile assembly (issued in program
+// order), and the fragment reaches its matrix instruction only through lds_wait, which waits until
+// at most N younger LDS instructions are outstanding (LDS instructions of a wavefront complete in
+// order, so extra ones the compiler adds only make a wait stricter).
 template <int IMM>
 __device__ __forceinline__ void lds_read_b128(u32x4& d, unsigned addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(IMM));
@@ -105,34 +120,61 @@ template <int N>
 __device__ __forceinline__ void lds_wait(u32x2& a, u32x2& b) {
   asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
 }
-// marks a fragment as defined after the preceding (volatile) wait
-__device__ __forceinline__ void after_wait(u32x4& f) { asm volatile("" : "+v"(f)); }
-__device__ __forceinline__ void after_wait(u32x2& a, u32x2& b) { asm volatile("" : "+v"(a), "+v"(b)); }
 
-// Order of the matrix instructions of one loop iteration.  ROLE 0 (first half of the waves):
-// K Q^T of tile t, then V^T P^T of tile t.  ROLE 1: V^T P^T of tile t, then K Q^T of tile t+1.
-template <int D, int ROLE>
-struct Seq {
-  static constexpr int NK = 2 * (D / 16);      // matrix instructions of K Q^T per tile (one 16-byte LDS read each)
-  static constexpr int NV = 4 * (D / 32);      //   and of V^T P^T (two transposing 8-byte reads each)
-  static constexpr int NOPS = NK + NV;
-  static constexpr bool is_k(int pos) { return ROLE == 0 ? pos < NK : pos >= NV; }
-  static constexpr int idx(int pos) { return ROLE == 0 ? (pos < NK ? pos : pos - NK) : (pos < NV ? pos : pos - NV); }
-  static constexpr int tile_off(int pos) { return ROLE == 1 && pos >= NV ? 1 : 0; }
-  // LDS reads issued between the read of position q and its wait when pd fragments are kept ahead (the counter holds 15)
-  static constexpr int younger(int q, int pd) {
-    int n = 0;
-    for (int r = q + 1; r <= q + pd; ++r) n += is_k(r % NOPS) ? 1 : 2;
-    return n < 15 ? n : 15;
-  }
-};
+// Matrix instructions as volatile assembly: they stay in program order, which is the schedule, and
+// the register classes are fixed: score tiles in VGPRs (the softmax reads them), O^T and the Q
+// fragments in AGPRs.  The compiler does not know these are matrix instructions, so the wait states
+// it would insert are placed by hand (the fence_* helpers):
+//   matrix result -> vector ALU / accvgpr read: 12 wait states;  vector ALU result -> matrix operand: 2.
+// Dependent matrix instructions on the same accumulator need none.
+// ACC: O^T and the Q fragments live in AGPRs (needed when a wave owns two strips; with one strip
+// everything fits the 256 VGPRs of a wave that shares its SIMD, and using any AGPR would make the
+// compiler split that budget in half).
+template <bool ACC>
+__device__ __forceinline__ void mfma_s_first(f32x16& d, const u32x4& a, const u32x4& b) {
+  if constexpr (ACC) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
+}
+template <bool ACC>
+__device__ __forceinline__ void mfma_s(f32x16& d, const u32x4& a, const u32x4& b) {
+  if constexpr (ACC) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
+}
+template <bool ACC>
+__device__ __forceinline__ void mfma_o(f32x16& d, const u32x4& a, const u32x4& b) {
+  if constexpr (ACC) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
+}
+// score tile: readable by the vector ALU after this point (placed at least one matrix instruction after the last one that wrote it)
+__device__ __forceinline__ void fence_s(f32x16& a, f32x16& b) { asm volatile("s_nop 15" : "+v"(a), "+v"(b)); }
+__device__ __forceinline__ void fence_s_next(f32x16& a, f32x16& b) { asm volatile("" : "+v"(a), "+v"(b)); }
+// P fragment: written by the vector ALU, read by matrix instructions after this point
+__device__ __forceinline__ void fence_p(u32x4& f) { asm volatile("s_nop 1" : "+v"(f)); }
+// O^T accumulator: readable / writable by the vector ALU after this point
+template <bool ACC>
+__device__ __forceinline__ void fence_o_first(f32x16& a) {
+  if constexpr (ACC) asm volatile("s_nop 15\n\ts_nop 3" : "+a"(a));
+  else asm volatile("s_nop 15\n\ts_nop 3" : "+v"(a));
+}
+template <bool ACC>
+__device__ __forceinline__ void fence_o_next(f32x16& a) {
+  if constexpr (ACC) asm volatile("" : "+a"(a));
+  else asm volatile("" : "+v"(a));
+}
+// O^T accumulator written by the vector ALU, read by matrix instructions after this point
+template <bool ACC>
+__device__ __forceinline__ void fence_o_written(f32x16& a) {
+  if constexpr (ACC) asm volatile("s_nop 1" : "+a"(a));
+  else asm volatile("s_nop 1" : "+v"(a));
+}
 
-template <int D, int NWAVES>
-__global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLaunch p) {
-  using C = Cfg<D, NWAVES>;
+template <int D, int NS>
+__global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(const AttnLaunch p) {
+  using C = Cfg<D, NS>;
   constexpr int BM = C::BM;
   constexpr int KS = D / 16;     // contraction steps of K Q^T
   constexpr int DB = D / 32;     // 32-row blocks of O^T
+  constexpr bool ACC = NS > 1;
 
   __shared__ __attribute__((aligned(16))) unsigned char smem[C::SMEM];   // ring of stages, each a K tile then a V tile
   __shared__ __attribute__((aligned(16))) int s_tok[C::STAGES][BN];   // global position of every key row of a tile (INT_MAX: none)
@@ -147,7 +189,7 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int h = lane >> 5;       // lane half
-  const int lq = lane & 31;      // query column inside the wave
+  const int lq = lane & 31;      // query column inside a strip
 
   // ---- which (KV head, task, query tile, query head) this workgroup owns.  Workgroups are dealt
   // round-robin to the 8 XCDs; the index is remapped so that each XCD gets a contiguous run of work
@@ -208,20 +250,23 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   const int total_keys = e_vbeg[n_eff];
   const int n_tiles = (total_keys + BN - 1) / BN;
 
-  // ---- Q fragments (B operand of K Q^T): lane holds query lq, d = 16 ks + 8 h .. +8
-  const int my_q = q_tile_row0 + wave * 32 + lq;              // row inside the task
-  const bool q_valid = my_q < T.n_q;
-  const int64_t q_row = T.q_row0 + (q_valid ? my_q : T.n_q - 1);
-  bf16x8 qf[KS];
-  {
+  // ---- Q fragments (B operand of K Q^T), strip s: lane holds query 32 s + lq, d = 16 ks + 8 h .. +8
+  int my_q[NS], q_pos[NS];
+  bool q_valid[NS];
+  u32x4 qf[NS][KS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    my_q[s] = q_tile_row0 + wave * (32 * NS) + 32 * s + lq;          // row inside the task
+    q_valid[s] = my_q[s] < T.n_q;
+    const int64_t q_row = T.q_row0 + (q_valid[s] ? my_q[s] : T.n_q - 1);
     const __bf16* src = static_cast<const __bf16*>(p.q) + (q_row * p.Hq + hq) * D + 8 * h;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
+    for (int ks = 0; ks < KS; ++ks) qf[s][ks] = *reinterpret_cast<const u32x4*>(src + 16 * ks);
+    q_pos[s] = p.causal ? T.q_pos0 + my_q[s] : INT_MAX - 1;
   }
-  // Land the Q fragments now (vmcnt(0)); otherwise their pending loads make the compiler wait on
-  // the K/V prefetch of each iteration in front of the first products that read qf.
+  // Land the Q fragments now (vmcnt(0)): the waits for the tile fetches below count vector memory
+  // instructions and assume that nothing else is in flight.
   __builtin_amdgcn_s_waitcnt(0x0F70);
-  const int q_pos = p.causal ? T.q_pos0 + my_q : INT_MAX - 1;
 
   // ---- loader: this thread fills rows fr + RPP*i, unit fu of every K and V tile.  Byte offsets
   // into K and V fit 32 bits (checked on the host).
@@ -230,15 +275,15 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   // Row bookkeeping of the loader.  Each thread follows its PASSES rows through the virtual
   // concatenation: from one tile to the next a row moves 64 keys on and normally stays inside its
   // effective segment (token += 64); only when it runs off the end of the segment is the segment
-  // list searched again.  tokk = global position (INT_MAX: past the last key), flagk = the row
-  // needs the element-wise mask, lefti = keys from the row to the end of its segment.
-  int tokk[C::PASSES], flagk[C::PASSES], segi[C::PASSES], lefti[C::PASSES];
+  // list searched again.  tokk = global position (INT_MAX: past the last key), lefti = keys from
+  // the row to the end of its segment.
+  int tokk[C::PASSES], segi[C::PASSES], lefti[C::PASSES];
   auto relocate = [&](int i, int v) __attribute__((always_inline)) {
     int j = segi[i];
     while (j < n_eff && v >= e_vbeg[j + 1]) ++j;              // rows only move forward
     segi[i] = j;
-    if (j < n_eff) { tokk[i] = v + e_goff[j]; flagk[i] = e_diag[j]; lefti[i] = e_vbeg[j + 1] - v; }
-    else { tokk[i] = INT_MAX; flagk[i] = 1; lefti[i] = 1 << 30; }
+    if (j < n_eff) { tokk[i] = v + e_goff[j]; lefti[i] = e_vbeg[j + 1] - v; }
+    else { tokk[i] = INT_MAX; lefti[i] = 1 << 30; }
   };
   // rows of tile t; must be called for t = 0, 1, 2, ... in this order
   auto locate = [&](int t) __attribute__((always_inline)) {
@@ -265,28 +310,31 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   // tile layout is applied on the source side: the lane that owns LDS slot (row, unit) reads the
   // 16 bytes of column swz(row, unit) of that row.  Rows past the end fetch token 0 and are masked.
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  const unsigned char* Kd = static_cast<const unsigned char*>(p.k) + (static_cast<size_t>(g) * D + C::swz_k(fr, fu) * 8) * 2;
-  const unsigned char* Vd = static_cast<const unsigned char*>(p.v) + (static_cast<size_t>(g) * D + C::swz_v(fr, fu) * 8) * 2;
+  const unsigned char* Kg = static_cast<const unsigned char*>(p.k) + static_cast<size_t>(g) * D * 2;   // this KV head, uniform
+  const unsigned char* Vg = static_cast<const unsigned char*>(p.v) + static_cast<size_t>(g) * D * 2;
+  const unsigned k_col = C::swz_k(fr, fu) * 16, v_col = C::swz_v(fr, fu) * 16;    // byte column this lane reads
   static_assert(C::RPP % 16 == 0, "the swizzle of a thread's rows must not depend on the pass");
   // A tile fetch is 2*PASSES loads per thread.  The path from L2 into LDS takes roughly 25 cycles per
   // wavefront-load and the issuing wave stalls once its queue is full, so the loads are not issued
-  // in one burst: fetch_begin does the bookkeeping, fetch_piece(j) issues load j, and the scores
-  // phase drops one piece between its matrix instructions.
-  unsigned fetch_off[C::PASSES];
+  // in one burst: fetch_begin does the bookkeeping, fetch_piece(j) issues load j, and the loop
+  // drops the pieces between its matrix instructions.
+  unsigned fetch_k[C::PASSES], fetch_v[C::PASSES];   // byte offsets from Kg / Vg
   unsigned char* fetch_dst = smem;
   auto fetch_begin = [&](int t, int stage) __attribute__((always_inline)) {
     locate(t);
     fetch_dst = smem + stage * 2 * C::TILE_BYTES + wave_u * 1024;
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
-      fetch_off[i] = __umul24(tokk[i] == INT_MAX ? 0u : static_cast<unsigned>(tokk[i]), row_bytes);   // both below 2^24 (host check)
-      if (fu == 0) s_tok[stage][fr + C::RPP * i] = tokk[i];
+      const unsigned row_off = __umul24(tokk[i] == INT_MAX ? 0u : static_cast<unsigned>(tokk[i]), row_bytes);   // both below 2^24 (host check)
+      fetch_k[i] = row_off + k_col;
+      fetch_v[i] = row_off + v_col;
+      s_tok[stage][fr + C::RPP * i] = tokk[i];    // the UNITS lanes of a row write the same value
     }
   };
   auto fetch_piece = [&](int j) __attribute__((always_inline)) {
     const int i = j >> 1;
-    if (j & 1) dma16(Vd + fetch_off[i], fetch_dst + C::TILE_BYTES + i * C::LOADERS * 16);
-    else dma16(Kd + fetch_off[i], fetch_dst + i * C::LOADERS * 16);
+    if (j & 1) dma16(Vg, fetch_v[i], fetch_dst + C::TILE_BYTES + i * C::NTHREADS * 16);
+    else dma16(Kg, fetch_k[i], fetch_dst + i * C::NTHREADS * 16);
   };
   auto fetch = [&](int t, int stage) __attribute__((always_inline)) {
     fetch_begin(t, stage);
@@ -299,59 +347,54 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
   };
 
-  // ---- per-lane LDS read offsets (loop invariant)
-  int koff[KS];       // K: row lq (+32 kb), unit 2 ks + h
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) koff[ks] = (lq * C::UNITS + C::swz_k(lq, 2 * ks + h)) * 16;
+  // ---- per-lane LDS read addresses, stage 0 (loop invariant)
   const unsigned smem_lds = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)smem));
-  unsigned kadr[KS];  // the same as LDS addresses, stage 0
+  unsigned kadr[KS];  // K: row lq (+32 kb), unit 2 ks + h
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) kadr[ks] = smem_lds + koff[ks];
+  for (int ks = 0; ks < KS; ++ks) kadr[ks] = smem_lds + (lq * C::UNITS + C::swz_k(lq, 2 * ks + h)) * 16;
   // V^T through the transposing read: 16-lane group a = lane/16 serves d columns 16 (a%2) .. +16 of
   // a 32-wide block for lane half h = a/2; lane jj of the group points at key 4 h + jj/4, 4 d values.
   const int ga = lane >> 4, jj = lane & 15;
   const int vrow = 4 * (ga >> 1) + (jj >> 2);                 // key row inside a 16-key block (+8 second read)
-  int voff[DB];
+  unsigned vadr[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db) {
     const int unit = 4 * db + 2 * (ga & 1) + ((jj & 3) >> 1);
-    voff[db] = (vrow * C::UNITS + C::swz_v(vrow, unit)) * 16 + 8 * (jj & 1);
+    vadr[db] = smem_lds + C::TILE_BYTES + (vrow * C::UNITS + C::swz_v(vrow, unit)) * 16 + 8 * (jj & 1);
   }
-  unsigned vadr[DB];  // LDS addresses inside the V tile of stage 0
-#pragma unroll
-  for (int db = 0; db < DB; ++db) vadr[db] = smem_lds + C::TILE_BYTES + voff[db];
 
-  // S^T = K Q^T of one K tile, reads left to the compiler (used once, before the loop)
-  auto scores = [&](int stage, f32x16 (&s)[2], auto) __attribute__((always_inline)) {
-    const unsigned char* kbase = smem + stage * 2 * C::TILE_BYTES;
+  // ---- running state, per strip
+  f32x16 o[NS][DB];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+  for (int s = 0; s < NS; ++s)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
+      for (int i = 0; i < 16; ++i) o[s][db][i] = 0.f;
+  float m_run[NS], l_run[NS];   // running max in the exp2 domain (scaled scores times log2 e); this lane's share of the running sum
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kbase + kb * 32 * D * 2 + koff[ks]);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
-      }
+  for (int s = 0; s < NS; ++s) { m_run[s] = kNegBig; l_run[s] = 0.f; }
+  const float c = p.scale * kLog2e;
+  auto fence_o = [&]() __attribute__((always_inline)) {
+    fence_o_first<ACC>(o[0][0]);
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        if (s + db > 0) fence_o_next<ACC>(o[s][db]);
   };
 
-  // ---- running state
-  f32x16 o[DB];
+  // a score tile becomes readable by the vector ALU
+  auto fence_scores = [&](f32x16 (&S)[NS][2]) __attribute__((always_inline)) {
+    fence_s(S[0][0], S[0][1]);
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-  float m_run = kNegBig;        // running max in the exp2 domain (scaled scores times log2 e)
-  float l_run = 0.f;            // this lane's share of the running sum
-  const float c = p.scale * kLog2e;
+    for (int s = 1; s < NS; ++s) fence_s_next(S[s][0], S[s][1]);
+  };
 
-  // ---- the three phases of a tile, for one wave
-  // element-wise mask, only for tiles that touch the diagonal or run past the last key
+  // element-wise mask of the scores of tile t, only for tiles that touch the diagonal or run past the last key
   int m_idx = 0;
   int m_cur_lo = __builtin_amdgcn_readfirstlane(m_lo[0]), m_cur_hi = __builtin_amdgcn_readfirstlane(m_hi[0]);
-  auto mask = [&](int t, f32x16 (&s)[2]) __attribute__((always_inline)) {
+  auto mask = [&](int t, f32x16 (&S)[NS][2]) __attribute__((always_inline)) {
     while (t > m_cur_hi) {     // t only grows; the last run never ends
       ++m_idx;
       m_cur_lo = __builtin_amdgcn_readfirstlane(m_lo[m_idx]);
@@ -365,121 +408,192 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
         for (int i4 = 0; i4 < 4; ++i4) {
           const i32x4 tk = *reinterpret_cast<const i32x4*>(&s_tok[stage][32 * kb + 8 * i4 + 4 * h]);
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (tk[e] > q_pos) s[kb][4 * i4 + e] = -__builtin_inff();
+          for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (tk[e] > q_pos[s]) S[s][kb][4 * i4 + e] = -__builtin_inff();
         }
     }
   };
-  // online softmax (exp2 domain): raises the running max lazily, returns P as bf16 B-operand fragments
-  auto softmax = [&](f32x16 (&s)[2], bf16x8 (&pf)[2][2]) __attribute__((always_inline)) {
-    float mx = s[0][0];
-#pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[0][i]);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
-    {
-      // the other half of the keys sits in the lane 32 away
-      const unsigned mu = __builtin_bit_cast(unsigned, mx);
-      const u32x2 sw = __builtin_amdgcn_permlane32_swap(mu, mu, false, false);
-      mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
-    }
-    const float m_cand = fmaxf(m_run, mx * c);
-    if (__builtin_amdgcn_ballot_w64(m_cand > m_run + kRescaleGap) != 0) {
-      const float alpha = fast_exp2(m_run - m_cand);
-      m_run = m_cand;
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-    }
-    float lsum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float pv = fast_exp2(__builtin_fmaf(s[kb][i], c, -m_run));
-        lsum += pv;
-        pf[kb][i >> 3][i & 7] = static_cast<__bf16>(pv);
-      }
-    l_run += lsum;
+  // row maximum of a score tile, in 16 steps per strip
+  float mx[NS];
+  auto max_step = [&](auto ii, f32x16 (&S)[NS][2]) __attribute__((always_inline)) {
+    constexpr int I = decltype(ii)::value;       // strip I % NS, scores 2 (I / NS), 2 (I / NS) + 1 of the 32 a lane holds
+    constexpr int s = I % NS, kb = I / NS / 8, e = 2 * ((I / NS) % 8);
+    if constexpr (I / NS == 0) mx[s] = max2(S[s][kb][e], S[s][kb][e + 1]);
+    else mx[s] = max3(mx[s], S[s][kb][e], S[s][kb][e + 1]);
   };
-  // ---- the matrix instructions of an iteration as one stream of operand fragments: the LDS reads
-  // of the fragment PD positions ahead are issued right after the matrix instruction of a position, so
-  // the reads run through the phase changes (the first fragments of the second product land while
-  // the softmax runs) and into the first products of the next iteration.
+  // after the 16 steps: fold the lane halves, raise the running max lazily (only when it grew by more
+  // than 2^8) and rescale what has been accumulated; the second product of the tile before must be complete
+  auto raise_max = [&]() __attribute__((always_inline)) {
+    float m_cand[NS];
+    bool grew = false;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const unsigned mu = __builtin_bit_cast(unsigned, mx[s]);
+      const u32x2 sw = __builtin_amdgcn_permlane32_swap(mu, mu, false, false);   // the other 16 keys of a block sit 32 lanes away
+      const float m2 = max2(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
+      m_cand[s] = max2(m_run[s], m2 * c);
+      grew |= m_cand[s] > m_run[s] + kRescaleGap;
+    }
+    if (__builtin_amdgcn_ballot_w64(grew) != 0) {
+      fence_o();
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const float alpha = fast_exp2(m_run[s] - m_cand[s]);
+        m_run[s] = m_cand[s];
+        l_run[s] *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[s][db][i] *= alpha;
+          fence_o_written<ACC>(o[s][db]);
+        }
+      }
+    }
+  };
+  // P = exp2(S c - m) for two neighbouring scores of a lane, packed to bf16 into the B-operand
+  // fragment of its 16-key group.  Pair index: group g = PI / 8 (kb = g / 2, j = g % 2), strip (PI % 8) / 4.
+  u32x4 pf[NS][4];
+  float x_even = 0.f;
+  auto exp_one = [&](auto ei, f32x16 (&S)[NS][2]) __attribute__((always_inline)) {
+    constexpr int EI = decltype(ei)::value;      // element: group EI / (8 NS) (kb = g / 2, j = g % 2), strip (EI % (8 NS)) / 8, score EI % 8 of the group
+    constexpr int gg = EI / (8 * NS), s = (EI % (8 * NS)) / 8, e = EI % 8, kb = gg / 2, j = gg % 2;
+    const float x = fast_exp2(__builtin_fmaf(S[s][kb][8 * j + e], c, -m_run[s]));
+    l_run[s] += x;
+    asm volatile("" : "+v"(l_run[s]));           // keeps the addition here instead of in a later block
+    if constexpr (e % 2 == 0) {
+      x_even = x;
+    } else {
+      const bf16x2 pk = {static_cast<__bf16>(x_even), static_cast<__bf16>(x)};
+      pf[s][gg][e / 2] = __builtin_bit_cast(unsigned, pk);
+    }
+  };
+
+  // ---- the matrix instructions of a loop body as one stream of operand fragments: fragments
+  // 0..NKF-1 are K (scores of tile t+1, contraction step f/2, key block f%2), the rest V^T (second
+  // product of tile t, 16-key group and 32-row block of O^T); each feeds the two strips.  The reads
+  // of fragment f+PD are issued when fragment f has been consumed.
+  constexpr int NKF = 2 * KS, NVF = 4 * DB, NF = NKF + NVF;
+  constexpr int NKM = NS * NKF, NVM = NS * NVF;        // matrix instructions per phase
   constexpr int PD = 8;
-  using SeqA = Seq<D, 0>;
-  constexpr int NK = SeqA::NK, NV = SeqA::NV, NOPS = SeqA::NOPS;
-  static_assert(NOPS % PD == 0 && NK >= PD && NV >= PD, "fragment ring must close over an iteration");
-  u32x4 fk[PD];            // K fragments in flight (ring slot = position % PD)
-  u32x2 fl[PD], fh[PD];    // V^T fragments in flight, low and high half
-  // issue the reads of stream position Q (may lie in the next iteration); base_* = ring stage byte offsets of tiles t, t+1
-  auto issue = [&](auto role, auto qq, unsigned base_cur, unsigned base_next) __attribute__((always_inline)) {
-    using S = Seq<D, decltype(role)::value>;
-    constexpr int Q = decltype(qq)::value;
-    constexpr int pos = Q % NOPS, adv = Q / NOPS + S::tile_off(pos), slot = Q % PD, i = S::idx(pos);
-    static_assert(adv <= 1, "only tiles t and t+1 are read");
-    const unsigned base = adv ? base_next : base_cur;
-    if constexpr (S::is_k(pos)) {
-      constexpr int ks = i / 2, kb = i % 2;
-      lds_read_b128<kb * 32 * D * 2>(fk[slot], kadr[ks] + base);
-    } else {
-      constexpr int g = i / DB, db = i % DB;    // 16-key group, 32-row block of O^T
-      lds_read_tr_b64<g * 16 * D * 2>(fl[slot], vadr[db] + base);
-      lds_read_tr_b64<g * 16 * D * 2 + 8 * D * 2>(fh[slot], vadr[db] + base);
-    }
-  };
-  // wait for the fragment of position Q and run its matrix instruction
-  auto exec = [&](auto role, auto qq, f32x16 (&s)[2], const bf16x8 (&pf)[2][2]) __attribute__((always_inline)) {
-    using S = Seq<D, decltype(role)::value>;
-    constexpr int Q = decltype(qq)::value;
-    constexpr int slot = Q % PD, i = S::idx(Q), W = S::younger(Q, PD - 1);
-    if constexpr (S::is_k(Q)) {
-      constexpr int ks = i / 2, kb = i % 2;
-      lds_wait<W>(fk[slot]);
-      const bf16x8 a = __builtin_bit_cast(bf16x8, fk[slot]);
-      if constexpr (ks == 0) {
-        f32x16 z;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) z[e] = 0.f;
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0], z, 0, 0, 0);
-      } else {
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
-      }
-    } else {
-      constexpr int g = i / DB, db = i % DB;
-      lds_wait<W>(fl[slot], fh[slot]);
-      const u32x4 av = {fl[slot][0], fl[slot][1], fh[slot][0], fh[slot][1]};
-      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pf[g / 2][g % 2], o[db], 0, 0, 0);
-    }
-  };
-  // Fragments that cross the loop edge are waited for before the closing barrier, where the wave
-  // waits anyway: a register copy the compiler may place on the loop edge then copies landed data.
-  auto land_k = [&]() __attribute__((always_inline)) {
-    lds_wait<0>(fk[0]);
-    static_for<PD - 1>([&](auto i) __attribute__((always_inline)) { after_wait(fk[decltype(i)::value + 1]); });
-  };
-  auto land_v = [&]() __attribute__((always_inline)) {
-    lds_wait<0>(fl[0], fh[0]);
-    static_for<PD - 1>([&](auto i) __attribute__((always_inline)) { after_wait(fl[decltype(i)::value + 1], fh[decltype(i)::value + 1]); });
-  };
+  static_assert(NKF >= PD && NVF >= PD, "");
   constexpr unsigned STAGE_BYTES = 2 * C::TILE_BYTES;
+  u32x4 fk[PD];            // K fragments in flight (ring slot = fragment % PD)
+  u32x2 fl[PD], fh[PD];    // V^T fragments in flight, low and high half
+  auto issue = [&](auto ff, unsigned base_k, unsigned base_v) __attribute__((always_inline)) {
+    constexpr int F = decltype(ff)::value, slot = F % PD;
+    if constexpr (F < NKF) {
+      constexpr int ks = F / 2, kb = F % 2;
+      lds_read_b128<kb * 32 * D * 2>(fk[slot], kadr[ks] + base_k);
+    } else {
+      constexpr int gg = (F - NKF) / DB, db = (F - NKF) % DB;
+      lds_read_tr_b64<gg * 16 * D * 2>(fl[slot], vadr[db] + base_v);
+      lds_read_tr_b64<gg * 16 * D * 2 + 8 * D * 2>(fh[slot], vadr[db] + base_v);
+    }
+  };
+  // LDS read instructions issued after those of fragment f and before its wait (the counter holds 15)
+  auto younger = [](int f) constexpr {
+    int n = 0;
+    for (int r = f + 1; r < f + PD && r < NF; ++r) n += r < NKF ? 1 : 2;
+    return n < 15 ? n : 15;
+  };
+  // ---- vector work dealt out to the matrix instructions of a body.  A matrix instruction keeps
+  // its pipe busy for 32 cycles; what the wave issues behind it in that time is free, what exceeds
+  // it delays the next one.  The 64 exponentials of a lane (16 per 16-key group, the groups in the
+  // order the second product uses them) are spread as evenly as the order allows: PRE before the
+  // first matrix instruction (its operand is still on its way from LDS), up to EK under the scores,
+  // the rest under the first VE instructions of the second product; the 32 maxima of the next score
+  // tile from its instruction VS on.  The instruction after which a tile-fetch load is issued gets
+  // no vector work: that load can stall the wave for about as long.
+  constexpr int FRAGS_PER_PIECE = NF / (2 * C::PASSES);
+  static_assert(NF % (2 * C::PASSES) == 0, "fetch pieces are spread evenly over the fragments");
+  constexpr int NE = 32 * NS;                           // exponentials per lane and tile
+  constexpr int PRE = 2 * NS, EK = 5 * NE / 8, VE = 3 * NVM / 4, VS = NVM / 4;
+  auto is_fetch_slot = [](int m) constexpr { return m % (NS * FRAGS_PER_PIECE) == NS * FRAGS_PER_PIECE - 1; };
+  auto work_slots = [is_fetch_slot](int m0, int m1) constexpr { int n = 0; for (int m = m0; m < m1; ++m) n += is_fetch_slot(m) ? 0 : 1; return n; };
+  auto vector_slot = [&](auto mm, f32x16 (&S_cur)[NS][2], f32x16 (&S_next)[NS][2]) __attribute__((always_inline)) {
+    constexpr int M = decltype(mm)::value;
+    if constexpr (!is_fetch_slot(M)) {
+      if constexpr (M < NKM) {
+        constexpr int n = work_slots(0, NKM), w = work_slots(0, M);
+        constexpr int lo = PRE + (EK - PRE) * w / n, hi = PRE + (EK - PRE) * (w + 1) / n;
+        static_for<hi - lo>([&](auto i) __attribute__((always_inline)) { exp_one(std::integral_constant<int, lo + decltype(i)::value>{}, S_cur); });
+      } else {
+        if constexpr (M - NKM < VE) {
+          constexpr int n = work_slots(NKM, NKM + VE), w = work_slots(NKM, M);
+          constexpr int lo = EK + (NE - EK) * w / n, hi = EK + (NE - EK) * (w + 1) / n;
+          static_for<hi - lo>([&](auto i) __attribute__((always_inline)) { exp_one(std::integral_constant<int, lo + decltype(i)::value>{}, S_cur); });
+        }
+        if constexpr (M - NKM >= VS) {
+          constexpr int n = work_slots(NKM + VS, NKM + NVM), w = work_slots(NKM + VS, M);
+          constexpr int lo = 16 * NS * w / n, hi = 16 * NS * (w + 1) / n;
+          static_for<hi - lo>([&](auto i) __attribute__((always_inline)) { max_step(std::integral_constant<int, lo + decltype(i)::value>{}, S_next); });
+        }
+      }
+    }
+  };
 
   // ---- main loop over 64-key tiles.  Ring of four LDS stages filled by direct global->LDS loads:
-  // at the barrier that opens iteration t, tiles t and t+1 are complete, tile t+2 is in flight and
-  // the first half of the waves starts the fetch of tile t+3 into the stage tile t-1 has left;
-  // before the barrier that closes the iteration they wait for tile t+2.
+  // at the barrier that opens body t, tiles t and t+1 are complete, tile t+2 is in flight and the
+  // fetch of tile t+3 starts into the stage tile t-1 has left; before the closing barrier every
+  // wave waits for its part of tile t+2.
   //
-  // The two wavefronts that share a SIMD run half an iteration apart: the first goes
-  // scores(t) -> softmax -> accumulate(t), the second softmax -> accumulate(t) -> scores(t+1), so
-  // that one of them has matrix work while the other is in its vector phase.
+  // Body t, entered with the masked scores S(t) and their row maxima (mx):
+  //   first the reads of the first fragments are issued and, while they are on their way, the
+  //   running max is raised if it has to be and the bookkeeping of the next tile fetch is done;
+  //   matrix stream:  S(t+1) = K(t+1) Q^T              then   O^T += V(t)^T P(t)^T
+  //   vector stream:  P(t) = exp2(S(t) c - m), most of it     the rest, mask and row maxima of S(t+1)
+  // Two score tiles alternate, so the loop is unrolled twice; an odd last body runs on a tile past
+  // the end, whose scores are all masked (its exponentials are 0, its maxima -inf).
   constexpr std::integral_constant<int, 1> one_in_flight{};
-  constexpr std::integral_constant<int, 0> role_a{};
-  constexpr std::integral_constant<int, 1> role_b{};
-  constexpr int OPS_PER_PIECE = NOPS / (2 * C::PASSES);
-  static_assert(NOPS % (2 * C::PASSES) == 0, "fetch pieces are spread evenly over the matrix instructions");
-  if (n_tiles > 0 && __builtin_amdgcn_readfirstlane(wave) < NWAVES / 2) {
+  auto body = [&](int t, f32x16 (&S_cur)[NS][2], f32x16 (&S_next)[NS][2]) __attribute__((always_inline)) {
+    const unsigned base_v = (t & 3) * STAGE_BYTES, base_k = ((t + 1) & 3) * STAGE_BYTES;
+    static_for<PD>([&](auto f) __attribute__((always_inline)) { issue(f, base_k, base_v); });
+    raise_max();                                  // of S_cur; also fills the time the first fragments take to arrive
+    fetch_begin(t + 3, (t + 3) & 3);
+    static_for<PRE>([&](auto i) __attribute__((always_inline)) { exp_one(i, S_cur); });
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<NF>([&](auto ff) __attribute__((always_inline)) {
+      constexpr int F = decltype(ff)::value, slot = F % PD, W = younger(F);
+      if constexpr (F < NKF) {
+        constexpr int ks = F / 2, kb = F % 2;
+        lds_wait<W>(fk[slot]);
+        static_for<NS>([&](auto ss) __attribute__((always_inline)) {
+          constexpr int s = decltype(ss)::value;
+          if constexpr (ks == 0) mfma_s_first<ACC>(S_next[s][kb], fk[slot], qf[s][0]);
+          else mfma_s<ACC>(S_next[s][kb], fk[slot], qf[s][ks]);
+          vector_slot(std::integral_constant<int, NS * F + s>{}, S_cur, S_next);
+          __builtin_amdgcn_sched_barrier(0);
+        });
+      } else {
+        constexpr int gg = (F - NKF) / DB, db = (F - NKF) % DB;
+        if constexpr (db == 0) {
+#pragma unroll
+          for (int s = 0; s < NS; ++s) fence_p(pf[s][gg]);
+        }
+        if constexpr (NS * (F - NKF) == VS) {
+          // the scores of tile t+1 are complete (several matrix instructions of the second product lie between)
+          fence_scores(S_next);
+          mask(t + 1, S_next);
+        }
+        lds_wait<W>(fl[slot], fh[slot]);
+        const u32x4 av = {fl[slot][0], fl[slot][1], fh[slot][0], fh[slot][1]};
+        static_for<NS>([&](auto ss) __attribute__((always_inline)) {
+          constexpr int s = decltype(ss)::value;
+          mfma_o<ACC>(o[s][db], av, pf[s][gg]);
+          vector_slot(std::integral_constant<int, NS * F + s>{}, S_cur, S_next);
+          __builtin_amdgcn_sched_barrier(0);
+        });
+      }
+      if constexpr (F + PD < NF) issue(std::integral_constant<int, F + PD>{}, base_k, base_v);
+      if constexpr ((F + 1) % FRAGS_PER_PIECE == 0) fetch_piece((F + 1) / FRAGS_PER_PIECE - 1);
+    });
+    wait_fetches(one_in_flight);
+    __syncthreads();
+  };
+
+  if (n_tiles > 0) {
     fetch(0, 0);
     fetch(1, 1);
     fetch(2, 2);
@@ -488,111 +602,96 @@ __global__ __launch_bounds__(64 * NWAVES, 2) void attn_bf16_kernel(const AttnLau
   __syncthreads();
 
   if (n_tiles > 0) {
-    if (__builtin_amdgcn_readfirstlane(wave) < NWAVES / 2) {
-      static_for<PD>([&](auto q) __attribute__((always_inline)) { issue(role_a, q, 0u, STAGE_BYTES); });
-      land_k();
-      for (int t = 0; t < n_tiles; ++t) {
-        fetch_begin(t + 3, (t + 3) & 3);
-        f32x16 s[2];
-        bf16x8 pf[2][2];
-        const unsigned base_cur = (t & 3) * STAGE_BYTES, base_next = ((t + 1) & 3) * STAGE_BYTES;
-        static_for<NOPS>([&](auto q) __attribute__((always_inline)) {
-          constexpr int Q = decltype(q)::value;
-          exec(role_a, q, s, pf);
-          issue(role_a, std::integral_constant<int, Q + PD>{}, base_cur, base_next);   // into the ring slot just consumed
-          if constexpr ((Q + 1) % OPS_PER_PIECE == 0) fetch_piece((Q + 1) / OPS_PER_PIECE - 1);
-          if constexpr (Q == NK - 1) {
-            mask(t, s);
-            softmax(s, pf);
-          }
-        });
-        wait_fetches(one_in_flight);
-        land_k();
-        __syncthreads();
+    f32x16 Sa[NS][2], Sb[NS][2];
+    // scores, mask and row maxima of tile 0, not pipelined
+    static_for<NKF>([&](auto ff) __attribute__((always_inline)) {
+      constexpr int F = decltype(ff)::value, ks = F / 2, kb = F % 2;
+      u32x4 f;
+      lds_read_b128<kb * 32 * D * 2>(f, kadr[ks]);
+      lds_wait<0>(f);
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        if constexpr (ks == 0) mfma_s_first<ACC>(Sa[s][kb], f, qf[s][0]);
+        else mfma_s<ACC>(Sa[s][kb], f, qf[s][ks]);
       }
-    } else {
-      f32x16 s[2];
-      scores(0, s, std::false_type{});
-      static_for<PD>([&](auto q) __attribute__((always_inline)) { issue(role_b, q, 0u, STAGE_BYTES); });
-      land_v();
-      for (int t = 0; t < n_tiles; ++t) {
-        bf16x8 pf[2][2];
-        mask(t, s);
-        softmax(s, pf);
-        const unsigned base_cur = (t & 3) * STAGE_BYTES, base_next = ((t + 1) & 3) * STAGE_BYTES;
-        static_for<NOPS>([&](auto q) __attribute__((always_inline)) {
-          constexpr int Q = decltype(q)::value;
-          exec(role_b, q, s, pf);     // tile t+1 for the scores; past the last tile that is a fetched dummy tile and is dropped
-          issue(role_b, std::integral_constant<int, Q + PD>{}, base_cur, base_next);
-        });
-        land_v();
-        __syncthreads();
-      }
+    });
+    fence_scores(Sa);
+    mask(0, Sa);
+    static_for<16 * NS>([&](auto i) __attribute__((always_inline)) { max_step(i, Sa); });
+    for (int t = 0; t < n_tiles; t += 2) {
+      body(t, Sa, Sb);
+      body(t + 1, Sb, Sa);
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // no fetch may still be writing LDS when the workgroup ends
+  fence_o();
 
-  // ---- epilogue: normalise and store.  A lane owns one query row; per (db, i4) it holds 4
-  // consecutive output columns, and its partner lane (+32) the next 4, so a wavefront writes
+  // ---- epilogue: normalise and store.  A lane owns one query row per strip; per (db, i4) it holds
+  // 4 consecutive output columns, and its partner lane (+32) the next 4, so a wavefront writes
   // 32-byte pieces of 32 rows per store and the 16 stores of a lane complete its 512-byte row.
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  const bool seen = l_tot > 0.f;
-  const float inv = seen ? 1.f / l_tot : 0.f;
-  float lse_new = seen ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -__builtin_inff();
-  if (q_valid) {
-    const int64_t grow = T.q_row0 + my_q;
-    float* od = p.o_dst + (grow * p.Hq + hq) * D + 4 * h;
-    float* ld = p.lse_dst + grow * p.Hq + hq;
-    float wa = 0.f, wb = inv;
-    if (p.merge) {
-      // update_out_lse of Algorithm 3 folded into the store
-      const float lse_old = *ld;
-      const float mxl = fmaxf(lse_old, lse_new);
-      if (mxl == -__builtin_inff()) {
-        wb = 0.f;
-      } else {
-        const float ea = __expf(lse_old - mxl), eb = __expf(lse_new - mxl);
-        const float rden = 1.f / (ea + eb);
-        wa = ea * rden;
-        wb = eb * rden * inv;
-        lse_new = mxl + __logf(ea + eb);
-      }
-    }
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        f32x4* dst = reinterpret_cast<f32x4*>(od + 32 * db + 8 * i4);
-        f32x4 val;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) val[e] = o[db][4 * i4 + e] * wb;
-        if (p.merge) {
-          const f32x4 old = *dst;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) val[e] = __builtin_fmaf(wa, old[e], val[e]);
+  for (int s = 0; s < NS; ++s) {
+    const float l_tot = l_run[s] + __shfl_xor(l_run[s], 32);
+    const bool seen = l_tot > 0.f;
+    const float inv = seen ? 1.f / l_tot : 0.f;
+    float lse_new = seen ? (m_run[s] + __builtin_amdgcn_logf(l_tot)) * kLn2 : -__builtin_inff();
+    if (q_valid[s]) {
+      const int64_t grow = T.q_row0 + my_q[s];
+      float* od = p.o_dst + (grow * p.Hq + hq) * D + 4 * h;
+      float* ld = p.lse_dst + grow * p.Hq + hq;
+      float wa = 0.f, wb = inv;
+      if (p.merge) {
+        // update_out_lse of Algorithm 3 folded into the store
+        const float lse_old = *ld;
+        const float mxl = fmaxf(lse_old, lse_new);
+        if (mxl == -__builtin_inff()) {
+          wb = 0.f;
+        } else {
+          const float ea = __expf(lse_old - mxl), eb = __expf(lse_new - mxl);
+          const float rden = 1.f / (ea + eb);
+          wa = ea * rden;
+          wb = eb * rden * inv;
+          lse_new = mxl + __logf(ea + eb);
         }
-        *dst = val;
       }
-    if (h == 0) *ld = lse_new;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          f32x4* dst = reinterpret_cast<f32x4*>(od + 32 * db + 8 * i4);
+          f32x4 val;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) val[e] = o[s][db][4 * i4 + e] * wb;
+          if (p.merge) {
+            const f32x4 old = *dst;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) val[e] = __builtin_fmaf(wa, old[e], val[e]);
+          }
+          *dst = val;
+        }
+      if (h == 0) *ld = lse_new;
+    }
   }
 }
 
-template <int D, int NWAVES>
+template <int D, int NS>
 hipError_t launch_variant(const AttnLaunch& p, hipStream_t stream) {
-  constexpr int BM = Cfg<D, NWAVES>::BM;
+  using C = Cfg<D, NS>;
   int64_t tiles = 0;
-  for (int t = 0; t < p.n_tasks; ++t) tiles += (p.task[t].n_q + BM - 1) / BM;
+  for (int t = 0; t < p.n_tasks; ++t) tiles += (p.task[t].n_q + C::BM - 1) / C::BM;
   const int64_t blocks = tiles * p.Hq;
   if (blocks == 0) return hipSuccess;
   if (blocks > INT_MAX) return hipErrorInvalidValue;
-  return TASP_LAUNCH((attn_bf16_kernel<D, NWAVES>), dim3(static_cast<unsigned>(blocks)), dim3(64 * NWAVES), stream, p);
+  return TASP_LAUNCH((attn_bf16_kernel<D, NS>), dim3(static_cast<unsigned>(blocks)), dim3(C::NTHREADS), stream, p);
 }
 
 }  // namespace
 
+// One strip per wavefront (eight wavefronts, two per SIMD) is the faster configuration: with two
+// strips the single wavefront of a SIMD has to issue every instruction itself and is bound by that.
 hipError_t launch_attn_bf16(const AttnLaunch& p, int d, hipStream_t stream) {
-  if (d == 128) return launch_variant<128, 8>(p, stream);
-  if (d == 64) return launch_variant<64, 8>(p, stream);
+  if (d == 128) return launch_variant<128, 1>(p, stream);
+  if (d == 64) return launch_variant<64, 1>(p, stream);
   return hipErrorInvalidValue;
 }
 
