@@ -1,0 +1,99 @@
+"""Static checks on the assembly hipcc generates for the bf16 attention kernel.
+
+The kernel issues its LDS operand reads as inline assembly and waits for them by hand (s_waitcnt
+lgkmcnt(N) placed in front of the matrix instruction that consumes the fragment).  The compiler does
+not know that the destination registers of such a read are still "in flight" after the read has been
+issued; the source keeps them live up to the wait, so a correct build never touches them in between.
+This module re-derives that property from the generated code: it walks the instruction stream, keeps
+the list of LDS instructions that may still be outstanding (LDS instructions of a wavefront complete
+in order, a wait for "at most N outstanding" retires all but the youngest N) and reports every
+instruction that reads or writes a register of an outstanding read.  It also reports register spills.
+"""
+import os
+import re
+import subprocess
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2509_26541_amd", "csrc")
+
+
+def compile_to_asm(source, out_path):
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-S", "--cuda-device-only",
+           "-x", "hip", os.path.join(CSRC, source), "-o", out_path]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stderr[-4000:])
+    with open(out_path) as f:
+        return f.read()
+
+
+def _regs(text):
+    out = set()
+    for m in re.finditer(r"\bv\[(\d+):(\d+)\]", text):
+        out.update(range(int(m.group(1)), int(m.group(2)) + 1))
+    for m in re.finditer(r"(?<![\w\[:])v(\d+)\b", text):
+        out.add(int(m.group(1)))
+    return out
+
+
+def kernels(asm):
+    """{kernel symbol: list of (line number, instruction text)} for every kernel of the module."""
+    out, name = {}, None
+    for i, line in enumerate(asm.split("\n")):
+        m = re.match(r"^(_Z\w+):", line)
+        if m:
+            name = m.group(1)
+            out[name] = []
+            continue
+        if name is None:
+            continue
+        if line.startswith("\t.end_amdhsa_kernel") or line.startswith(".Lfunc_end"):
+            name = None
+            continue
+        s = line.split(";")[0].strip()
+        if not s or s.startswith(".") or s.endswith(":"):
+            continue
+        out[name].append((i + 1, s))
+    return out
+
+
+def in_flight_violations(instructions):
+    """Instructions that touch a register of an LDS read that may not have landed yet."""
+    pending = []          # (destination registers, line) of possibly outstanding LDS instructions, oldest first
+    bad = []
+    for line, s in instructions:
+        op = s.split()[0]
+        operands = s[len(op):].split(",")
+        if op.startswith("ds_read") or op.startswith("ds_bpermute") or op.startswith("ds_permute"):
+            src = set().union(*[_regs(x) for x in operands[1:]]) if len(operands) > 1 else set()
+            for regs, issued in pending:
+                if regs & src:
+                    bad.append((line, s, issued))
+            pending.append((_regs(operands[0]), line))
+            continue
+        if op.startswith("ds_") or op.startswith("s_load") or op.startswith("s_buffer_load") or op == "s_memtime":
+            pending.append((set(), line))      # counts towards lgkmcnt, returns no vector register
+            continue
+        if op == "s_waitcnt":
+            m = re.search(r"lgkmcnt\((\d+)\)", s)
+            if m:
+                n = int(m.group(1))
+                pending = pending[len(pending) - n:] if n > 0 else []
+            elif not re.search(r"(vmcnt|expcnt)\(", s):
+                pending = []                    # numeric form: treat as a full wait
+            continue
+        touched = _regs(s[len(op):])
+        for regs, issued in pending:
+            if regs & touched:
+                bad.append((line, s, issued))
+    return bad
+
+
+def spill_report(asm):
+    """(kernel, vgpr_spill_count, private_segment_fixed_size) per kernel from the metadata block."""
+    out = []
+    for m in re.finditer(r"\.name:\s+(\S+)\n(?:.*\n)*?\s+\.private_segment_fixed_size:\s+(\d+)\n(?:.*\n)*?\s+\.vgpr_spill_count:\s+(\d+)", asm):
+        out.append((m.group(1), int(m.group(3)), int(m.group(2))))
+    return out

@@ -1,0 +1,54 @@
+"""The generated code of the bf16 attention kernel keeps the hand-placed LDS waits valid (CPU only:
+hipcc cross-compiles to assembly without a GPU)."""
+import os
+import shutil
+
+import pytest
+
+from tests import asm_checks
+
+pytestmark = pytest.mark.skipif(shutil.which(os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")) is None,
+                                reason="hipcc not found")
+
+
+@pytest.fixture(scope="module")
+def attn_asm(tmp_path_factory):
+    out = tmp_path_factory.mktemp("asm") / "attn_bf16.s"
+    return asm_checks.compile_to_asm("attn_bf16.hip", str(out))
+
+
+def test_checker_flags_a_planted_violation():
+    ok = [(1, "ds_read_b128 v[4:7], v1 offset:0"), (2, "s_waitcnt lgkmcnt(0)"), (3, "v_mov_b32_e32 v9, v4")]
+    early = [(1, "ds_read_b128 v[4:7], v1 offset:0"), (2, "v_mov_b32_e32 v9, v4"), (3, "s_waitcnt lgkmcnt(0)")]
+    younger = [(1, "ds_read_b128 v[4:7], v1"), (2, "ds_read_b128 v[8:11], v1"), (3, "s_waitcnt lgkmcnt(1)"),
+               (4, "v_add_f32_e32 v0, v4, v5"), (5, "v_add_f32_e32 v0, v8, v9")]
+    assert asm_checks.in_flight_violations(ok) == []
+    assert [b[0] for b in asm_checks.in_flight_violations(early)] == [2]
+    assert [b[0] for b in asm_checks.in_flight_violations(younger)] == [5]
+
+
+def test_attention_kernels_found(attn_asm):
+    ks = asm_checks.kernels(attn_asm)
+    names = [k for k in ks if "attn_bf16_kernel" in k]
+    assert len(names) == 2, names                      # d = 128 and d = 64
+    for k in names:
+        ops = [s.split()[0] for _, s in ks[k]]
+        assert sum(o.startswith("v_mfma_f32_32x32x16_bf16") for o in ops) >= 32
+        assert any(o == "ds_read_b64_tr_b16" for o in ops) and any(o == "ds_read_b128" for o in ops)
+        assert any(o == "global_load_lds_dwordx4" for o in ops)
+
+
+def test_no_register_of_a_pending_lds_read_is_touched(attn_asm):
+    for name, ins in asm_checks.kernels(attn_asm).items():
+        if "attn_bf16_kernel" not in name:
+            continue
+        bad = asm_checks.in_flight_violations(ins)
+        assert bad == [], "%s: %d instructions touch registers of LDS reads still in flight, first: %r" % (
+            name, len(bad), bad[:3])
+
+
+def test_no_spills(attn_asm):
+    rep = [r for r in asm_checks.spill_report(attn_asm) if "attn_bf16_kernel" in r[0]]
+    assert len(rep) == 2
+    for name, spills, scratch in rep:
+        assert spills == 0 and scratch == 0, (name, spills, scratch)
