@@ -4,7 +4,11 @@ A "step" is one whole tasp_chunk_attn call (all N steps of Algorithm 3: step att
 arriving sub-chunks, update_out_lse, final cast) over one batch of seeded synthetic input that is
 already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--fuse-merge 0|1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--fuse-merge 1|0]
+
+The timed call folds update_out_lse into the attention epilogue (fuse_merge, the faster of the two
+modes of the library); the same call with the separate HBM-bound merge kernel is timed next to it
+("other_merge_mode") and provides the merge kernel's GB/s ("merge").
 """
 import argparse
 import json
@@ -69,9 +73,11 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="1..5, the workload list of BASELINE.json")
-    ap.add_argument("--fuse-merge", type=int, default=0)
+    ap.add_argument("--fuse-merge", type=int, default=1)
     ap.add_argument("--order", choices=["tasp", "ring"], default="tasp")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-mode", action="store_true",
+                    help="skip the leg that runs the other merge mode (profiler runs: one kind of launch only)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 256 MiB copy with the library's copy kernel (scales profiler traffic counters)")
     args = ap.parse_args()
@@ -139,8 +145,7 @@ def main():
         "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
         "avg_launch_ms": attn_avg_ms, "launches_per_call": attn_n // n_prof,
     }
-    merge = None
-    if merge_n:
+    def merge_stats(ms_total, launches, calls):
         # update_out_lse: per (row, head) read 2(4d+4) and write 4d+4 bytes; rows merged per call =
         # all rows of every task of steps 1..N-1
         bytes_per_rh = 3 * (4 * w.d + 4)
@@ -149,21 +154,35 @@ def main():
             for qb in range(2 if w.mask_mode == wl.ZIGZAG_CAUSAL else 1):
                 if sched.step_segments(w.S, w.mask_mode, step, qb, order=order):
                     rows_heads += (w.L // (2 if w.mask_mode == wl.ZIGZAG_CAUSAL else 1)) * w.Hq
-        gbs = rows_heads * bytes_per_rh / (merge_ms / n_prof * 1e-3) / 1e9
-        merge = {"bound": "hbm", "kernel": "merge_kernel", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                 "frac": gbs / PEAK_HBM_GBS, "ms_per_call": merge_ms / n_prof, "launches_per_call": merge_n // n_prof}
+        gbs = rows_heads * bytes_per_rh / (ms_total / calls * 1e-3) / 1e9
+        return {"bound": "hbm", "kernel": "merge_kernel", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": gbs / PEAK_HBM_GBS, "ms_per_call": ms_total / calls, "launches_per_call": launches // calls}
 
-    # the same call with update_out_lse folded into the attention epilogue (no partial buffers)
-    alt = tb.ChunkAttnPlan(sched, qd, kd, vd, w.mask_mode, order=order, fuse_merge=not bool(args.fuse_merge))
-    for _ in range(max(1, args.warmup)):
-        alt.run()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        alt.run()
-    torch.cuda.synchronize()
-    alt_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    del alt
+    merge = merge_stats(merge_ms, merge_n, n_prof) if merge_n else None
+
+    # the same call in the other merge mode
+    other = None
+    if not args.no_other_mode:
+        alt = tb.ChunkAttnPlan(sched, qd, kd, vd, w.mask_mode, order=order, fuse_merge=not bool(args.fuse_merge))
+        for _ in range(max(1, args.warmup)):
+            alt.run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            alt.run()
+        torch.cuda.synchronize()
+        alt_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        other = {"fuse_merge": int(not bool(args.fuse_merge)), "ms_per_step": alt_ms,
+                 "value": flops / (alt_ms * 1e-3) / 1e12}
+        if merge is None:
+            a_ms, a_n = 0.0, 0
+            for _ in range(n_prof):
+                pr = alt.profile()
+                a_ms += pr.merge_ms
+                a_n += pr.merge_launches
+            if a_n:
+                merge = merge_stats(a_ms, a_n, n_prof)
+        del alt
 
     value = flops / (ms_per_step * 1e-3) / 1e12
     line = {
@@ -178,8 +197,7 @@ def main():
         "roofline": roofline,
         "merge": merge,
         "ms_breakdown": {"attn": attn_ms / n_prof, "merge": merge_ms / n_prof, "cast": other_ms / n_prof},
-        "other_merge_mode": {"fuse_merge": int(not bool(args.fuse_merge)), "ms_per_step": alt_ms,
-                             "value": flops / (alt_ms * 1e-3) / 1e12},
+        "other_merge_mode": other,
     }
     if not args.no_cpu_baseline:
         del plan, qd, kd, vd
