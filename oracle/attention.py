@@ -85,6 +85,28 @@ def lse_merge(out_a, lse_a, out_b, lse_b):
     return wa[..., None] * out_a + wb[..., None] * out_b, lse
 
 
+def lse_merge_many(outs, lses):
+    """All partial pairs of a row at once: lse = log sum_i exp(lse_i), out = sum_i exp(lse_i - lse) out_i.
+
+    Algorithm 3 folds update_out_lse over the steps one at a time; this is the same quantity written
+    out for N partials (the fold telescopes to it).  outs: sequence of [..., d]; lses: sequence of
+    [...].  Partials with lse = -inf contribute nothing; if all are -inf the result is (0, -inf).
+    """
+    outs = [np.asarray(o, dtype=np.float64) for o in outs]
+    lses = [np.asarray(l, dtype=np.float64) for l in lses]
+    stack = np.stack(lses, axis=0)
+    mx = np.max(stack, axis=0)
+    safe = np.where(np.isfinite(mx), mx, 0.0)
+    den = np.sum(np.exp(stack - safe), axis=0)
+    with np.errstate(divide="ignore"):
+        lse = np.where(np.isfinite(mx), safe + np.log(den), -np.inf)
+    ref = np.where(np.isfinite(lse), lse, 0.0)
+    out = np.zeros_like(outs[0])
+    for o, l in zip(outs, lses):
+        out = out + np.exp(l - ref)[..., None] * o
+    return out, lse
+
+
 def step_tokens(n, rank, S, mask_mode, looping, step):
     """Global key positions a rank holds at `step`, concatenated in ring order (reading A5)."""
     toks = []

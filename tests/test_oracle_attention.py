@@ -121,6 +121,54 @@ def test_merge_with_empty_partials():
     np.testing.assert_allclose(l4, l, atol=0)
 
 
+def test_merge_many_equals_softmax_over_the_union_and_the_fold():
+    """N partials over disjoint key sets: the one-pass form equals the unsplit softmax (library
+    logsumexp / softmax) and the left fold of the pairwise update, in any order of the partials."""
+    d = 6
+    q = rand((1, d), 21)[0]
+    k, v = rand((47, d), 22), rand((47, d), 23)
+    cuts = [0, 5, 6, 19, 19, 30, 47]            # one empty set among them
+    outs, lses = [], []
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        o, l = att.partial_over_tokens(q, 99, k, v, list(range(a, b)), False, 0.9)
+        outs.append(o[None])
+        lses.append(np.array([l]))
+    assert np.isneginf(lses[3][0])
+    o, l = att.lse_merge_many(outs, lses)
+    s = k @ q * 0.9
+    assert abs(l[0] - logsumexp(s)) < 1e-13
+    np.testing.assert_allclose(o[0], softmax(s) @ v, atol=1e-13)
+    fo, fl = outs[0], lses[0]
+    for po, pl in zip(outs[1:], lses[1:]):
+        fo, fl = att.lse_merge(fo, fl, po, pl)
+    np.testing.assert_allclose(o, fo, atol=1e-13)
+    np.testing.assert_allclose(l, fl, atol=1e-13)
+    perm = [4, 0, 5, 2, 3, 1]
+    o2, l2 = att.lse_merge_many([outs[i] for i in perm], [lses[i] for i in perm])
+    np.testing.assert_allclose(o2, o, atol=1e-13)
+    np.testing.assert_allclose(l2, l, atol=1e-13)
+
+
+def test_merge_many_degenerate_cases():
+    d = 4
+    o = rand((3, d), 24)
+    l = np.array([0.3, -2.0, 5.0])
+    z = np.zeros((3, d))
+    ninf = np.full(3, -np.inf)
+    o1, l1 = att.lse_merge_many([o], [l])                       # one partial: unchanged
+    np.testing.assert_array_equal(o1, o)
+    np.testing.assert_array_equal(l1, l)
+    o2, l2 = att.lse_merge_many([z, o, z], [ninf, l, ninf])     # empty partials contribute nothing
+    np.testing.assert_array_equal(o2, o)
+    np.testing.assert_array_equal(l2, l)
+    o3, l3 = att.lse_merge_many([z, z], [ninf, ninf])
+    assert np.all(o3 == 0) and np.all(np.isneginf(l3))
+    # two equal partials: lse grows by ln 2, out unchanged
+    o4, l4 = att.lse_merge_many([o, o], [l, l])
+    np.testing.assert_allclose(o4, o, atol=1e-15)
+    np.testing.assert_allclose(l4, l + math.log(2.0), atol=1e-15)
+
+
 # ---------------------------------------------------------------- Algorithm 3 == dense attention
 TINY = [(4, 24, 2, 1), (8, 112, 2, 2), (8, 224, 4, 2), (12, 264, 1, 1)]
 
