@@ -184,6 +184,40 @@ def main():
                 merge = merge_stats(a_ms, a_n, n_prof)
         del alt
 
+    def event_ms(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    # what the matrix pipe of this box sustains with nothing else in the loop (clock under load included)
+    calib_flops = tb.tasp_calibration_mfma(2000)
+    mfma_peak = calib_flops / (event_ms(lambda: tb.tasp_calibration_mfma(2000), 3) * 1e-3) / 1e12
+
+    # N partial pairs merged in one pass against the fold of the pairwise kernel (same buffers)
+    merge_many = None
+    if not args.no_other_mode:
+        n_parts = w.n_ranks
+        po = [torch.randn((w.L, w.Hq, w.d), dtype=torch.float32, device=dev) for _ in range(n_parts)]
+        pl = [torch.randn((w.L, w.Hq), dtype=torch.float32, device=dev) for _ in range(n_parts)]
+        oo, ol = torch.empty_like(po[0]), torch.empty_like(pl[0])
+        unit = w.L * w.Hq * (4 * w.d + 4)
+
+        def fold():
+            for i in range(1, n_parts):
+                tb.tasp_lse_merge(po[0], pl[0], po[i], pl[i])
+
+        many_ms = event_ms(lambda: tb.tasp_lse_merge_many(po, pl, oo, ol), 3)
+        fold_ms = event_ms(fold, 3)
+        merge_many = {"n_parts": n_parts, "ms": many_ms, "GB/s": (n_parts + 1) * unit / (many_ms * 1e-3) / 1e9,
+                      "pairwise_fold_ms": fold_ms, "pairwise_fold_GB/s": 3 * (n_parts - 1) * unit / (fold_ms * 1e-3) / 1e9}
+        del po, pl, oo, ol
+
     value = flops / (ms_per_step * 1e-3) / 1e12
     line = {
         "metric": "per-rank chunked-attention TFLOP/s on 1 MI355X", "value": value, "unit": "TFLOP/s",
@@ -191,6 +225,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if is_bf16 else "f32", "data": "synthetic",
         "frac_of_bf16_mfma_peak": value / PEAK_BF16_TFLOPS if is_bf16 else None,
+        "measured_mfma_only": {"value": mfma_peak, "unit": "TFLOP/s", "frac_of_it": value / mfma_peak if is_bf16 else None,
+                               "what": "tasp_calibration_mfma: only v_mfma_f32_32x32x16_bf16, operands in registers"},
         "config": {"workload": w.name, "n_ranks": w.n_ranks, "rank": w.rank, "S": w.S, "L": w.L, "Hq": w.Hq,
                    "Hkv": w.Hkv, "d": w.d, "mask": "zigzag_causal" if w.mask_mode else "full",
                    "order": args.order, "fuse_merge": int(args.fuse_merge), "flops_per_call": flops},
@@ -198,6 +234,7 @@ def main():
         "merge": merge,
         "ms_breakdown": {"attn": attn_ms / n_prof, "merge": merge_ms / n_prof, "cast": other_ms / n_prof},
         "other_merge_mode": other,
+        "merge_many": merge_many,
     }
     if not args.no_cpu_baseline:
         del plan, qd, kd, vd

@@ -171,10 +171,30 @@ int tasp_step_attn(const tasp_schedule_t* s, const tasp_attn_args* a, int32_t st
 int tasp_lse_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
                    int64_t rows, int32_t heads, int32_t d, void* hip_stream);
 
+/* All partial pairs of Algorithm 3 merged in one pass instead of N-1 applications of
+ * update_out_lse (the fold telescopes to this):
+ *   lse = log(sum_i exp(lse_i)),   o = sum_i exp(lse_i - lse) * o_i
+ * o_parts / lse_parts: HOST arrays of n_parts DEVICE pointers, o_parts[i] -> [rows, heads, d] fp32
+ * (16-byte aligned), lse_parts[i] -> [rows, heads] fp32; they are read during the call only.
+ * o_out / lse_out: device, same shapes; they may alias one of the partials (every (row, head) is
+ * read completely before it is written).  1 <= n_parts <= TASP_MAX_MERGE_PARTS, d as for
+ * tasp_lse_merge.  Partials with lse = -inf contribute nothing; all -inf gives o = 0, lse = -inf.
+ * HBM traffic per (row, head): (n_parts + 1)(4d + 4) bytes against 3 (n_parts - 1)(4d + 4) for the fold. */
+#define TASP_MAX_MERGE_PARTS 64
+int tasp_lse_merge_many(float* o_out, float* lse_out, const float* const* o_parts, const float* const* lse_parts,
+                        int32_t n_parts, int64_t rows, int32_t heads, int32_t d, void* hip_stream);
+
 /* Plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned) by
  * a streaming kernel of this library.  Not part of the method: it gives profilers a transfer of
  * known size with which to scale their HBM traffic counters. */
 int tasp_calibration_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
+/* Runs `iters` x 32 independent v_mfma_f32_32x32x16_bf16 per wavefront on 2048 workgroups of 8
+ * wavefronts (pseudo-random operands of magnitude about one in registers, nothing else in the loop) and stores the number of floating
+ * point operations that is in *flops (host pointer, may be NULL).  Not part of the method: timed by
+ * the caller it gives the rate the matrix pipe of this GPU sustains at the clock it runs at under
+ * load, next to which a fraction of the published peak can be read.  iters in [1, 1 << 20]. */
+int tasp_calibration_mfma(int32_t iters, double* flops, void* hip_stream);
 
 /* Algorithmic work of one tasp_chunk_attn call: 4*d*Hq*(visible (query,key) pairs). */
 double tasp_chunk_attn_flops(const tasp_schedule_t* s, const tasp_attn_args* a);

@@ -25,6 +25,7 @@ EXPORTS = [
     "tasp_schedule_out_mapping", "tasp_schedule_in_mapping", "tasp_schedule_arrival", "tasp_subchunk_ranges",
     "tasp_step_segments", "tasp_chunk_attn_workspace_bytes", "tasp_chunk_attn", "tasp_step_attn",
     "tasp_lse_merge", "tasp_chunk_attn_flops", "tasp_chunk_attn_profile", "tasp_last_hip_error", "tasp_calibration_copy",
+    "tasp_lse_merge_many", "tasp_calibration_mfma",
 ]
 
 
@@ -86,6 +87,9 @@ def _load():
     lib.tasp_lse_merge.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                    C.c_int32, C.c_void_p]
     lib.tasp_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.tasp_lse_merge_many.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32,
+                                        C.c_int64, C.c_int32, C.c_int32, C.c_void_p]
+    lib.tasp_calibration_mfma.argtypes = [C.c_int32, C.POINTER(C.c_double), C.c_void_p]
     lib.tasp_chunk_attn_flops.argtypes = [C.c_void_p, C.POINTER(AttnArgs)]
     lib.tasp_chunk_attn_flops.restype = C.c_double
     return lib
@@ -232,6 +236,41 @@ def tasp_calibration_copy(dst, src):
     s = torch.cuda.current_stream().cuda_stream
     _check(lib.tasp_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, C.c_void_p(s)), "tasp_calibration_copy")
     return dst
+
+
+def tasp_calibration_mfma(iters):
+    """Launches the matrix-pipe calibration kernel on the current stream; returns its flop count."""
+    torch = _torch()
+    flops = C.c_double(0.0)
+    s = torch.cuda.current_stream().cuda_stream
+    _check(lib.tasp_calibration_mfma(int(iters), C.byref(flops), C.c_void_p(s)), "tasp_calibration_mfma")
+    return flops.value
+
+
+def tasp_lse_merge_many(o_parts, lse_parts, o_out=None, lse_out=None):
+    """All partial pairs merged in one pass.  o_parts: list of fp32 device tensors [rows, heads, d],
+    lse_parts: list of [rows, heads]; returns (o_out, lse_out) (allocated if not given)."""
+    torch = _torch()
+    n = len(o_parts)
+    if n == 0 or n != len(lse_parts):
+        raise ValueError("equally many out and lse partials, at least one")
+    for t in list(o_parts) + list(lse_parts):
+        if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+            raise ValueError("contiguous fp32 device tensors expected")
+    rows, heads, d = o_parts[0].shape
+    for o, l in zip(o_parts, lse_parts):
+        if tuple(o.shape) != (rows, heads, d) or tuple(l.shape) != (rows, heads):
+            raise ValueError("all partials must have the same shape")
+    if o_out is None:
+        o_out = torch.empty_like(o_parts[0])
+    if lse_out is None:
+        lse_out = torch.empty_like(lse_parts[0])
+    op = (C.c_void_p * n)(*[t.data_ptr() for t in o_parts])
+    lp = (C.c_void_p * n)(*[t.data_ptr() for t in lse_parts])
+    s = torch.cuda.current_stream().cuda_stream
+    _check(lib.tasp_lse_merge_many(o_out.data_ptr(), lse_out.data_ptr(), op, lp, n, rows, heads, d, C.c_void_p(s)),
+           "tasp_lse_merge_many")
+    return o_out, lse_out
 
 
 def tasp_lse_merge(o_acc, lse_acc, o_part, lse_part):

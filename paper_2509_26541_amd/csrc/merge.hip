@@ -46,6 +46,41 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(float* __restrict_
   }
 }
 
+// N partials in one pass.  The pointers travel in the kernel argument block.
+struct ManyParts {
+  const float* o[TASP_MAX_MERGE_PARTS];
+  const float* lse[TASP_MAX_MERGE_PARTS];
+};
+
+__global__ __launch_bounds__(MERGE_THREADS) void merge_many_kernel(float* __restrict__ o_out, float* __restrict__ lse_out,
+                                                                  const ManyParts parts, int32_t n_parts, int64_t n4,
+                                                                  int32_t pieces) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * MERGE_THREADS;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * MERGE_THREADS + threadIdx.x; i < n4; i += stride) {
+    const int64_t rh = i / pieces;
+    float mx = -__builtin_inff();
+    for (int p = 0; p < n_parts; ++p) mx = fmaxf(mx, parts.lse[p][rh]);
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    float den = 0.f;
+    if (mx != -__builtin_inff()) {
+      for (int p = 0; p < n_parts; ++p) {
+        const float w = __expf(parts.lse[p][rh] - mx);        // the second read of lse hits the cache
+        const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(parts.o[p]) + i);
+        den += w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(w, b[e], acc[e]);
+      }
+      const float rden = 1.f / den;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[e] *= rden;
+    }
+    reinterpret_cast<f32x4*>(o_out)[i] = acc;
+    // all pieces of a (row, head) sit in one wavefront (d/4 divides 64): every lane has read its lse
+    // values before this store, so lse_out may alias a partial
+    if (i - rh * pieces == 0) lse_out[rh] = mx != -__builtin_inff() ? mx + __logf(den) : mx;
+  }
+}
+
 __global__ __launch_bounds__(MERGE_THREADS) void fill_empty_kernel(float* __restrict__ o, float* __restrict__ lse,
                                                                   int64_t n4, int32_t pieces) {
   const int64_t stride = static_cast<int64_t>(gridDim.x) * MERGE_THREADS;
@@ -118,6 +153,29 @@ extern "C" int tasp_calibration_copy(void* dst, const void* src, size_t bytes, v
   const hipError_t e = TASP_LAUNCH(tasp::copy_kernel, dim3(tasp::grid_for(n4)), dim3(tasp::MERGE_THREADS),
                                    static_cast<hipStream_t>(hip_stream), static_cast<const tasp::f32x4*>(src),
                                    static_cast<tasp::f32x4*>(dst), n4);
+  return e == hipSuccess ? TASP_OK : TASP_EHIP;
+}
+
+extern "C" int tasp_lse_merge_many(float* o_out, float* lse_out, const float* const* o_parts,
+                                   const float* const* lse_parts, int32_t n_parts, int64_t rows, int32_t heads,
+                                   int32_t d, void* hip_stream) {
+  if (rows < 0 || heads <= 0 || d <= 0 || n_parts < 1 || n_parts > TASP_MAX_MERGE_PARTS) return TASP_EINVAL;
+  if (d < 4 || d > 256 || (d & (d - 1)) != 0) return TASP_EUNSUPPORTED_SHAPE;
+  if (rows == 0) return TASP_OK;
+  if (o_out == nullptr || lse_out == nullptr || o_parts == nullptr || lse_parts == nullptr) return TASP_EINVAL;
+  tasp::ManyParts parts{};
+  uintptr_t bits16 = reinterpret_cast<uintptr_t>(o_out), bits4 = reinterpret_cast<uintptr_t>(lse_out);
+  for (int p = 0; p < n_parts; ++p) {
+    if (o_parts[p] == nullptr || lse_parts[p] == nullptr) return TASP_EINVAL;
+    parts.o[p] = o_parts[p];
+    parts.lse[p] = lse_parts[p];
+    bits16 |= reinterpret_cast<uintptr_t>(o_parts[p]);
+    bits4 |= reinterpret_cast<uintptr_t>(lse_parts[p]);
+  }
+  if ((bits16 & 15) || (bits4 & 3)) return TASP_EALIGN;
+  const int64_t n4 = rows * heads * (d / 4);
+  const hipError_t e = TASP_LAUNCH(tasp::merge_many_kernel, dim3(tasp::grid_for(n4)), dim3(tasp::MERGE_THREADS),
+                                   static_cast<hipStream_t>(hip_stream), o_out, lse_out, parts, n_parts, n4, d / 4);
   return e == hipSuccess ? TASP_OK : TASP_EHIP;
 }
 

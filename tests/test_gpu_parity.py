@@ -150,6 +150,48 @@ def test_lse_merge_kernel(tb):
     assert max_abs(t[1].cpu().numpy(), ref_l) <= 1e-5 and max_abs(t[0].cpu().numpy(), ref_o) <= 1e-5
 
 
+def test_lse_merge_many_kernel(tb):
+    """One pass over N partials against the oracle's closed form; also in place on the first partial
+    and against the fold of the pairwise kernel."""
+    rng = np.random.default_rng(12)
+    for rows, heads, d, n in [(301, 5, 128, 8), (33, 3, 64, 3), (7, 2, 128, 1), (64, 4, 128, 16)]:
+        os_ = [rng.standard_normal((rows, heads, d)) for _ in range(n)]
+        ls = [rng.standard_normal((rows, heads)) * 6 for _ in range(n)]
+        for i in range(n):
+            ls[i][i::(n + 2)] = -np.inf                # empty partials here and there
+            os_[i][np.isneginf(ls[i])] = 0
+        for l in ls:
+            l[5 % rows] = -np.inf                      # a row no partial has seen
+        for o in os_:
+            o[5 % rows] = 0
+        ls[0][2 % rows, 0] = 70.0                      # one partial dominates
+        to = [torch.tensor(x, dtype=torch.float32).cuda() for x in os_]
+        tl = [torch.tensor(x, dtype=torch.float32).cuda() for x in ls]
+        ref_o, ref_l = att.lse_merge_many([x.cpu().double().numpy() for x in to], [x.cpu().double().numpy() for x in tl])
+        got_o, got_l = tb.tasp_lse_merge_many(to, tl)
+        torch.cuda.synchronize()
+        go, gl = got_o.cpu().numpy(), got_l.cpu().numpy()
+        assert np.array_equal(np.isneginf(gl), np.isneginf(ref_l))
+        assert np.isneginf(gl[5 % rows]).all() and np.all(go[5 % rows] == 0)
+        assert max_abs(gl, ref_l) <= 1e-5 and max_abs(go, ref_o) <= 1e-5
+        # the fold of the pairwise kernel gives the same up to rounding
+        fo, fl = to[0].clone(), tl[0].clone()
+        for i in range(1, n):
+            tb.tasp_lse_merge(fo, fl, to[i], tl[i])
+        torch.cuda.synchronize()
+        assert max_abs(fl.cpu().numpy(), gl) <= 2e-5 and max_abs(fo.cpu().numpy(), go) <= 2e-5
+        # in place on the first partial
+        tb.tasp_lse_merge_many(to, tl, o_out=to[0], lse_out=tl[0])
+        torch.cuda.synchronize()
+        assert np.array_equal(to[0].cpu().numpy(), go) and np.array_equal(tl[0].cpu().numpy(), gl)
+
+
+def test_calibration_mfma_runs(tb):
+    flops = tb.tasp_calibration_mfma(10)
+    torch.cuda.synchronize()
+    assert flops == 2048 * 8 * 10 * 32 * 32768.0
+
+
 # ------------------------------------------------------------------ full-size configs, sampled rows
 FULL_SIZE = [(1, 24, 96), (2, 16, 48), (3, 12, 32), (4, 8, 24)]
 

@@ -169,6 +169,20 @@ def test_error_codes():
     assert tb.lib.tasp_lse_merge(4096, 4096, 4096, 4096, 4, 2, 24, None) == tb.EUNSUPPORTED_SHAPE
     assert tb.lib.tasp_lse_merge(4096, 4096, 4104, 4096, 4, 2, 64, None) == tb.EALIGN
     assert tb.lib.tasp_lse_merge(None, None, None, None, 0, 2, 64, None) == tb.OK
+    two = (C.c_void_p * 2)(4096, 8192)
+    odd = (C.c_void_p * 2)(4096, 8200)
+    hole = (C.c_void_p * 2)(4096, None)
+    many = tb.lib.tasp_lse_merge_many
+    assert many(4096, 4096, two, two, 0, 4, 2, 64, None) == tb.EINVAL                    # no partial
+    assert many(4096, 4096, two, two, 65, 4, 2, 64, None) == tb.EINVAL                   # more than the maximum
+    assert many(4096, 4096, None, two, 2, 4, 2, 64, None) == tb.EINVAL
+    assert many(None, 4096, two, two, 2, 4, 2, 64, None) == tb.EINVAL
+    assert many(4096, 4096, hole, two, 2, 4, 2, 64, None) == tb.EINVAL
+    assert many(4096, 4096, two, two, 2, 4, 2, 48, None) == tb.EUNSUPPORTED_SHAPE
+    assert many(4096, 4096, odd, two, 2, 4, 2, 64, None) == tb.EALIGN
+    assert many(None, None, None, None, 2, 0, 2, 64, None) == tb.OK                      # no rows: nothing to do
+    assert tb.lib.tasp_calibration_mfma(0, None, None) == tb.EINVAL
+    assert tb.lib.tasp_calibration_mfma((1 << 20) + 1, None, None) == tb.EINVAL
 
 
 def test_flops_and_workspace():
