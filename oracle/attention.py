@@ -112,12 +112,12 @@ def step_tokens(n, rank, S, mask_mode, looping, step):
     toks = []
     arrival = sch.arrival_table(looping, rank)[step]
     for ring, src in enumerate(arrival):
-        for a, b in sch.subchunk_ranges(n, S, mask_mode, ring, src):
+        for a, b in sch.subchunk_ranges(n, S, mask_mode, ring, src, n_rings=len(looping)):
             toks.extend(range(a, b))
     return toks
 
 
-def stepwise_rows(q_rows, positions, k, v, n, rank, mask_mode, step_order=None, scale=None):
+def stepwise_rows(q_rows, positions, k, v, n, rank, mask_mode, step_order=None, scale=None, looping=None):
     """Algorithm 3 for a few local rows of one head: N partials folded left to right.
 
     Returns (out, lse, partials) where partials[s] = (out_s, lse_s) of every step.
@@ -129,7 +129,7 @@ def stepwise_rows(q_rows, positions, k, v, n, rank, mask_mode, step_order=None, 
     S = k.shape[0]
     scale = 1.0 / math.sqrt(d) if scale is None else scale
     causal = mask_mode == sch.ZIGZAG_CAUSAL
-    looping = sch.hamilton_rings(n)
+    looping = sch.hamilton_rings(n) if looping is None else looping      # any ring table over the n ranks
     order = list(range(n)) if step_order is None else list(step_order)
     out = np.zeros((R, d))
     lse = np.full((R,), -np.inf)

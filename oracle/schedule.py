@@ -5,6 +5,8 @@ What is written here
 * ``hamilton_rings(n)``      -- the K_n-decomposition of Sec. 3.1.2, Algorithm 1: the complete
                                directed graph on n ranks split into n-1 directed Hamiltonian cycles
                                ("orthogonal ring datapaths", Sec. 3.1.1, eq. (2)).
+* ``multinode_rings(m, u)``  -- the (m-K_m-m)^u-decomposition of Sec. 3.1.3: u nodes of m ranks, each K_m
+                               cut into m Hamiltonian paths that are chained through the nodes.
 * ``routing_table``          -- Algorithm 2 (in / out mapping).
 * ``simulate_allgather``     -- the Multi-Ring AllGather of Sec. 3.2.2 / Fig. 4 played hop by hop.
 * ``arrival_table``          -- the same thing in closed form for one rank.
@@ -23,6 +25,11 @@ Readings taken where the paper leaves a gap (each is pinned by tests/test_oracle
   R5  Sub-chunk bounds use floors: piece i of a length-len block is [i*len//m, (i+1)*len//m).
   R6  Eq. (5), (6) are read with the index (n-1)*j+i (piece i of half-chunk j) and its mirror
       image; the printed index 2nj+i does not tile the sequence.
+  R8  Sec. 3.1.3 gives the multi-node scheme in words only.  It is read as: the paths of a node are
+      GetPath(m) (the same row-complete Latin square, m even) on that node's ranks c*m .. c*m+m-1;
+      ring i is path i of node 0, then path i of node 1, ... and closes from the last node back to
+      node 0 (the induction of Sec. 3.1.3 inserts node u between node u-1 and node 0).  There are m
+      rings, so a chunk is cut in m sub-chunks instead of n-1.
   R7  n=4 admits no decomposition (Algorithm 1 requires n>=8); three Hamiltonian rings with the
       least possible arc overlap are used instead, the lexicographically smallest such triple.
 """
@@ -96,6 +103,20 @@ def _least_overlap_rings_k4():
 
 
 # ----------------------------------------------------------------------------------------------
+# Sec. 3.1.3: (m-K_m-m)^u-decomposition
+# ----------------------------------------------------------------------------------------------
+def multinode_rings(m, u):
+    """m rings over the m*u ranks of u nodes (reading R8).  Inside a node a ring follows one of the
+    m Hamiltonian paths of K_m; the last rank of the path sends to the first rank of the same path
+    in the next node, so every rank uses its link to another node once for sending and once for
+    receiving."""
+    if m < 2 or m % 2 or u < 2:
+        raise ValueError("m even and >= 2, u >= 2")
+    paths = get_path(m)
+    return [[c * m + v for c in range(u) for v in paths[i]] for i in range(m)]
+
+
+# ----------------------------------------------------------------------------------------------
 # Algorithm 2
 # ----------------------------------------------------------------------------------------------
 def routing_table(looping, d):
@@ -165,10 +186,11 @@ def piece(i, length, m):
     return (i * length) // m, ((i + 1) * length) // m
 
 
-def subchunk_ranges(n, S, mask_mode, ring, src):
+def subchunk_ranges(n, S, mask_mode, ring, src, n_rings=None):
     """Global token ranges [start, end) of sub-chunk t[ring, src]; one range for FULL (eq. (3) cut
-    in n-1 pieces), two for ZIGZAG_CAUSAL (eq. (5) and its mirror image eq. (6))."""
-    m = n - 1
+    in n-1 pieces), two for ZIGZAG_CAUSAL (eq. (5) and its mirror image eq. (6)).  With a ring table
+    of another size (reading R8) a chunk is cut in n_rings pieces."""
+    m = n - 1 if n_rings is None else n_rings
     if mask_mode == FULL:
         if S % n:
             raise ValueError("S must be a multiple of n")
@@ -206,6 +228,38 @@ def arc_loads(looping):
             a = (ring[j], ring[(j + 1) % n])
             load[a] = load.get(a, 0) + 1
     return load
+
+
+def is_path_decomposition(paths):
+    """m Hamiltonian paths on m vertices in which every ordered pair of distinct vertices is adjacent
+    exactly once (all arcs of K_m), and every vertex stands once in every position."""
+    m = len(paths)
+    if not all(sorted(p) == list(range(m)) for p in paths):
+        return False
+    arcs = [(p[j], p[j + 1]) for p in paths for j in range(m - 1)]
+    if len(set(arcs)) != m * (m - 1):
+        return False
+    return all(sorted(p[j] for p in paths) == list(range(m)) for j in range(m))
+
+
+def is_multinode_scheme(looping, m, u):
+    """What Sec. 3.1.3 asks of the (m-K_m-m)^u scheme, checked from the rings alone: m Hamiltonian
+    cycles on m*u ranks; inside every node each of the m(m-1) arcs is used exactly once; every rank
+    sends to another node exactly once and receives from another node exactly once; a ring leaves a
+    node only for the next one."""
+    n = m * u
+    if len(looping) != m or not all(is_hamiltonian_cycle(r, n) for r in looping):
+        return False
+    load = arc_loads(looping)
+    if max(load.values()) != 1:
+        return False
+    intra = [(a, b) for (a, b) in load if a // m == b // m]
+    inter = [(a, b) for (a, b) in load if a // m != b // m]
+    if len(intra) != u * m * (m - 1) or len(inter) != n:
+        return False
+    if sorted(a for a, _ in inter) != list(range(n)) or sorted(b for _, b in inter) != list(range(n)):
+        return False
+    return all(b // m == (a // m + 1) % u for a, b in inter)
 
 
 def is_decomposition(looping):

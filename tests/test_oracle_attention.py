@@ -193,6 +193,23 @@ def test_blockwise_merge_identity_all_ranks(n, S, Hq, Hkv, mode):
             assert np.all(np.isfinite(l))                         # every row sees itself at step 0
 
 
+@pytest.mark.parametrize("m,u,S", [(4, 2, 112), (2, 3, 60), (8, 2, 160)])
+@pytest.mark.parametrize("mode", [sch.FULL, sch.ZIGZAG_CAUSAL])
+def test_blockwise_merge_identity_multinode_rings(m, u, S, mode):
+    """The same identity over the m rings of the (m-K_m-m)^u scheme (m sub-chunks per chunk)."""
+    n, d = m * u, 8
+    rings = sch.multinode_rings(m, u)
+    k, v = rand((S, d), 400 + n), rand((S, d), 500 + n)
+    for rank in (0, m - 1, n - 1):
+        pos = sch.local_positions(n, rank, S, mode)
+        q = rand((len(pos), d), 600 + rank)
+        ref_o, ref_l = att.dense_rows(q, pos, k, v, mode == sch.ZIGZAG_CAUSAL)
+        o, l, partials = att.stepwise_rows(q, pos, k, v, n, rank, mode, looping=rings)
+        np.testing.assert_allclose(o, ref_o, rtol=0, atol=1e-12)
+        np.testing.assert_allclose(l, ref_l, rtol=0, atol=1e-12)
+        assert len(partials) == n
+
+
 def test_step_order_does_not_matter():
     n, S, d = 8, 112, 8
     rank = 3

@@ -172,6 +172,101 @@ def test_k_8x2_link_counts():
     assert 800 / (8 * 2) == 50
 
 
+# ---------------------------------------------------------------- Sec. 3.1.3 (m-K_m-m)^u scheme
+MULTINODE = [(2, 2), (4, 2), (8, 2), (8, 3), (8, 4), (6, 5), (16, 2), (32, 2)]
+
+
+@pytest.mark.parametrize("m", [2, 4, 6, 8, 10, 16, 32])
+def test_node_paths_decompose_k_m(m):
+    assert sch.is_path_decomposition(sch.get_path(m))
+    bad = sch.get_path(m)
+    bad[0] = list(reversed(bad[0]))                                  # a reversed path repeats arcs of others
+    assert m == 2 or not sch.is_path_decomposition(bad)
+
+
+@pytest.mark.parametrize("m,u", MULTINODE)
+def test_multinode_scheme_properties(m, u):
+    """Sec. 3.1.3 from the rings alone: Hamiltonian cycles, every arc inside a node used once, every
+    rank's link to another node used once each way, and the AllGather properties of Sec. 3.2.2."""
+    rings = sch.multinode_rings(m, u)
+    n = m * u
+    assert len(rings) == m and all(len(r) == n for r in rings)
+    assert sch.is_multinode_scheme(rings, m, u)
+    arcs = [a for ring in rings for a in arcs_of(ring)]
+    assert sum(1 for a, b in arcs if a // m == b // m) == u * m * (m - 1)
+    assert sum(1 for a, b in arcs if a // m != b // m) == 2 * m * u // 2   # one per rank: all NICs busy
+    held = sch.simulate_allgather(rings)                             # asserts zero-copy at every hop
+    for rank in range(n):
+        table = sch.arrival_table(rings, rank)
+        assert table == [held[s][rank] for s in range(n)]
+        assert table[0] == [rank] * m
+        for i in range(m):                                           # accessibility
+            assert sorted(table[s][i] for s in range(n)) == list(range(n))
+
+
+def test_multinode_8x2_matches_the_figures_of_the_paper():
+    """(8-K_8-8)^2: 8 rings over 16 ranks; 2*8 = 16 links between the nodes, i.e. 800 GB/s of a node's
+    NICs shared by 8 outgoing rings = 50 GB/s per direction each, against 64 GB/s inside a node."""
+    rings = sch.multinode_rings(8, 2)
+    arcs = [a for ring in rings for a in arcs_of(ring)]
+    cross = [(a, b) for a, b in arcs if a // 8 != b // 8]
+    assert len(rings) == 8 and len(cross) == 16
+    assert sorted(a for a, _ in cross) == list(range(16))            # every rank starts or ends a path once
+    intra0 = sum(1 for a, b in arcs if a < 8 and b < 8)
+    assert intra0 == 56 and round(7200 / (intra0 * 2)) == 64
+    assert 800 / (len(cross)) == 50
+    assert abs(1 - 50 / 64.3) < 0.28 + 1e-9                          # "only a 28 % difference"
+
+
+@pytest.mark.parametrize("m,u", [(8, 2), (8, 3), (4, 4)])
+def test_multinode_induction_step(m, u):
+    """Sec. 3.1.3: from u nodes to u+1 by cutting the links last node -> node 0 and routing them
+    through the new node."""
+    small, big = sch.multinode_rings(m, u), sch.multinode_rings(m, u + 1)
+    for i in range(m):
+        a = set(arcs_of(small[i]))
+        b = set(arcs_of(big[i]))
+        removed, added = a - b, b - a
+        assert len(removed) == 1 and len(added) == m + 1             # one link cut, m-1 new inside the node, 2 across
+        (x, y), = removed
+        assert x // m == u - 1 and y // m == 0
+        new_node = [v for v in big[i] if v // m == u]
+        assert sorted(new_node) == list(range(u * m, (u + 1) * m))
+        assert (x, new_node[0]) in added and (new_node[-1], y) in added
+        assert big[i][: m * u] == small[i]
+
+
+def test_multinode_domain_and_planted_mistakes():
+    for m, u in [(3, 2), (8, 1), (0, 2), (7, 3)]:
+        with pytest.raises(ValueError):
+            sch.multinode_rings(m, u)
+    rings = sch.multinode_rings(8, 2)
+    assert not sch.is_multinode_scheme(sch.hamilton_rings(16)[:8], 8, 2)    # K_16 rings cross nodes freely
+    swapped = [list(r) for r in rings]
+    swapped[0][0], swapped[0][1] = swapped[0][1], swapped[0][0]             # repeats an arc of another ring
+    assert not sch.is_multinode_scheme(swapped, 8, 2)
+    same_path = [list(rings[0]) for _ in range(8)]
+    assert not sch.is_multinode_scheme(same_path, 8, 2)
+
+
+@pytest.mark.parametrize("m,u,S", [(8, 2, 16 * 2 * 8 * 3), (4, 2, 8 * 2 * 4 * 5 + 16), (8, 3, 48 * 7)])
+@pytest.mark.parametrize("mode", [sch.FULL, sch.ZIGZAG_CAUSAL])
+def test_multinode_subchunks_tile_the_sequence_once(m, u, S, mode):
+    n = m * u
+    if S % (2 * n):
+        S = S // (2 * n) * (2 * n)
+    seen = []
+    for src in range(n):
+        for ring in range(m):
+            for a, b in sch.subchunk_ranges(n, S, mode, ring, src, n_rings=m):
+                seen.extend(range(a, b))
+    assert sorted(seen) == list(range(S))
+    for src in range(n):                                             # the pieces of a rank are its own chunk
+        own = sorted(t for ring in range(m) for a, b in sch.subchunk_ranges(n, S, mode, ring, src, n_rings=m)
+                     for t in range(a, b))
+        assert own == sorted(sch.local_positions(n, src, S, mode))
+
+
 # ---------------------------------------------------------------- Sec. 3.2.3 placements
 CASES = [(4, 24), (4, 1024), (8, 112), (8, 131072), (16, 524288), (8, 1048576), (12, 264)]
 
