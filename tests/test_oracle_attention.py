@@ -251,7 +251,7 @@ def test_identity_detects_planted_schedule_mistakes(monkeypatch):
 
     real = sch.subchunk_ranges
 
-    def no_mirror(n_, S_, mode_, ring, src):            # drop eq. (6)
+    def no_mirror(n_, S_, mode_, ring, src, n_rings=None):            # drop eq. (6)
         return real(n_, S_, mode_, ring, src)[:1]
     monkeypatch.setattr(sch, "subchunk_ranges", no_mirror)
     o, l, _ = att.stepwise_rows(q, pos, k, v, n, rank, mode)
