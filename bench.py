@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="1..5, the workload list of BASELINE.json")
     ap.add_argument("--fuse-merge", type=int, default=1)
     ap.add_argument("--order", choices=["tasp", "ring"], default="tasp")
+    ap.add_argument("--nodes", type=int, default=0,
+                    help="U > 1: the (m-K_m-m)^U ring scheme for U nodes of N/U ranks (m rings) instead of the N-1 rings of K_N")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-mode", action="store_true",
                     help="skip the leg that runs the other merge mode (profiler runs: one kind of launch only)")
@@ -96,7 +98,10 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
-    sched = tb.tasp_schedule(w.n_ranks, w.rank)
+    if args.nodes > 1:
+        sched = tb.tasp_schedule_multinode(w.n_ranks // args.nodes, args.nodes, w.rank)
+    else:
+        sched = tb.tasp_schedule(w.n_ranks, w.rank)
     order = tb.ORDER_TASP if args.order == "tasp" else tb.ORDER_RING
     plan = tb.ChunkAttnPlan(sched, qd, kd, vd, w.mask_mode, order=order, fuse_merge=bool(args.fuse_merge))
     flops = plan.flops()
@@ -229,7 +234,7 @@ def main():
                                "what": "tasp_calibration_mfma: only v_mfma_f32_32x32x16_bf16, operands in registers"},
         "config": {"workload": w.name, "n_ranks": w.n_ranks, "rank": w.rank, "S": w.S, "L": w.L, "Hq": w.Hq,
                    "Hkv": w.Hkv, "d": w.d, "mask": "zigzag_causal" if w.mask_mode else "full",
-                   "order": args.order, "fuse_merge": int(args.fuse_merge), "flops_per_call": flops},
+                   "order": args.order, "rings": sched.n_rings, "fuse_merge": int(args.fuse_merge), "flops_per_call": flops},
         "roofline": roofline,
         "merge": merge,
         "ms_breakdown": {"attn": attn_ms / n_prof, "merge": merge_ms / n_prof, "cast": other_ms / n_prof},

@@ -64,12 +64,24 @@ typedef struct tasp_schedule tasp_schedule_t;
 int  tasp_schedule_create(int32_t n_ranks, int32_t rank, tasp_schedule_t** out);
 void tasp_schedule_destroy(tasp_schedule_t* s);
 
+/* Sec. 3.1.3, the (m-K_m-m)^u-decomposition for u nodes of m ranks each (N = m*u; the ranks of node
+ * c are c*m .. c*m+m-1): the complete graph of every node is cut into m Hamiltonian paths (the
+ * row-complete Latin square of the zig-zag sequence 0,1,m-1,2,...), and ring i runs through path i
+ * of node 0, path i of node 1, ... and closes from the last node to the first.  It has m rings
+ * instead of N-1: every arc inside a node lies on exactly one ring, every rank sends to the next
+ * node once and receives from the previous node once.  A chunk is cut in m sub-chunks; everything
+ * else (tables, ranges, tasp_chunk_attn) works as with tasp_schedule_create.
+ * ranks_per_node must be even and n_nodes >= 2 (the closing arcs of a single node would repeat arcs
+ * of its paths), N <= 4096; otherwise TASP_EUNSUPPORTED_N (TASP_EINVAL for non-positive arguments
+ * or a rank outside [0, N)). */
+int  tasp_schedule_create_multinode(int32_t ranks_per_node, int32_t n_nodes, int32_t rank, tasp_schedule_t** out);
+
 int32_t tasp_schedule_n_ranks(const tasp_schedule_t* s);
 int32_t tasp_schedule_rank(const tasp_schedule_t* s);
-int32_t tasp_schedule_n_rings(const tasp_schedule_t* s);          /* N-1 */
+int32_t tasp_schedule_n_rings(const tasp_schedule_t* s);          /* R: N-1, or m for the multi-node scheme */
 int32_t tasp_schedule_max_arc_load(const tasp_schedule_t* s);     /* 1: true decomposition, 2: N == 4 */
 
-/* rings[i*N + j], i < N-1, j < N: rank at position j of ring i; data moves from position j to
+/* rings[i*N + j], i < R, j < N: rank at position j of ring i; data moves from position j to
  * position (j+1) % N (Algorithm 1's h_cycles, Algorithm 2's looping matrix). */
 const int32_t* tasp_schedule_rings(const tasp_schedule_t* s);
 /* Algorithm 2.  out_mapping[u*N + v] = ring on which u sends to v; in_mapping[u*N + v] = ring on
@@ -77,7 +89,7 @@ const int32_t* tasp_schedule_rings(const tasp_schedule_t* s);
  * (N == 4 only) the lower ring id is stored. */
 const int32_t* tasp_schedule_out_mapping(const tasp_schedule_t* s);
 const int32_t* tasp_schedule_in_mapping(const tasp_schedule_t* s);
-/* Sec. 3.2.2, Fig. 4.  arrival[s*(N-1) + i] = rank at which the sub-chunk t[i, .] that this rank
+/* Sec. 3.2.2, Fig. 4.  arrival[s*R + i] = rank at which the sub-chunk t[i, .] that this rank
  * holds on ring i at step s started; row 0 is the rank itself. */
 const int32_t* tasp_schedule_arrival(const tasp_schedule_t* s);
 
@@ -85,7 +97,7 @@ const int32_t* tasp_schedule_arrival(const tasp_schedule_t* s);
  *   TASP_MASK_FULL           one range: piece `ring` of the contiguous chunk of eq. (3);
  *   TASP_MASK_ZIGZAG_CAUSAL  two ranges: piece `ring` of half-chunk src_rank (eq. (5)) and its
  *                            mirror image in half-chunk 2N-1-src_rank (eq. (6)).
- * Piece i of a block of `len` tokens is [i*len/(N-1), (i+1)*len/(N-1)) with integer division.
+ * Piece i of a block of `len` tokens is [i*len/R, (i+1)*len/R) with integer division (R rings).
  * ranges (host, 4 entries) receives start0,end0[,start1,end1]; *n_ranges receives 1 or 2.
  * S must be a positive multiple of N (FULL) or 2N (ZIGZAG_CAUSAL). */
 int tasp_subchunk_ranges(const tasp_schedule_t* s, int64_t S, int32_t mask_mode, int32_t ring,

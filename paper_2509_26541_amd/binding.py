@@ -25,7 +25,7 @@ EXPORTS = [
     "tasp_schedule_out_mapping", "tasp_schedule_in_mapping", "tasp_schedule_arrival", "tasp_subchunk_ranges",
     "tasp_step_segments", "tasp_chunk_attn_workspace_bytes", "tasp_chunk_attn", "tasp_step_attn",
     "tasp_lse_merge", "tasp_chunk_attn_flops", "tasp_chunk_attn_profile", "tasp_last_hip_error", "tasp_calibration_copy",
-    "tasp_lse_merge_many", "tasp_calibration_mfma",
+    "tasp_lse_merge_many", "tasp_calibration_mfma", "tasp_schedule_create_multinode",
 ]
 
 
@@ -65,6 +65,7 @@ def _load():
     lib.tasp_last_hip_error.restype = C.c_char_p
     lib.tasp_last_hip_error.argtypes = []
     lib.tasp_schedule_create.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+    lib.tasp_schedule_create_multinode.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
     lib.tasp_schedule_destroy.argtypes = [C.c_void_p]
     lib.tasp_schedule_destroy.restype = None
     for name in ("n_ranks", "rank", "n_rings", "max_arc_load"):
@@ -110,9 +111,15 @@ def _check(status, where):
 class Schedule:
     """tasp_schedule(N, rank): owns a tasp_schedule_t; arrays are copied out as numpy int32."""
 
-    def __init__(self, n_ranks, rank):
+    def __init__(self, n_ranks, rank, ranks_per_node=None):
         self._h = C.c_void_p()
-        _check(lib.tasp_schedule_create(n_ranks, rank, C.byref(self._h)), "tasp_schedule_create")
+        if ranks_per_node is None:
+            _check(lib.tasp_schedule_create(n_ranks, rank, C.byref(self._h)), "tasp_schedule_create")
+        else:
+            if ranks_per_node <= 0 or n_ranks % ranks_per_node:
+                raise ValueError("n_ranks must be a multiple of ranks_per_node")
+            _check(lib.tasp_schedule_create_multinode(ranks_per_node, n_ranks // ranks_per_node, rank, C.byref(self._h)),
+                   "tasp_schedule_create_multinode")
         n = lib.tasp_schedule_n_ranks(self._h)
         m = lib.tasp_schedule_n_rings(self._h)
         self.n_ranks, self.rank, self.n_rings = n, lib.tasp_schedule_rank(self._h), m
@@ -149,6 +156,11 @@ class Schedule:
 
 def tasp_schedule(n_ranks, rank):
     return Schedule(n_ranks, rank)
+
+
+def tasp_schedule_multinode(ranks_per_node, n_nodes, rank):
+    """The (m-K_m-m)^u scheme: m = ranks_per_node rings over m * n_nodes ranks."""
+    return Schedule(ranks_per_node * n_nodes, rank, ranks_per_node=ranks_per_node)
 
 
 def _torch():

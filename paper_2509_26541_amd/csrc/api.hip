@@ -41,7 +41,7 @@ int validate(const tasp_schedule_t* s, const tasp_attn_args* a, Shape* sh) {
     if (a->S >= (1 << 24) || row_bytes >= (1 << 24) || a->S * row_bytes > (int64_t{1} << 32))
       return TASP_EUNSUPPORTED_SHAPE;
   }
-  if (2 * (s->n - 1) > tasp::kMaxSeg) return TASP_EUNSUPPORTED_SHAPE;
+  if (2 * s->n_rings > tasp::kMaxSeg) return TASP_EUNSUPPORTED_SHAPE;
   if ((reinterpret_cast<uintptr_t>(a->q) | reinterpret_cast<uintptr_t>(a->k) | reinterpret_cast<uintptr_t>(a->v)) & 15)
     return TASP_EALIGN;
   sh->L = a->S / s->n;

@@ -1,6 +1,7 @@
-// tasp_schedule(N, rank): K_N ring decomposition (Sec. 3.1.2, Algorithm 1), routing tables
-// (Algorithm 2), arrival order of the Multi-Ring AllGather (Sec. 3.2.2, Fig. 4) and sub-chunk
-// placement (Sec. 3.2.3, eq. (3)-(6)).  Host code, integers only.
+// tasp_schedule(N, rank): K_N ring decomposition (Sec. 3.1.2, Algorithm 1) or the multi-node
+// (m-K_m-m)^u scheme (Sec. 3.1.3), routing tables (Algorithm 2), arrival order of the Multi-Ring
+// AllGather (Sec. 3.2.2, Fig. 4) and sub-chunk placement (Sec. 3.2.3, eq. (3)-(6)).  Host code,
+// integers only.
 #include "schedule.hpp"
 
 #include <algorithm>
@@ -48,6 +49,19 @@ void decompose(int32_t n, std::vector<int32_t>& rings) {
   last[len] = n - 1;
 }
 
+// Sec. 3.1.3: every node (ranks c*m .. c*m+m-1) is cut into the m zig-zag paths; ring i runs through
+// path i of node 0, path i of node 1, ... and closes from the last node to the first.  The paths of
+// a node use each of its m(m-1) arcs once, and because every rank starts one path and ends one
+// path, it sends to the next node once and receives from the previous node once.
+void chain_nodes(int32_t m, int32_t u, std::vector<int32_t>& rings) {
+  const int32_t n = m * u;
+  rings.assign(static_cast<size_t>(m) * n, -1);
+  for (int32_t i = 0; i < m; ++i)
+    for (int32_t c = 0; c < u; ++c)
+      for (int32_t t = 0; t < m; ++t)
+        rings[static_cast<size_t>(i) * n + c * m + t] = c * m + (i + zigzag_at(t, m)) % m;
+}
+
 void fill_k4(std::vector<int32_t>& rings) {
   // K_4 has six directed Hamiltonian cycles and no three of them are arc-disjoint; this triple
   // repeats two arcs (0->1, 2->3) and leaves two unused (0->3, 2->1), the least possible.
@@ -90,7 +104,7 @@ static void piece_bounds(int64_t len, int32_t m, int32_t i, int64_t* a, int64_t*
 
 static int subchunk(const tasp_schedule& s, int64_t S, int32_t mask_mode, int32_t ring, int32_t src,
                     int64_t r[4]) {
-  const int32_t m = s.n - 1;
+  const int32_t m = s.n_rings;
   int64_t a, b;
   if (mask_mode == TASP_MASK_FULL) {
     const int64_t L = S / s.n;
@@ -129,7 +143,7 @@ int step_segments(const tasp_schedule& s, int64_t S, int32_t mask_mode, int32_t 
     else out->push_back({a, b, diag});
   };
   if (order == TASP_ORDER_TASP) {
-    const int32_t m = s.n - 1;
+    const int32_t m = s.n_rings;
     for (int32_t ring = 0; ring < m; ++ring) {
       const int32_t src = s.arrival[static_cast<size_t>(step) * m + ring];
       int64_t r[4];
@@ -172,6 +186,35 @@ const char* tasp_strerror(int status) {
   }
 }
 
+// Algorithm 2 and the arrival order, from the ring table of s.
+static void derive_tables(tasp_schedule* s) {
+  const int32_t n = s->n, m = s->n_rings, rank = s->rank;
+  // Algorithm 2: highest ring first so that the lower id survives on a shared arc (N == 4).
+  s->out_mapping.assign(static_cast<size_t>(n) * n, -1);
+  s->in_mapping.assign(static_cast<size_t>(n) * n, -1);
+  std::vector<int32_t> load(static_cast<size_t>(n) * n, 0);
+  for (int32_t i = m - 1; i >= 0; --i) {
+    const int32_t* ring = &s->rings[static_cast<size_t>(i) * n];
+    for (int32_t j = 0; j < n; ++j) {
+      const int32_t u = ring[j], v = ring[(j + 1) % n];
+      s->out_mapping[static_cast<size_t>(u) * n + v] = i;
+      s->in_mapping[static_cast<size_t>(v) * n + u] = i;
+      ++load[static_cast<size_t>(u) * n + v];
+    }
+  }
+  s->max_arc_load = *std::max_element(load.begin(), load.end());
+
+  // Arrival order: on ring i the sub-chunk seen at step s started s hops upstream.
+  s->arrival.assign(static_cast<size_t>(n) * m, -1);
+  for (int32_t i = 0; i < m; ++i) {
+    const int32_t* ring = &s->rings[static_cast<size_t>(i) * n];
+    int32_t pos = 0;
+    while (pos < n && ring[pos] != rank) ++pos;
+    for (int32_t step = 0; step < n; ++step)
+      s->arrival[static_cast<size_t>(step) * m + i] = ring[((pos - step) % n + n) % n];
+  }
+}
+
 int tasp_schedule_create(int32_t n_ranks, int32_t rank, tasp_schedule_t** out) {
   if (out == nullptr) return TASP_EINVAL;
   *out = nullptr;
@@ -181,35 +224,35 @@ int tasp_schedule_create(int32_t n_ranks, int32_t rank, tasp_schedule_t** out) {
   tasp_schedule* s = new (std::nothrow) tasp_schedule;
   if (s == nullptr) return TASP_ENOMEM;
   try {
-    const int32_t n = n_ranks, m = n_ranks - 1;
-    s->n = n;
+    s->n = n_ranks;
+    s->n_rings = n_ranks - 1;
     s->rank = rank;
-    if (n == 4) fill_k4(s->rings); else decompose(n, s->rings);
+    if (n_ranks == 4) fill_k4(s->rings); else decompose(n_ranks, s->rings);
+    derive_tables(s);
+  } catch (...) {
+    delete s;
+    return TASP_ENOMEM;
+  }
+  *out = s;
+  return TASP_OK;
+}
 
-    // Algorithm 2: highest ring first so that the lower id survives on a shared arc (N == 4).
-    s->out_mapping.assign(static_cast<size_t>(n) * n, -1);
-    s->in_mapping.assign(static_cast<size_t>(n) * n, -1);
-    std::vector<int32_t> load(static_cast<size_t>(n) * n, 0);
-    for (int32_t i = m - 1; i >= 0; --i) {
-      const int32_t* ring = &s->rings[static_cast<size_t>(i) * n];
-      for (int32_t j = 0; j < n; ++j) {
-        const int32_t u = ring[j], v = ring[(j + 1) % n];
-        s->out_mapping[static_cast<size_t>(u) * n + v] = i;
-        s->in_mapping[static_cast<size_t>(v) * n + u] = i;
-        ++load[static_cast<size_t>(u) * n + v];
-      }
-    }
-    s->max_arc_load = *std::max_element(load.begin(), load.end());
-
-    // Arrival order: on ring i the sub-chunk seen at step s started s hops upstream.
-    s->arrival.assign(static_cast<size_t>(n) * m, -1);
-    for (int32_t i = 0; i < m; ++i) {
-      const int32_t* ring = &s->rings[static_cast<size_t>(i) * n];
-      int32_t pos = 0;
-      while (pos < n && ring[pos] != rank) ++pos;
-      for (int32_t step = 0; step < n; ++step)
-        s->arrival[static_cast<size_t>(step) * m + i] = ring[((pos - step) % n + n) % n];
-    }
+int tasp_schedule_create_multinode(int32_t ranks_per_node, int32_t n_nodes, int32_t rank, tasp_schedule_t** out) {
+  if (out == nullptr) return TASP_EINVAL;
+  *out = nullptr;
+  if (ranks_per_node < 1 || n_nodes < 1 || ranks_per_node > 4096 || n_nodes > 4096) return TASP_EINVAL;
+  const int32_t n = ranks_per_node * n_nodes;
+  if (rank < 0 || rank >= n) return TASP_EINVAL;
+  // the zig-zag paths need an even node size; with one node the closing arcs would repeat arcs of the paths
+  if (ranks_per_node % 2 != 0 || n_nodes < 2 || n > 4096) return TASP_EUNSUPPORTED_N;
+  tasp_schedule* s = new (std::nothrow) tasp_schedule;
+  if (s == nullptr) return TASP_ENOMEM;
+  try {
+    s->n = n;
+    s->n_rings = ranks_per_node;
+    s->rank = rank;
+    chain_nodes(ranks_per_node, n_nodes, s->rings);
+    derive_tables(s);
   } catch (...) {
     delete s;
     return TASP_ENOMEM;
@@ -222,7 +265,7 @@ void tasp_schedule_destroy(tasp_schedule_t* s) { delete s; }
 
 int32_t tasp_schedule_n_ranks(const tasp_schedule_t* s) { return s ? s->n : 0; }
 int32_t tasp_schedule_rank(const tasp_schedule_t* s) { return s ? s->rank : -1; }
-int32_t tasp_schedule_n_rings(const tasp_schedule_t* s) { return s ? s->n - 1 : 0; }
+int32_t tasp_schedule_n_rings(const tasp_schedule_t* s) { return s ? s->n_rings : 0; }
 int32_t tasp_schedule_max_arc_load(const tasp_schedule_t* s) { return s ? s->max_arc_load : 0; }
 const int32_t* tasp_schedule_rings(const tasp_schedule_t* s) { return s ? s->rings.data() : nullptr; }
 const int32_t* tasp_schedule_out_mapping(const tasp_schedule_t* s) { return s ? s->out_mapping.data() : nullptr; }
@@ -234,7 +277,7 @@ int tasp_subchunk_ranges(const tasp_schedule_t* s, int64_t S, int32_t mask_mode,
   if (s == nullptr || ranges == nullptr || n_ranges == nullptr) return TASP_EINVAL;
   int st = tasp::check_sequence(*s, S, mask_mode);
   if (st != TASP_OK) return st;
-  if (ring < 0 || ring >= s->n - 1 || src_rank < 0 || src_rank >= s->n) return TASP_EINVAL;
+  if (ring < 0 || ring >= s->n_rings || src_rank < 0 || src_rank >= s->n) return TASP_EINVAL;
   *n_ranges = tasp::subchunk(*s, S, mask_mode, ring, src_rank, ranges);
   return TASP_OK;
 }

@@ -7,12 +7,13 @@
 
 struct tasp_schedule {
   int32_t n = 0;             // ranks
+  int32_t n_rings = 0;       // rings = sub-chunks per chunk: n-1 (K_n scheme) or m ((m-K_m-m)^u scheme)
   int32_t rank = 0;
   int32_t max_arc_load = 1;
-  std::vector<int32_t> rings;        // [(n-1) * n]
+  std::vector<int32_t> rings;        // [n_rings * n]
   std::vector<int32_t> out_mapping;  // [n * n]
   std::vector<int32_t> in_mapping;   // [n * n]
-  std::vector<int32_t> arrival;      // [n * (n-1)]
+  std::vector<int32_t> arrival;      // [n * n_rings]
 };
 
 namespace tasp {

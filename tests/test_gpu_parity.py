@@ -193,6 +193,66 @@ def test_calibration_mfma_runs(tb):
 
 
 # ------------------------------------------------------------------ full-size configs, sampled rows
+# ------------------------------------------------------------------ (m-K_m-m)^u schedules (Sec. 3.1.3)
+MULTINODE = [
+    # name, ranks per node, nodes, rank, S, Hq, Hkv, d, mask
+    ("mn_4x2_zz", 4, 2, 5, 8 * 2 * 200, 4, 2, 128, wl.ZIGZAG_CAUSAL),      # 4 sub-chunks of 50 tokens
+    ("mn_8x2_zz", 8, 2, 9, 16 * 2 * 100, 4, 1, 128, wl.ZIGZAG_CAUSAL),     # pieces of 12/13 tokens
+    ("mn_8x2_full", 8, 2, 0, 16 * 150, 2, 2, 128, wl.FULL),
+    ("mn_2x3_zz_d64", 2, 3, 4, 6 * 2 * 96, 2, 2, 64, wl.ZIGZAG_CAUSAL),
+]
+
+
+@pytest.mark.parametrize("case", MULTINODE, ids=[c[0] for c in MULTINODE])
+@pytest.mark.parametrize("fuse", [False, True])
+def test_small_multinode_schedule_all_rows(tb, case, fuse):
+    """The result does not depend on the ring table; with m rings a step concatenates m sub-chunks."""
+    name, m, u, rank, S, Hq, Hkv, d, mode = case
+    w = wl.Workload(name, m * u, rank, S, Hq, Hkv, d, "bf16", mode, seed=wl.BASE_SEED + 300 + m + u)
+    q, k, v = wl.make_qkv(w)
+    s = tb.tasp_schedule_multinode(m, u, rank)
+    assert s.n_rings == m
+    out, lse = tb.tasp_chunk_attn(q.cuda(), k.cuda(), v.cuda(), s, mode, fuse_merge=fuse)
+    torch.cuda.synchronize()
+    rows = list(range(w.L))
+    ref_o, ref_l = oracle_rows(w, q, k, v, rows)
+    check(w, out.float().cpu().numpy(), lse.cpu().numpy(), ref_o, ref_l, rows)
+    # the partial of one step against the oracle's partial over that step's tokens
+    rings = sch.multinode_rings(m, u)
+    step = 1 + (rank % (m * u - 1))
+    o_s, l_s = tb.tasp_step_attn(q.cuda(), k.cuda(), v.cuda(), s, mode, step)
+    torch.cuda.synchronize()
+    toks = att.step_tokens(m * u, rank, S, mode, rings, step)
+    pos = sch.local_positions(m * u, rank, S, mode)
+    kk, vv = k[:, 0].double().numpy(), v[:, 0].double().numpy()
+    for r in (0, w.L // 2 - 1, w.L // 2, w.L - 1):
+        ro, rl = att.partial_over_tokens(q[r, 0].double().numpy(), pos[r], kk, vv, toks, mode == wl.ZIGZAG_CAUSAL,
+                                         1.0 / np.sqrt(d))
+        assert max_abs(l_s[r, 0].cpu().numpy(), rl) <= 1e-3
+        assert max_abs(o_s[r, 0].cpu().numpy(), ro) <= 2e-2
+
+
+@pytest.mark.timeout(900)
+def test_full_size_multinode_8x2_sampled_rows(tb):
+    """Workload 4's shape (16 ranks as 2 nodes of 8) with the (8-K_8-8)^2 schedule: 8 sub-chunks per
+    step instead of 15."""
+    w = wl.CONFIGS[3]
+    say = lambda msg: print("[%s, (8-K_8-8)^2] %s" % (w.name, msg), flush=True)
+    say("generating inputs")
+    q, k, v = wl.make_qkv(w)
+    s = tb.tasp_schedule_multinode(8, 2, w.rank)
+    say("running tasp_chunk_attn")
+    out, lse = tb.tasp_chunk_attn(q.cuda(), k.cuda(), v.cuda(), s, w.mask_mode, fuse_merge=True)
+    torch.cuda.synchronize()
+    out, lse = out.float().cpu().numpy(), lse.cpu().numpy()
+    torch.cuda.empty_cache()
+    rows = wl.sample_rows(w, 8)[:16]
+    say("oracle: %d rows x all heads" % len(rows))
+    ref_o, ref_l = oracle_rows(w, q, k, v, rows)
+    check(w, out, lse, ref_o, ref_l, rows)
+    assert np.all(np.isfinite(lse)) and np.all(np.isfinite(out))
+
+
 FULL_SIZE = [(1, 24, 96), (2, 16, 48), (3, 12, 32), (4, 8, 24)]
 
 

@@ -24,6 +24,31 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(raw, name), name
 
 
+@pytest.mark.parametrize("m,u", [(2, 2), (4, 2), (8, 2), (8, 3), (6, 5), (16, 2), (32, 2), (8, 8)])
+def test_multinode_schedule_bit_exact_all_ranks(m, u):
+    rings = sch.multinode_rings(m, u)
+    n = m * u
+    out_m, in_m = sch.out_mapping(rings), sch.in_mapping(rings)
+    for rank in range(n):
+        s = tb.tasp_schedule_multinode(m, u, rank)
+        assert (s.n_ranks, s.rank, s.n_rings, s.max_arc_load) == (n, rank, m, 1)
+        assert s.rings.tolist() == rings
+        assert s.out_mapping.tolist() == out_m
+        assert s.in_mapping.tolist() == in_m
+        assert s.arrival.tolist() == sch.arrival_table(rings, rank)
+    S = 2 * n * 37
+    s = tb.tasp_schedule_multinode(m, u, n - 1)
+    for mode in (sch.FULL, sch.ZIGZAG_CAUSAL):
+        for ring in range(m):
+            for src in (0, n // 2, n - 1):
+                assert s.subchunk_ranges(S, mode, ring, src) == sch.subchunk_ranges(n, S, mode, ring, src, n_rings=m)
+    h = C.c_void_p()
+    for args, code in [((3, 2, 0), tb.EUNSUPPORTED_N), ((8, 1, 0), tb.EUNSUPPORTED_N), ((0, 2, 0), tb.EINVAL),
+                       ((8, 2, 16), tb.EINVAL), ((8, 2, -1), tb.EINVAL), ((64, 128, 0), tb.EUNSUPPORTED_N)]:
+        assert tb.lib.tasp_schedule_create_multinode(*args, C.byref(h)) == code and not h.value
+    assert tb.lib.tasp_schedule_create_multinode(8, 2, 0, None) == tb.EINVAL
+
+
 @pytest.mark.parametrize("n", NS)
 def test_schedule_bit_exact_all_ranks(n):
     rings = sch.hamilton_rings(n)
@@ -73,6 +98,24 @@ def test_step_segments_against_oracle(n, S, mode):
                     assert diag == (1 if (mode == sch.ZIGZAG_CAUSAL and b - 1 > rows[0]) else 0)
                 for (a0, b0, d0), (a1, b1, d1) in zip(segs, segs[1:]):
                     assert not (b0 == a1 and d0 == d1)          # neighbours were joined
+
+
+@pytest.mark.parametrize("m,u,S", [(4, 2, 112), (8, 2, 480), (2, 3, 60)])
+@pytest.mark.parametrize("mode", [sch.FULL, sch.ZIGZAG_CAUSAL])
+def test_step_segments_multinode_against_oracle(m, u, S, mode):
+    from oracle import attention as att
+    n = m * u
+    rings = sch.multinode_rings(m, u)
+    for rank in range(n):
+        s = tb.tasp_schedule_multinode(m, u, rank)
+        pos = sch.local_positions(n, rank, S, mode)
+        blocks = [pos] if mode == sch.FULL else [pos[: len(pos) // 2], pos[len(pos) // 2:]]
+        for step in range(n):
+            toks = att.step_tokens(n, rank, S, mode, rings, step)
+            for qb, rows in enumerate(blocks):
+                segs = s.step_segments(S, mode, step, qb)
+                want = toks if mode == sch.FULL else [t for t in toks if t <= rows[-1]]
+                assert expand(segs) == want
 
 
 def test_zigzag_classification_matches_the_load_balance_argument():
