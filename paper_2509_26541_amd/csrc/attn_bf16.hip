@@ -16,8 +16,9 @@
 //
 // The loop is software-pipelined by hand inside each wavefront: the scores of tile t+1 and the
 // second product of tile t form one stream of matrix instructions, the softmax arithmetic of tile t
-// and the row maxima of tile t+1 are dealt out between them, operand fragments are read eight
-// ahead.  Matrix instructions and LDS reads are volatile assembly, so their order is the schedule.
+// and the row maxima of tile t+1 are dealt out between them, operand fragments are read four
+// ahead (two would do: the depth from 2 to 8 makes no measurable difference).  Matrix instructions
+// and LDS reads are volatile assembly, so their order is the schedule.
 //
 // A wavefront owns NS strips.  NS = 1 (eight wavefronts, two per SIMD) is what the library
 // launches.  With 32 rows per wavefront every matrix instruction needs 1 KiB of operand from LDS,
@@ -476,7 +477,7 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
   // of fragment f+PD are issued when fragment f has been consumed.
   constexpr int NKF = 2 * KS, NVF = 4 * DB, NF = NKF + NVF;
   constexpr int NKM = NS * NKF, NVM = NS * NVF;        // matrix instructions per phase
-  constexpr int PD = 8;
+  constexpr int PD = 4;
   static_assert(NKF >= PD && NVF >= PD, "");
   constexpr unsigned STAGE_BYTES = 2 * C::TILE_BYTES;
   u32x4 fk[PD];            // K fragments in flight (ring slot = fragment % PD)
