@@ -456,19 +456,28 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
   // P = exp2(S c - m) for two neighbouring scores of a lane, packed to bf16 into the B-operand
   // fragment of its 16-key group.  Pair index: group g = PI / 8 (kb = g / 2, j = g % 2), strip (PI % 8) / 4.
   u32x4 pf[NS][4];
-  float x_even = 0.f;
+  // The exponential of an element is issued one element before its result is used (sum, packing):
+  // a transcendental takes longer than the instruction behind it would wait.
+  float x_late = 0.f, x_later = 0.f;   // exp of element EI-1, EI-2
+  auto use_exp = [&](auto ei) __attribute__((always_inline)) {      // consume element EI, whose exp is x_late (x_later holds EI-1)
+    constexpr int EI = decltype(ei)::value;
+    constexpr int gg = EI / (8 * NS), s = (EI % (8 * NS)) / 8, e = EI % 8;
+    l_run[s] += x_late;
+    asm volatile("" : "+v"(l_run[s]));           // keeps the addition here instead of in a later block
+    if constexpr (e % 2 == 1) {
+      const bf16x2 pk = {static_cast<__bf16>(x_later), static_cast<__bf16>(x_late)};
+      pf[s][gg][e / 2] = __builtin_bit_cast(unsigned, pk);
+    }
+  };
+  constexpr int NE_ = 32 * NS;
   auto exp_one = [&](auto ei, f32x16 (&S)[NS][2]) __attribute__((always_inline)) {
     constexpr int EI = decltype(ei)::value;      // element: group EI / (8 NS) (kb = g / 2, j = g % 2), strip (EI % (8 NS)) / 8, score EI % 8 of the group
     constexpr int gg = EI / (8 * NS), s = (EI % (8 * NS)) / 8, e = EI % 8, kb = gg / 2, j = gg % 2;
     const float x = fast_exp2(__builtin_fmaf(S[s][kb][8 * j + e], c, -m_run[s]));
-    l_run[s] += x;
-    asm volatile("" : "+v"(l_run[s]));           // keeps the addition here instead of in a later block
-    if constexpr (e % 2 == 0) {
-      x_even = x;
-    } else {
-      const bf16x2 pk = {static_cast<__bf16>(x_even), static_cast<__bf16>(x)};
-      pf[s][gg][e / 2] = __builtin_bit_cast(unsigned, pk);
-    }
+    if constexpr (EI > 0) use_exp(std::integral_constant<int, EI - 1>{});
+    x_later = x_late;
+    x_late = x;
+    if constexpr (EI == NE_ - 1) use_exp(ei);    // the last one is needed right away
   };
 
   // ---- the matrix instructions of a loop body as one stream of operand fragments: fragments
