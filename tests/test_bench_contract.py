@@ -1,0 +1,29 @@
+"""bench.py argument contract that can be checked without a GPU."""
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    for extra_env, args in (({}, ["--gpus", "2"]), ({"WORLD_SIZE": "2"}, [])):
+        env = dict(os.environ, **extra_env)
+        res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")] + args, capture_output=True, text=True,
+                             env=env, timeout=120)
+        assert res.returncode != 0
+        assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_profiles_name_the_workload_the_bench_times():
+    import json
+    from paper_2509_26541_amd import workloads as wl
+    with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+        traffic = json.load(f)
+    name = wl.CONFIGS[1].name                      # the default workload of bench.py
+    assert name in traffic and traffic[name]["attn_bytes_per_launch"] > 0
+    for suffix in ("_kernel_stats.txt", "_counters.txt"):
+        path = os.path.join(ROOT, "profiles", name + suffix)
+        assert os.path.exists(path)
+        text = open(path).read()
+        assert "rocprofv3" in text and "bench.py --config 2" in text
