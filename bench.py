@@ -77,6 +77,8 @@ def main():
     ap.add_argument("--order", choices=["tasp", "ring"], default="tasp")
     ap.add_argument("--nodes", type=int, default=0,
                     help="U > 1: the (m-K_m-m)^U ring scheme for U nodes of N/U ranks (m rings) instead of the N-1 rings of K_N")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="B > 1: B sequences of the workload's shape in one call (sequence b seeded with seed + 1000 b)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-mode", action="store_true",
                     help="skip the leg that runs the other merge mode (profiler runs: one kind of launch only)")
@@ -98,6 +100,11 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    if args.batch > 1:
+        import dataclasses
+        more = [wl.make_qkv(dataclasses.replace(w, seed=w.seed + 1000 * b)) for b in range(1, args.batch)]
+        qd, kd, vd = (torch.stack([x] + [m[i].to(dev) for m in more]) for i, x in enumerate((qd, kd, vd)))
+        del more
     if args.nodes > 1:
         sched = tb.tasp_schedule_multinode(w.n_ranks // args.nodes, args.nodes, w.rank)
     else:
@@ -142,7 +149,7 @@ def main():
     # the copy-kernel calibration); the figures live in profiles/traffic.json next to their summaries
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and args.batch == 1 and args.nodes <= 1 and args.order == "tasp":   # what was profiled
         with open(tpath) as f:
             traffic = json.load(f).get(w.name, {}).get("attn_bytes_per_launch")
     roofline = {
@@ -159,7 +166,7 @@ def main():
             for qb in range(2 if w.mask_mode == wl.ZIGZAG_CAUSAL else 1):
                 if sched.step_segments(w.S, w.mask_mode, step, qb, order=order):
                     rows_heads += (w.L // (2 if w.mask_mode == wl.ZIGZAG_CAUSAL else 1)) * w.Hq
-        gbs = rows_heads * bytes_per_rh / (ms_total / calls * 1e-3) / 1e9
+        gbs = args.batch * rows_heads * bytes_per_rh / (ms_total / calls * 1e-3) / 1e9
         return {"bound": "hbm", "kernel": "merge_kernel", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": gbs / PEAK_HBM_GBS, "ms_per_call": ms_total / calls, "launches_per_call": launches // calls}
 
@@ -234,7 +241,7 @@ def main():
                                "what": "tasp_calibration_mfma: only v_mfma_f32_32x32x16_bf16, operands in registers"},
         "config": {"workload": w.name, "n_ranks": w.n_ranks, "rank": w.rank, "S": w.S, "L": w.L, "Hq": w.Hq,
                    "Hkv": w.Hkv, "d": w.d, "mask": "zigzag_causal" if w.mask_mode else "full",
-                   "order": args.order, "rings": sched.n_rings, "fuse_merge": int(args.fuse_merge), "flops_per_call": flops},
+                   "order": args.order, "rings": sched.n_rings, "batch": args.batch, "fuse_merge": int(args.fuse_merge), "flops_per_call": flops},
         "roofline": roofline,
         "merge": merge,
         "ms_breakdown": {"attn": attn_ms / n_prof, "merge": merge_ms / n_prof, "cast": other_ms / n_prof},

@@ -133,6 +133,10 @@ int tasp_step_segments(const tasp_schedule_t* s, int64_t S, int32_t mask_mode, i
  *                 (update_out_lse of Algorithm 3);  1: the attention kernel folds it in itself.
  *   workspace device, >= tasp_chunk_attn_workspace_bytes() bytes, 256-byte aligned, caller-owned,
  *             contents undefined on entry and exit.
+ *   batch    B independent sequences handled in one call (0 counts as 1, at most 65535): every
+ *            tensor gets a leading dimension, q/out [B, L, Hq, d], k/v [B, S, Hkv, d], lse
+ *            [B, L, Hq]; all sequences share S, the schedule and the mask (the shape grid of the
+ *            paper's evaluation, Sec. 5.1, has batches of up to 128 sequences).
  * Supported: d in {64, 128}; N <= 32; S < 2^31; for bf16 also S < 2^24 and S*Hkv*d*2 <= 2^32 bytes
  * (K and V are addressed with 32-bit offsets).  All device pointers 16-byte aligned.
  * The call only enqueues work on `hip_stream` (a hipStream_t, NULL = default stream); results are
@@ -153,6 +157,7 @@ typedef struct tasp_attn_args {
   int32_t     order;          /* TASP_ORDER_TASP or TASP_ORDER_RING */
   int32_t     fuse_merge;
   float       softmax_scale;
+  int32_t     batch;
 } tasp_attn_args;
 
 size_t tasp_chunk_attn_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_args* a);

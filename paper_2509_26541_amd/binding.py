@@ -42,6 +42,7 @@ class AttnArgs(C.Structure):
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("S", C.c_int64),
         ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32), ("dtype", C.c_int32),
         ("mask_mode", C.c_int32), ("order", C.c_int32), ("fuse_merge", C.c_int32), ("softmax_scale", C.c_float),
+        ("batch", C.c_int32),
     ]
 
 
@@ -176,11 +177,14 @@ def _args(q, k, v, mask_mode, order, fuse_merge, softmax_scale):
         raise ValueError("q, k, v must be contiguous")
     if q.dtype != k.dtype or q.dtype != v.dtype or q.dtype not in (torch.float32, torch.bfloat16):
         raise ValueError("q, k, v must share dtype float32 or bfloat16")
-    if q.dim() != 3 or k.dim() != 3 or v.shape != k.shape or q.shape[2] != k.shape[2]:
-        raise ValueError("expected q [L, Hq, d] and k, v [S, Hkv, d]")
+    if q.dim() not in (3, 4) or k.dim() != q.dim() or v.shape != k.shape or q.shape[-1] != k.shape[-1]:
+        raise ValueError("expected q [L, Hq, d] and k, v [S, Hkv, d], or all three with a leading batch dimension")
+    if q.dim() == 4 and q.shape[0] != k.shape[0]:
+        raise ValueError("q and k, v must hold the same number of sequences")
     a = AttnArgs()
     a.q, a.k, a.v = q.data_ptr(), k.data_ptr(), v.data_ptr()
-    a.S, a.Hq, a.Hkv, a.d = k.shape[0], q.shape[1], k.shape[1], q.shape[2]
+    a.S, a.Hq, a.Hkv, a.d = k.shape[-3], q.shape[-2], k.shape[-2], q.shape[-1]
+    a.batch = q.shape[0] if q.dim() == 4 else 1
     a.dtype = DTYPE_FP32 if q.dtype == torch.float32 else DTYPE_BF16
     a.mask_mode, a.order, a.fuse_merge, a.softmax_scale = mask_mode, order, int(bool(fuse_merge)), softmax_scale
     return a
@@ -193,10 +197,10 @@ class ChunkAttnPlan:
         torch = _torch()
         self.schedule = schedule
         self.args = _args(q, k, v, mask_mode, order, fuse_merge, softmax_scale)
-        if q.shape[0] * schedule.n_ranks != k.shape[0]:
+        if q.shape[-3] * schedule.n_ranks != k.shape[-3]:
             raise ValueError("q must hold S / N local rows")
         self.out = torch.empty_like(q)
-        self.lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+        self.lse = torch.empty(q.shape[:-1], dtype=torch.float32, device=q.device)
         nbytes = lib.tasp_chunk_attn_workspace_bytes(schedule.handle, C.byref(self.args))
         self.workspace = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=q.device)
         self.args.out, self.args.lse = self.out.data_ptr(), self.lse.data_ptr()
@@ -232,7 +236,7 @@ def tasp_step_attn(q, k, v, schedule, mask_mode, step, order=ORDER_TASP, softmax
     torch = _torch()
     a = _args(q, k, v, mask_mode, order, False, softmax_scale)
     o = torch.empty(q.shape, dtype=torch.float32, device=q.device)
-    lse = torch.empty(q.shape[:2], dtype=torch.float32, device=q.device)
+    lse = torch.empty(q.shape[:-1], dtype=torch.float32, device=q.device)
     s = torch.cuda.current_stream().cuda_stream
     _check(lib.tasp_step_attn(schedule.handle, C.byref(a), step, o.data_ptr(), lse.data_ptr(), C.c_void_p(s)),
            "tasp_step_attn")

@@ -19,10 +19,13 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Shape {
-  int64_t L;            // local rows
-  size_t o_bytes;       // fp32 [L, Hq, d]
-  size_t lse_bytes;     // fp32 [L, Hq]
+  int64_t L;            // local rows of one sequence
+  int32_t B;            // sequences in the batch
+  size_t o_bytes;       // fp32 [B, L, Hq, d]
+  size_t lse_bytes;     // fp32 [B, L, Hq]
 };
+
+int32_t batch_of(const tasp_attn_args* a) { return a->batch == 0 ? 1 : a->batch; }
 
 int validate(const tasp_schedule_t* s, const tasp_attn_args* a, Shape* sh) {
   if (s == nullptr || a == nullptr) return TASP_EINVAL;
@@ -42,11 +45,13 @@ int validate(const tasp_schedule_t* s, const tasp_attn_args* a, Shape* sh) {
       return TASP_EUNSUPPORTED_SHAPE;
   }
   if (2 * s->n_rings > tasp::kMaxSeg) return TASP_EUNSUPPORTED_SHAPE;
+  if (a->batch < 0 || a->batch > 65535) return TASP_EINVAL;
   if ((reinterpret_cast<uintptr_t>(a->q) | reinterpret_cast<uintptr_t>(a->k) | reinterpret_cast<uintptr_t>(a->v)) & 15)
     return TASP_EALIGN;
   sh->L = a->S / s->n;
-  sh->o_bytes = static_cast<size_t>(sh->L) * a->Hq * a->d * sizeof(float);
-  sh->lse_bytes = static_cast<size_t>(sh->L) * a->Hq * sizeof(float);
+  sh->B = batch_of(a);
+  sh->o_bytes = static_cast<size_t>(sh->B) * sh->L * a->Hq * a->d * sizeof(float);
+  sh->lse_bytes = static_cast<size_t>(sh->B) * sh->L * a->Hq * sizeof(float);
   return TASP_OK;
 }
 
@@ -57,6 +62,12 @@ int build_step(const tasp_schedule_t* s, const tasp_attn_args* a, int step, Attn
   lp->Hq = a->Hq; lp->Hkv = a->Hkv;
   lp->causal = a->mask_mode == TASP_MASK_ZIGZAG_CAUSAL ? 1 : 0;
   lp->scale = a->softmax_scale > 0.f ? a->softmax_scale : 1.0f / std::sqrt(static_cast<float>(a->d));
+  const int64_t L = a->S / s->n;
+  lp->batch = batch_of(a);
+  lp->q_bstride = L * a->Hq * a->d;
+  lp->kv_bstride = a->S * a->Hkv * a->d;
+  lp->o_bstride = L * a->Hq * a->d;
+  lp->lse_bstride = L * a->Hq;
   lp->n_tasks = 0;
   int64_t keys[tasp::kMaxTasks] = {0, 0};
   std::vector<tasp::Segment> segs;
@@ -133,10 +144,11 @@ extern "C" {
 const char* tasp_last_hip_error(void) { return hipGetErrorString(tasp::g_last_hip_error); }
 
 size_t tasp_chunk_attn_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_args* a) {
-  if (s == nullptr || a == nullptr || a->S <= 0 || a->Hq <= 0 || a->d <= 0 || s->n <= 0) return 0;
+  if (s == nullptr || a == nullptr || a->S <= 0 || a->Hq <= 0 || a->d <= 0 || s->n <= 0 || a->batch < 0) return 0;
   const int64_t L = a->S / s->n;
-  const size_t o_bytes = align_up(static_cast<size_t>(L) * a->Hq * a->d * sizeof(float));
-  const size_t lse_bytes = align_up(static_cast<size_t>(L) * a->Hq * sizeof(float));
+  const size_t B = static_cast<size_t>(batch_of(a));
+  const size_t o_bytes = align_up(B * L * a->Hq * a->d * sizeof(float));
+  const size_t lse_bytes = align_up(B * L * a->Hq * sizeof(float));
   size_t total = 0;
   if (a->dtype == TASP_DTYPE_BF16) total += o_bytes;              // running fp32 output
   if (!a->fuse_merge) total += o_bytes + lse_bytes;               // partial (out_s, lse_s) of a step
@@ -154,7 +166,7 @@ double tasp_chunk_attn_flops(const tasp_schedule_t* s, const tasp_attn_args* a) 
     if (a->mask_mode == TASP_MASK_FULL) pairs += rows * static_cast<double>(a->S);
     else pairs += rows * static_cast<double>(blk.pos0) + rows * (rows + 1.0) / 2.0;   // sum of (p + 1)
   }
-  return 4.0 * a->d * a->Hq * pairs;
+  return 4.0 * a->d * a->Hq * pairs * (a->batch > 0 ? a->batch : 1);
 }
 
 int tasp_step_attn(const tasp_schedule_t* s, const tasp_attn_args* a, int32_t step, float* o_part,
@@ -173,7 +185,8 @@ int tasp_step_attn(const tasp_schedule_t* s, const tasp_attn_args* a, int32_t st
     lp.o_dst = o_part; lp.lse_dst = lse_part; lp.merge = 0;
     if (launch_attn(lp, a, stream) != hipSuccess) return TASP_EHIP;
     for (const auto& blk : empty)
-      if (tasp::launch_fill_empty(o_part, lse_part, blk.local_row0, blk.rows, a->Hq, a->d, stream) != hipSuccess)
+      if (tasp::launch_fill_empty(o_part, lse_part, blk.local_row0, blk.rows, a->Hq, a->d, sh.B, sh.L, stream) !=
+          hipSuccess)
         return TASP_EHIP;
   } catch (...) {
     return TASP_ENOMEM;
@@ -218,7 +231,8 @@ static int run_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, voi
           if (launch_attn(lp, a, stream) != hipSuccess) return TASP_EHIP;
         }
         for (const auto& blk : empty)      // cannot happen with the placements of Sec. 3.2.3; kept for safety
-          if (tasp::launch_fill_empty(o_run, a->lse, blk.local_row0, blk.rows, a->Hq, a->d, stream) != hipSuccess)
+          if (tasp::launch_fill_empty(o_run, a->lse, blk.local_row0, blk.rows, a->Hq, a->d, sh.B, sh.L, stream) !=
+              hipSuccess)
             return TASP_EHIP;
       } else if (a->fuse_merge) {
         lp.o_dst = o_run; lp.lse_dst = a->lse; lp.merge = 1;
@@ -234,14 +248,14 @@ static int run_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, voi
         for (int t = 0; t < lp.n_tasks; ++t) {
           Scope sc(prof, Profiler::kMerge);
           if (tasp::launch_merge(o_run, a->lse, o_part, lse_part, lp.task[t].q_row0, lp.task[t].n_q, a->Hq, a->d,
-                                 stream) != hipSuccess)
+                                 sh.B, sh.L, stream) != hipSuccess)
             return TASP_EHIP;
         }
       }
     }
     if (a->dtype == TASP_DTYPE_BF16) {
       Scope sc(prof, Profiler::kOther);
-      if (tasp::launch_cast_bf16(o_run, a->out, sh.L * a->Hq * a->d, stream) != hipSuccess) return TASP_EHIP;
+      if (tasp::launch_cast_bf16(o_run, a->out, sh.B * sh.L * a->Hq * a->d, stream) != hipSuccess) return TASP_EHIP;
     }
   } catch (...) {
     return TASP_ENOMEM;

@@ -202,7 +202,10 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
   const int nblocks = gridDim.x;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int q8 = nblocks >> 3, r8 = nblocks & 7;
-  const int w = xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
+  const int w_all = xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
+  const int per_b = per_g * p.Hkv;                            // workgroups of one sequence of the batch
+  const int bi = w_all / per_b;
+  const int w = w_all - bi * per_b;
   const int g = w / per_g;
   int rem = w - g * per_g;
   const int tsk = rem >= tiles0 * G ? 1 : 0;
@@ -260,7 +263,7 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
     my_q[s] = q_tile_row0 + wave * (32 * NS) + 32 * s + lq;          // row inside the task
     q_valid[s] = my_q[s] < T.n_q;
     const int64_t q_row = T.q_row0 + (q_valid[s] ? my_q[s] : T.n_q - 1);
-    const __bf16* src = static_cast<const __bf16*>(p.q) + (q_row * p.Hq + hq) * D + 8 * h;
+    const __bf16* src = static_cast<const __bf16*>(p.q) + bi * p.q_bstride + (q_row * p.Hq + hq) * D + 8 * h;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[s][ks] = *reinterpret_cast<const u32x4*>(src + 16 * ks);
     q_pos[s] = p.causal ? T.q_pos0 + my_q[s] : INT_MAX - 1;
@@ -311,8 +314,8 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
   // tile layout is applied on the source side: the lane that owns LDS slot (row, unit) reads the
   // 16 bytes of column swz(row, unit) of that row.  Rows past the end fetch token 0 and are masked.
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  const unsigned char* Kg = static_cast<const unsigned char*>(p.k) + static_cast<size_t>(g) * D * 2;   // this KV head, uniform
-  const unsigned char* Vg = static_cast<const unsigned char*>(p.v) + static_cast<size_t>(g) * D * 2;
+  const unsigned char* Kg = static_cast<const unsigned char*>(p.k) + (bi * p.kv_bstride + static_cast<int64_t>(g) * D) * 2;   // this sequence and KV head, uniform
+  const unsigned char* Vg = static_cast<const unsigned char*>(p.v) + (bi * p.kv_bstride + static_cast<int64_t>(g) * D) * 2;
   const unsigned k_col = C::swz_k(fr, fu) * 16, v_col = C::swz_v(fr, fu) * 16;    // byte column this lane reads
   static_assert(C::RPP % 16 == 0, "the swizzle of a thread's rows must not depend on the pass");
   // A tile fetch is 2*PASSES loads per thread.  The path from L2 into LDS takes roughly 25 cycles per
@@ -647,8 +650,8 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
     float lse_new = seen ? (m_run[s] + __builtin_amdgcn_logf(l_tot)) * kLn2 : -__builtin_inff();
     if (q_valid[s]) {
       const int64_t grow = T.q_row0 + my_q[s];
-      float* od = p.o_dst + (grow * p.Hq + hq) * D + 4 * h;
-      float* ld = p.lse_dst + grow * p.Hq + hq;
+      float* od = p.o_dst + bi * p.o_bstride + (grow * p.Hq + hq) * D + 4 * h;
+      float* ld = p.lse_dst + bi * p.lse_bstride + grow * p.Hq + hq;
       float wa = 0.f, wb = inv;
       if (p.merge) {
         // update_out_lse of Algorithm 3 folded into the store
@@ -689,7 +692,7 @@ hipError_t launch_variant(const AttnLaunch& p, hipStream_t stream) {
   using C = Cfg<D, NS>;
   int64_t tiles = 0;
   for (int t = 0; t < p.n_tasks; ++t) tiles += (p.task[t].n_q + C::BM - 1) / C::BM;
-  const int64_t blocks = tiles * p.Hq;
+  const int64_t blocks = tiles * p.Hq * p.batch;
   if (blocks == 0) return hipSuccess;
   if (blocks > INT_MAX) return hipErrorInvalidValue;
   return TASP_LAUNCH((attn_bf16_kernel<D, NS>), dim3(static_cast<unsigned>(blocks)), dim3(C::NTHREADS), stream, p);

@@ -40,9 +40,10 @@ __global__ __launch_bounds__(WAVES * 64) void attn_fp32_kernel(const AttnLaunch 
   const int g = hq / (p.Hq / p.Hkv);
   const int64_t row = T.q_row0 + r;
   const int q_pos = T.q_pos0 + r;
-  const float* Qg = static_cast<const float*>(p.q) + (row * p.Hq + hq) * D;
-  const float* Kg = static_cast<const float*>(p.k) + static_cast<int64_t>(g) * D;
-  const float* Vg = static_cast<const float*>(p.v) + static_cast<int64_t>(g) * D;
+  const int64_t bi = blockIdx.y;                     // sequence of the batch
+  const float* Qg = static_cast<const float*>(p.q) + bi * p.q_bstride + (row * p.Hq + hq) * D;
+  const float* Kg = static_cast<const float*>(p.k) + bi * p.kv_bstride + static_cast<int64_t>(g) * D;
+  const float* Vg = static_cast<const float*>(p.v) + bi * p.kv_bstride + static_cast<int64_t>(g) * D;
   const int64_t kv_stride = static_cast<int64_t>(p.Hkv) * D;
 #pragma unroll
   for (int c = 0; c < CPL; ++c) s_q[wave][lane + 64 * c] = Qg[lane + 64 * c];
@@ -94,8 +95,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_fp32_kernel(const AttnLaunch 
   const bool seen = l > 0.f;
   const float inv = seen ? 1.f / l : 0.f;
   float lse_new = seen ? m + logf(l) : -__builtin_inff();
-  float* od = p.o_dst + (row * p.Hq + hq) * D;
-  float* ld = p.lse_dst + row * p.Hq + hq;
+  float* od = p.o_dst + bi * p.o_bstride + (row * p.Hq + hq) * D;
+  float* ld = p.lse_dst + bi * p.lse_bstride + row * p.Hq + hq;
   float wa = 0.f, wb = 1.f;
   if (p.merge) {                                     // update_out_lse of Algorithm 3
     const float lse_old = *ld;
@@ -126,7 +127,8 @@ hipError_t launch_attn_fp32(const AttnLaunch& p, int d, hipStream_t stream) {
   if (items == 0) return hipSuccess;
   const int64_t blocks = (items + WAVES - 1) / WAVES;
   if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-  dim3 grid(static_cast<unsigned>(blocks)), block(WAVES * 64);
+  if (p.batch < 1 || p.batch > 65535) return hipErrorInvalidValue;
+  dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(p.batch)), block(WAVES * 64);
   if (d == 64) return TASP_LAUNCH(attn_fp32_kernel<64>, grid, block, stream, p);
   if (d == 128) return TASP_LAUNCH(attn_fp32_kernel<128>, grid, block, stream, p);
   return hipErrorInvalidValue;

@@ -30,6 +30,8 @@ struct AttnLaunch {
   int32_t causal;     // key t visible to query p iff t <= p
   int32_t merge;      // 0: dst = partial of this step; 1: dst = update_out_lse(dst, partial)
   float scale;        // softmax scale (natural units)
+  int32_t batch;      // independent sequences; element strides between them:
+  int64_t q_bstride, kv_bstride, o_bstride, lse_bstride;
   int32_t n_tasks;
   AttnTask task[kMaxTasks];
 };
@@ -53,10 +55,12 @@ inline hipError_t note_hip(hipError_t e) {
 // Implemented in attn_bf16.hip / attn_fp32.hip / merge.hip.  Each returns a hipError_t from the launch.
 hipError_t launch_attn_bf16(const AttnLaunch& p, int d, hipStream_t stream);
 hipError_t launch_attn_fp32(const AttnLaunch& p, int d, hipStream_t stream);
+// rows [row0, row0 + rows) of every one of `batch` sequences of L rows each
 hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
-                        int64_t row0, int64_t rows, int32_t heads, int32_t d, hipStream_t stream);
+                        int64_t row0, int64_t rows, int32_t heads, int32_t d, int32_t batch, int64_t L,
+                        hipStream_t stream);
 hipError_t launch_fill_empty(float* o, float* lse, int64_t row0, int64_t rows, int32_t heads, int32_t d,
-                             hipStream_t stream);
+                             int32_t batch, int64_t L, hipStream_t stream);
 hipError_t launch_cast_bf16(const float* src, void* dst, int64_t n, hipStream_t stream);
 
 }  // namespace tasp

@@ -119,21 +119,32 @@ unsigned grid_for(int64_t n_items) {
 }  // namespace merge_detail
 
 hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
-                        int64_t row0, int64_t rows, int32_t heads, int32_t d, hipStream_t stream) {
+                        int64_t row0, int64_t rows, int32_t heads, int32_t d, int32_t batch, int64_t L,
+                        hipStream_t stream) {
   if (rows <= 0) return hipSuccess;
-  const int64_t off = row0 * heads;
+  if (rows == L) { rows *= batch; batch = 1; }       // whole sequences: one contiguous range
   const int64_t n4 = rows * heads * (d / 4);
-  return TASP_LAUNCH(merge_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), stream, o_acc + off * d, lse_acc + off,
-                     o_part + off * d, lse_part + off, n4, d / 4);
+  for (int32_t b = 0; b < batch; ++b) {
+    const int64_t off = (b * L + row0) * heads;
+    const hipError_t e = TASP_LAUNCH(merge_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), stream, o_acc + off * d,
+                                     lse_acc + off, o_part + off * d, lse_part + off, n4, d / 4);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_fill_empty(float* o, float* lse, int64_t row0, int64_t rows, int32_t heads, int32_t d,
-                             hipStream_t stream) {
+                             int32_t batch, int64_t L, hipStream_t stream) {
   if (rows <= 0) return hipSuccess;
-  const int64_t off = row0 * heads;
+  if (rows == L) { rows *= batch; batch = 1; }
   const int64_t n4 = rows * heads * (d / 4);
-  return TASP_LAUNCH(fill_empty_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), stream, o + off * d, lse + off,
-                     n4, d / 4);
+  for (int32_t b = 0; b < batch; ++b) {
+    const int64_t off = (b * L + row0) * heads;
+    const hipError_t e = TASP_LAUNCH(fill_empty_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), stream, o + off * d,
+                                     lse + off, n4, d / 4);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_cast_bf16(const float* src, void* dst, int64_t n, hipStream_t stream) {
@@ -187,7 +198,7 @@ extern "C" int tasp_lse_merge(float* o_acc, float* lse_acc, const float* o_part,
   if (o_acc == nullptr || lse_acc == nullptr || o_part == nullptr || lse_part == nullptr) return TASP_EINVAL;
   if ((reinterpret_cast<uintptr_t>(o_acc) | reinterpret_cast<uintptr_t>(o_part)) & 15) return TASP_EALIGN;
   if ((reinterpret_cast<uintptr_t>(lse_acc) | reinterpret_cast<uintptr_t>(lse_part)) & 3) return TASP_EALIGN;
-  const hipError_t e = tasp::launch_merge(o_acc, lse_acc, o_part, lse_part, 0, rows, heads, d,
+  const hipError_t e = tasp::launch_merge(o_acc, lse_acc, o_part, lse_part, 0, rows, heads, d, 1, rows,
                                           static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? TASP_OK : TASP_EHIP;
 }

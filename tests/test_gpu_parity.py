@@ -193,6 +193,44 @@ def test_calibration_mfma_runs(tb):
 
 
 # ------------------------------------------------------------------ full-size configs, sampled rows
+# ------------------------------------------------------------------ a batch of sequences in one call
+BATCHED = [
+    ("bf16_zz_b3", 8, 3, 8 * 2 * 100, 4, 2, 128, "bf16", wl.ZIGZAG_CAUSAL, 3),
+    ("bf16_full_b2_d64", 8, 6, 8 * 150, 2, 2, 64, "bf16", wl.FULL, 2),
+    ("fp32_zz_b4", 4, 1, 4 * 2 * 30, 2, 1, 64, "fp32", wl.ZIGZAG_CAUSAL, 4),
+]
+
+
+@pytest.mark.parametrize("case", BATCHED, ids=[c[0] for c in BATCHED])
+@pytest.mark.parametrize("fuse", [False, True])
+def test_batched_call(tb, case, fuse):
+    """B sequences in one call (the paper's shape grid has a batch dimension): every sequence against
+    the oracle, and bit-identical to B separate calls."""
+    name, n, rank, S, Hq, Hkv, d, dtype, mode, B = case
+    ws = [wl.Workload("%s_%d" % (name, b), n, rank, S, Hq, Hkv, d, dtype, mode, seed=wl.BASE_SEED + 500 + 7 * b)
+          for b in range(B)]
+    qkv = [wl.make_qkv(w) for w in ws]
+    q = torch.stack([x[0] for x in qkv]).cuda()
+    k = torch.stack([x[1] for x in qkv]).cuda()
+    v = torch.stack([x[2] for x in qkv]).cuda()
+    s = tb.tasp_schedule(n, rank)
+    out, lse = tb.tasp_chunk_attn(q, k, v, s, mode, fuse_merge=fuse)
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == tuple(q.shape) and tuple(lse.shape) == tuple(q.shape[:-1])
+    rows = list(range(ws[0].L))
+    for b in range(B):
+        ref_o, ref_l = oracle_rows(ws[b], *qkv[b], rows)
+        check(ws[b], out[b].float().cpu().numpy(), lse[b].cpu().numpy(), ref_o, ref_l, rows)
+        o1, l1 = tb.tasp_chunk_attn(q[b].contiguous(), k[b].contiguous(), v[b].contiguous(), s, mode, fuse_merge=fuse)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, out[b]) and torch.equal(l1, lse[b])
+    # the partial of one step, batched
+    o_s, l_s = tb.tasp_step_attn(q, k, v, s, mode, 2)
+    o_1, l_1 = tb.tasp_step_attn(q[B - 1].contiguous(), k[B - 1].contiguous(), v[B - 1].contiguous(), s, mode, 2)
+    torch.cuda.synchronize()
+    assert torch.equal(o_s[B - 1], o_1) and torch.equal(l_s[B - 1], l_1)
+
+
 # ------------------------------------------------------------------ (m-K_m-m)^u schedules (Sec. 3.1.3)
 MULTINODE = [
     # name, ranks per node, nodes, rank, S, Hq, Hkv, d, mask

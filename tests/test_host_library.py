@@ -243,3 +243,10 @@ def test_flops_and_workspace():
         assert tb.lib.tasp_chunk_attn_workspace_bytes(s.handle, C.byref(a)) == (o if dt else 0) + o + l
         a.fuse_merge = 1
         assert tb.lib.tasp_chunk_attn_workspace_bytes(s.handle, C.byref(a)) == (o if dt else 0)
+        # a batch of B sequences is B times the work and B times the buffers
+        a.batch, a.fuse_merge = 3, 0
+        assert tb.lib.tasp_chunk_attn_flops(s.handle, C.byref(a)) == 3 * float(att.attention_flops(n, rank, S, mode, Hq, d))
+        assert tb.lib.tasp_chunk_attn_workspace_bytes(s.handle, C.byref(a)) == 3 * ((o if dt else 0) + o + l)
+        a.batch = -1
+        assert tb.lib.tasp_chunk_attn_workspace_bytes(s.handle, C.byref(a)) == 0
+        assert tb.lib.tasp_chunk_attn(s.handle, C.byref(a), None) == tb.EINVAL
