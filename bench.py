@@ -79,6 +79,9 @@ def main():
                     help="U > 1: the (m-K_m-m)^U ring scheme for U nodes of N/U ranks (m rings) instead of the N-1 rings of K_N")
     ap.add_argument("--batch", type=int, default=1,
                     help="B > 1: B sequences of the workload's shape in one call (sequence b seeded with seed + 1000 b)")
+    ap.add_argument("--grid", default="",
+                    help="HEADS,SEQ: a shape of the paper's own grid (Sec. 5.1.2: MHA, d = 64, bf16) on 8 ranks "
+                         "instead of --config; combine with --batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-mode", action="store_true",
                     help="skip the leg that runs the other merge mode (profiler runs: one kind of launch only)")
@@ -95,7 +98,11 @@ def main():
     from paper_2509_26541_amd import binding as tb
     from paper_2509_26541_amd import workloads as wl
 
-    w = wl.CONFIGS[args.config - 1]
+    if args.grid:
+        heads, seq = (int(x) for x in args.grid.split(","))
+        w = wl.paper_grid(heads, seq)
+    else:
+        w = wl.CONFIGS[args.config - 1]
     q, k, v = wl.make_qkv(w)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

@@ -53,6 +53,14 @@ CONFIGS = [
 ]
 
 
+def paper_grid(heads, seq, n_ranks=8, rank=3, mask_mode=ZIGZAG_CAUSAL, seed_offset=0):
+    """One sequence of the paper's own benchmark grid (Sec. 5.1.2): multi-head attention with 4, 12 or
+    20 heads of dimension 64 in bf16, sequence length `seq` (3K-1M there); the grid's batch dimension
+    is the `batch` argument of the attention call (sequences seeded seed, seed + 1000, ...)."""
+    name = "grid_n%d_h%d_s%d_d64_%s" % (n_ranks, heads, seq, "zigzag" if mask_mode == ZIGZAG_CAUSAL else "full")
+    return Workload(name, n_ranks, rank, seq, heads, heads, 64, "bf16", mask_mode, seed=BASE_SEED + 100 + heads + seed_offset)
+
+
 def _normal(shape, gen, dtype, rows_per_pass=1 << 16):
     """N(0,1) in fp32 from `gen`, cast (round to nearest even) to dtype; drawn in fixed-size row
     blocks so that the bits do not depend on available memory."""

@@ -201,6 +201,22 @@ BATCHED = [
 ]
 
 
+def test_paper_grid_shape_batched(tb):
+    """A shape of the paper's own grid (Sec. 5.1.2: 12 heads of 64, its shortest sequence 3K) with a
+    batch of 3: every row of every sequence against the oracle."""
+    ws = [wl.paper_grid(12, 3072, seed_offset=1000 * b) for b in range(3)]
+    qkv = [wl.make_qkv(w) for w in ws]
+    q, k, v = (torch.stack([x[i] for x in qkv]).cuda() for i in range(3))
+    s = tb.tasp_schedule(ws[0].n_ranks, ws[0].rank)
+    for fuse in (False, True):
+        out, lse = tb.tasp_chunk_attn(q, k, v, s, ws[0].mask_mode, fuse_merge=fuse)
+        torch.cuda.synchronize()
+        rows = list(range(ws[0].L))
+        for b in range(3):
+            ref_o, ref_l = oracle_rows(ws[b], *qkv[b], rows)
+            check(ws[b], out[b].float().cpu().numpy(), lse[b].cpu().numpy(), ref_o, ref_l, rows)
+
+
 @pytest.mark.parametrize("case", BATCHED, ids=[c[0] for c in BATCHED])
 @pytest.mark.parametrize("fuse", [False, True])
 def test_batched_call(tb, case, fuse):
