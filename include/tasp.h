@@ -216,6 +216,64 @@ int tasp_calibration_mfma(int32_t iters, double* flops, void* hip_stream);
 /* Algorithmic work of one tasp_chunk_attn call: 4*d*Hq*(visible (query,key) pairs). */
 double tasp_chunk_attn_flops(const tasp_schedule_t* s, const tasp_attn_args* a);
 
+/* ----------------------------------------------------------------------------------------------
+ * Backward pass of the same computation.  The paper measures the forward pass only (Sec. 5.1.2);
+ * this is the gradient of what tasp_chunk_attn computes, walked in the same arrival order
+ * (Algorithm 3): at every step the KV sub-chunks held at that step receive dk and dv from the local
+ * query rows (a key is held at exactly one step, so its rows are complete after that step), and dq
+ * accumulates over the steps.  The probabilities are recomputed from the final lse:
+ *   p = exp(scale q.k - lse),  delta = sum_d dout*out,  ds = p (dout.v - delta),
+ *   dq = scale ds k,  dk = scale ds^T q,  dv = p^T dout.
+ * dk and dv are THIS RANK'S contribution (its local query rows); with grouped-query attention a KV
+ * head receives the sum over its query heads.  In a distributed run they would travel on along the
+ * rings with their sub-chunk; that transport is not part of this library.
+ *
+ * All tensor pointers are DEVICE pointers, 16-byte aligned, dense row-major, laid out as for
+ * tasp_chunk_attn: q, out, dout, dq [B, L, Hq, d]; k, v, dk, dv [B, S, Hkv, d]; lse [B, L, Hq] fp32
+ * (out and lse as written by tasp_chunk_attn on the same inputs).  dtype must be TASP_DTYPE_BF16
+ * (anything else: TASP_EUNSUPPORTED_SHAPE); d is 64 or 128.  Every row of dq, dk and dv is written.
+ * workspace: device, 256-byte aligned, at least tasp_chunk_attn_bwd_workspace_bytes() (an fp32 copy
+ * of dq and the delta vector); contents are scratch.  Kernels are enqueued on hip_stream; the call
+ * returns without synchronising.  Errors as for tasp_chunk_attn.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct tasp_attn_bwd_args {
+  const void*  q;
+  const void*  k;
+  const void*  v;
+  const void*  out;
+  const float* lse;
+  const void*  dout;
+  void*        dq;
+  void*        dk;
+  void*        dv;
+  void*        workspace;
+  size_t       workspace_bytes;
+  int64_t      S;
+  int32_t      Hq, Hkv, d;
+  int32_t      dtype;
+  int32_t      mask_mode;
+  int32_t      order;
+  float        softmax_scale;   /* 0: 1/sqrt(d) */
+  int32_t      batch;           /* 0 counts as 1 */
+} tasp_attn_bwd_args;
+
+size_t tasp_chunk_attn_bwd_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_bwd_args* a);
+int    tasp_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args* a, void* hip_stream);
+
+/* The same call with every launch bracketed by HIP events; synchronises the stream.  dq = the
+ * kernels that accumulate dq, dkv = the kernels that write dk and dv, other = delta, clearing the
+ * fp32 dq and the final cast. */
+typedef struct tasp_bwd_profile {
+  double  dq_ms, dkv_ms, other_ms;
+  int32_t dq_launches, dkv_launches, other_launches;
+} tasp_bwd_profile;
+int tasp_chunk_attn_bwd_profile(const tasp_schedule_t* s, const tasp_attn_bwd_args* a, void* hip_stream,
+                                tasp_bwd_profile* out);
+
+/* Algorithmic work of one backward call: five products against the forward's two, i.e. 2.5 times
+ * tasp_chunk_attn_flops (the recomputation of the scores in both kernels is not counted). */
+double tasp_chunk_attn_bwd_flops(const tasp_schedule_t* s, const tasp_attn_bwd_args* a);
+
 #ifdef __cplusplus
 }
 #endif

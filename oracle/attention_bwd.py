@@ -19,6 +19,9 @@ Readings (the paper is silent on each; tests/test_oracle_attention_bwd.py pins t
       dq = scale * ds k,  dk = scale * ds^T q,  dv = p^T dout.
   B3  grouped-query attention: a KV head receives the sum over the query heads that read it.
   B4  a query row that saw no key (lse = -inf) has p = 0 and contributes nothing.
+  B5  the forward output is an INPUT of the backward call (it was stored, in the storage precision);
+      ``out_rows`` passes such a stored copy, and delta is then taken from it as B2 says.  Left out,
+      the exact output is used, which is the gradient's plain definition.
 """
 import math
 
@@ -28,11 +31,11 @@ from . import attention as att
 from . import schedule as sch
 
 
-def dense_grads(q_rows, positions, k, v, dout_rows, causal, scale=None):
+def dense_grads(q_rows, positions, k, v, dout_rows, causal, scale=None, out_rows=None):
     """Gradients of sum(dout * softmax(q k^T scale) v) for a few query rows of ONE head.
 
-    q_rows, dout_rows [R, d]; positions [R]; k, v [S, d] (natural token order).
-    Returns (dq [R, d], dk [S, d], dv [S, d]) in fp64.
+    q_rows, dout_rows [R, d]; positions [R]; k, v [S, d] (natural token order); out_rows [R, d]
+    (reading B5) or None.  Returns (dq [R, d], dk [S, d], dv [S, d]) in fp64.
     """
     q = np.asarray(q_rows, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
@@ -57,7 +60,7 @@ def dense_grads(q_rows, positions, k, v, dout_rows, causal, scale=None):
         e = np.exp(s - np.where(seen, mx, 0.0))
         den = e.sum(axis=1, keepdims=True)
         p = np.where(seen, e / np.where(den > 0, den, 1.0), 0.0)      # softmax rows (B4: all zero if nothing seen)
-        out = p @ v
+        out = p @ v if out_rows is None else np.asarray(out_rows, dtype=np.float64)[r0:r1]
         dp = do[r0:r1] @ v.T                                          # d loss / d p
         delta = (do[r0:r1] * out).sum(axis=1, keepdims=True)
         ds = p * (dp - delta)                                         # softmax Jacobian applied

@@ -26,6 +26,8 @@ EXPORTS = [
     "tasp_step_segments", "tasp_chunk_attn_workspace_bytes", "tasp_chunk_attn", "tasp_step_attn",
     "tasp_lse_merge", "tasp_chunk_attn_flops", "tasp_chunk_attn_profile", "tasp_last_hip_error", "tasp_calibration_copy",
     "tasp_lse_merge_many", "tasp_calibration_mfma", "tasp_schedule_create_multinode",
+    "tasp_chunk_attn_bwd_workspace_bytes", "tasp_chunk_attn_bwd", "tasp_chunk_attn_bwd_profile",
+    "tasp_chunk_attn_bwd_flops",
 ]
 
 
@@ -49,6 +51,21 @@ class AttnArgs(C.Structure):
 class Profile(C.Structure):
     _fields_ = [("attn_ms", C.c_double), ("merge_ms", C.c_double), ("other_ms", C.c_double),
                 ("attn_launches", C.c_int32), ("merge_launches", C.c_int32), ("other_launches", C.c_int32)]
+
+
+class AttnBwdArgs(C.Structure):
+    _fields_ = [
+        ("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p), ("out", C.c_void_p), ("lse", C.c_void_p),
+        ("dout", C.c_void_p), ("dq", C.c_void_p), ("dk", C.c_void_p), ("dv", C.c_void_p),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("S", C.c_int64),
+        ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32), ("dtype", C.c_int32),
+        ("mask_mode", C.c_int32), ("order", C.c_int32), ("softmax_scale", C.c_float), ("batch", C.c_int32),
+    ]
+
+
+class BwdProfile(C.Structure):
+    _fields_ = [("dq_ms", C.c_double), ("dkv_ms", C.c_double), ("other_ms", C.c_double),
+                ("dq_launches", C.c_int32), ("dkv_launches", C.c_int32), ("other_launches", C.c_int32)]
 
 
 def _load():
@@ -94,6 +111,12 @@ def _load():
     lib.tasp_calibration_mfma.argtypes = [C.c_int32, C.POINTER(C.c_double), C.c_void_p]
     lib.tasp_chunk_attn_flops.argtypes = [C.c_void_p, C.POINTER(AttnArgs)]
     lib.tasp_chunk_attn_flops.restype = C.c_double
+    lib.tasp_chunk_attn_bwd_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(AttnBwdArgs)]
+    lib.tasp_chunk_attn_bwd_workspace_bytes.restype = C.c_size_t
+    lib.tasp_chunk_attn_bwd.argtypes = [C.c_void_p, C.POINTER(AttnBwdArgs), C.c_void_p]
+    lib.tasp_chunk_attn_bwd_profile.argtypes = [C.c_void_p, C.POINTER(AttnBwdArgs), C.c_void_p, C.POINTER(BwdProfile)]
+    lib.tasp_chunk_attn_bwd_flops.argtypes = [C.c_void_p, C.POINTER(AttnBwdArgs)]
+    lib.tasp_chunk_attn_bwd_flops.restype = C.c_double
     return lib
 
 
@@ -229,6 +252,56 @@ class ChunkAttnPlan:
 def tasp_chunk_attn(q, k, v, schedule, mask_mode, order=ORDER_TASP, fuse_merge=False, softmax_scale=0.0):
     """One rank's forward pass (Algorithm 3).  Returns (out [L, Hq, d] in q's dtype, lse [L, Hq] fp32)."""
     return ChunkAttnPlan(schedule, q, k, v, mask_mode, order, fuse_merge, softmax_scale).run()
+
+
+class ChunkAttnBwdPlan:
+    """Buffers of one tasp_chunk_attn_bwd shape (dq, dk, dv, workspace), so that repeated calls allocate nothing."""
+
+    def __init__(self, schedule, q, k, v, out, lse, dout, mask_mode, order=ORDER_TASP, softmax_scale=0.0):
+        torch = _torch()
+        fa = _args(q, k, v, mask_mode, order, True, softmax_scale)
+        if q.shape[-3] * schedule.n_ranks != k.shape[-3]:
+            raise ValueError("q must hold S / N local rows")
+        for name, t, like in (("out", out, q), ("dout", dout, q)):
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == like.dtype and t.shape == like.shape):
+                raise ValueError("%s must be a contiguous device tensor shaped and typed like q" % name)
+        if not (lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and lse.shape == q.shape[:-1]):
+            raise ValueError("lse must be a contiguous fp32 device tensor [.., L, Hq]")
+        self.schedule = schedule
+        a = AttnBwdArgs()
+        a.q, a.k, a.v, a.out, a.lse, a.dout = (t.data_ptr() for t in (q, k, v, out, lse, dout))
+        a.S, a.Hq, a.Hkv, a.d, a.batch, a.dtype = fa.S, fa.Hq, fa.Hkv, fa.d, fa.batch, fa.dtype
+        a.mask_mode, a.order, a.softmax_scale = mask_mode, order, softmax_scale
+        self.dq, self.dk, self.dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        a.dq, a.dk, a.dv = self.dq.data_ptr(), self.dk.data_ptr(), self.dv.data_ptr()
+        nbytes = lib.tasp_chunk_attn_bwd_workspace_bytes(schedule.handle, C.byref(a))
+        self.workspace = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=q.device)
+        a.workspace, a.workspace_bytes = self.workspace.data_ptr(), nbytes
+        self.args = a
+        self._keep = (q, k, v, out, lse, dout)
+
+    def run(self, stream=None):
+        torch = _torch()
+        s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        _check(lib.tasp_chunk_attn_bwd(self.schedule.handle, C.byref(self.args), C.c_void_p(s)), "tasp_chunk_attn_bwd")
+        return self.dq, self.dk, self.dv
+
+    def profile(self, stream=None):
+        torch = _torch()
+        s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        prof = BwdProfile()
+        _check(lib.tasp_chunk_attn_bwd_profile(self.schedule.handle, C.byref(self.args), C.c_void_p(s), C.byref(prof)),
+               "tasp_chunk_attn_bwd_profile")
+        return prof
+
+    def flops(self):
+        return lib.tasp_chunk_attn_bwd_flops(self.schedule.handle, C.byref(self.args))
+
+
+def tasp_chunk_attn_bwd(q, k, v, out, lse, dout, schedule, mask_mode, order=ORDER_TASP, softmax_scale=0.0):
+    """One rank's backward pass in the forward's arrival order.  out, lse: what tasp_chunk_attn returned
+    for the same inputs.  Returns (dq like q, dk like k, dv like v); dk, dv are this rank's contribution."""
+    return ChunkAttnBwdPlan(schedule, q, k, v, out, lse, dout, mask_mode, order, softmax_scale).run()
 
 
 def tasp_step_attn(q, k, v, schedule, mask_mode, step, order=ORDER_TASP, softmax_scale=0.0):

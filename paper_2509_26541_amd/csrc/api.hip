@@ -1,5 +1,6 @@
 // Host orchestration of one rank's forward pass (Algorithm 3): N steps, each one attention launch
-// over the sub-chunks the schedule delivers at that step, followed by update_out_lse.
+// over the sub-chunks the schedule delivers at that step, followed by update_out_lse; and of the
+// backward pass, which walks the same steps in the same order.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -133,6 +134,37 @@ hipError_t launch_attn(const AttnLaunch& lp, const tasp_attn_args* a, hipStream_
                                      : tasp::launch_attn_fp32(lp, a->d, stream);
 }
 
+// ---- backward pass
+// The forward's argument block with the fields both passes share, so that one validation serves both.
+tasp_attn_args as_forward(const tasp_attn_bwd_args* b) {
+  tasp_attn_args a{};
+  a.q = b->q; a.k = b->k; a.v = b->v;
+  a.S = b->S; a.Hq = b->Hq; a.Hkv = b->Hkv; a.d = b->d;
+  a.dtype = b->dtype; a.mask_mode = b->mask_mode; a.order = b->order;
+  a.fuse_merge = 1; a.softmax_scale = b->softmax_scale; a.batch = b->batch;
+  return a;
+}
+
+int validate_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args* b, tasp_attn_args* a, Shape* sh) {
+  if (s == nullptr || b == nullptr) return TASP_EINVAL;
+  *a = as_forward(b);
+  int st = validate(s, a, sh);
+  if (st != TASP_OK) return st;
+  if (b->dtype != TASP_DTYPE_BF16) return TASP_EUNSUPPORTED_SHAPE;      // the backward kernels are bf16 only
+  if (b->out == nullptr || b->lse == nullptr || b->dout == nullptr || b->dq == nullptr || b->dk == nullptr ||
+      b->dv == nullptr)
+    return TASP_EINVAL;
+  // the kernels address Q and dout with 32-bit byte offsets
+  if (static_cast<int64_t>(sh->L) * b->Hq * b->d * 2 > (int64_t{1} << 32)) return TASP_EUNSUPPORTED_SHAPE;
+  const uintptr_t all = reinterpret_cast<uintptr_t>(b->out) | reinterpret_cast<uintptr_t>(b->dout) |
+                        reinterpret_cast<uintptr_t>(b->dq) | reinterpret_cast<uintptr_t>(b->dk) |
+                        reinterpret_cast<uintptr_t>(b->dv);
+  if (all & 15) return TASP_EALIGN;
+  return TASP_OK;
+}
+
+struct BwdSpans { enum Kind { kDq = 0, kDkv = 1, kOther = 2 }; };
+
 }  // namespace
 
 namespace tasp {
@@ -265,6 +297,119 @@ static int run_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, voi
 
 int tasp_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream) {
   return run_chunk_attn(s, a, hip_stream, nullptr);
+}
+
+size_t tasp_chunk_attn_bwd_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_bwd_args* b) {
+  if (s == nullptr || b == nullptr || b->S <= 0 || b->Hq <= 0 || b->d <= 0 || s->n <= 0 || b->batch < 0) return 0;
+  const int64_t L = b->S / s->n;
+  const size_t B = static_cast<size_t>(b->batch == 0 ? 1 : b->batch);
+  return align_up(B * L * b->Hq * b->d * sizeof(float)) + align_up(B * L * b->Hq * sizeof(float));   // fp32 dq, delta
+}
+
+double tasp_chunk_attn_bwd_flops(const tasp_schedule_t* s, const tasp_attn_bwd_args* b) {
+  if (s == nullptr || b == nullptr) return 0.0;
+  const tasp_attn_args a = as_forward(b);
+  return 2.5 * tasp_chunk_attn_flops(s, &a);
+}
+
+static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args* b, void* hip_stream, Profiler* prof) {
+  Shape sh;
+  tasp_attn_args a;
+  int st = validate_bwd(s, b, &a, &sh);
+  if (st != TASP_OK) return st;
+  const size_t need = tasp_chunk_attn_bwd_workspace_bytes(s, b);
+  if (b->workspace == nullptr || b->workspace_bytes < need) return TASP_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(b->workspace) & (kAlign - 1)) return TASP_EALIGN;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  float* dq_acc = static_cast<float*>(b->workspace);
+  float* delta = reinterpret_cast<float*>(static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes));
+  const int64_t n_q_elems = static_cast<int64_t>(sh.B) * sh.L * b->Hq * b->d;
+
+  try {
+    {
+      Scope sc(prof, BwdSpans::kOther);
+      if (tasp::launch_bwd_delta_bf16(b->out, b->dout, delta, static_cast<int64_t>(sh.B) * sh.L * b->Hq, b->d, stream) !=
+          hipSuccess)
+        return TASP_EHIP;
+      if (tasp::launch_zero_f32(dq_acc, n_q_elems, stream) != hipSuccess) return TASP_EHIP;
+    }
+    std::vector<tasp::QueryBlock> empty;
+    std::vector<tasp::Segment> ranges;
+    for (int step = 0; step < s->n; ++step) {
+      AttnLaunch lp{};
+      empty.clear();
+      st = build_step(s, &a, step, &lp, &empty);
+      if (st != TASP_OK) return st;
+      tasp::BwdLaunch bp{};
+      bp.q = b->q; bp.k = b->k; bp.v = b->v; bp.dout = b->dout; bp.lse = b->lse; bp.delta = delta;
+      bp.dq_acc = dq_acc; bp.dk = b->dk; bp.dv = b->dv;
+      bp.Hq = lp.Hq; bp.Hkv = lp.Hkv; bp.causal = lp.causal; bp.scale = lp.scale; bp.batch = lp.batch;
+      bp.q_bstride = lp.q_bstride; bp.kv_bstride = lp.kv_bstride; bp.lse_bstride = lp.lse_bstride;
+      bp.n_tasks = lp.n_tasks;
+      for (int t = 0; t < lp.n_tasks; ++t) bp.task[t] = lp.task[t];
+      bp.n_blk = tasp::n_query_blocks(b->mask_mode);
+      for (int qb = 0; qb < bp.n_blk; ++qb) {
+        tasp::QueryBlock blk;
+        st = tasp::query_block(*s, b->S, b->mask_mode, qb, &blk);
+        if (st != TASP_OK) return st;
+        bp.blk[qb] = {static_cast<int32_t>(blk.local_row0), static_cast<int32_t>(blk.rows), static_cast<int32_t>(blk.pos0)};
+      }
+      st = tasp::step_key_ranges(*s, b->S, b->mask_mode, b->order, step, &ranges);
+      if (st != TASP_OK) return st;
+      if (ranges.size() > static_cast<size_t>(tasp::kMaxSeg)) return TASP_EUNSUPPORTED_SHAPE;
+      bp.n_rng = static_cast<int32_t>(ranges.size());
+      int64_t vpos = 0;
+      for (size_t i = 0; i < ranges.size(); ++i) {
+        bp.rng_start[i] = static_cast<int32_t>(ranges[i].start);
+        bp.rng_vbeg[i] = static_cast<int32_t>(vpos);
+        vpos += ranges[i].end - ranges[i].start;
+      }
+      bp.rng_vbeg[ranges.size()] = static_cast<int32_t>(vpos);
+      {
+        Scope sc(prof, BwdSpans::kDq);
+        if (tasp::launch_bwd_dq_bf16(bp, b->d, stream) != hipSuccess) return TASP_EHIP;
+      }
+      {
+        Scope sc(prof, BwdSpans::kDkv);
+        if (tasp::launch_bwd_dkv_bf16(bp, b->d, stream) != hipSuccess) return TASP_EHIP;
+      }
+    }
+    {
+      Scope sc(prof, BwdSpans::kOther);
+      if (tasp::launch_cast_bf16(dq_acc, b->dq, n_q_elems, stream) != hipSuccess) return TASP_EHIP;
+    }
+  } catch (...) {
+    return TASP_ENOMEM;
+  }
+  return TASP_OK;
+}
+
+int tasp_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args* b, void* hip_stream) {
+  return run_chunk_attn_bwd(s, b, hip_stream, nullptr);
+}
+
+int tasp_chunk_attn_bwd_profile(const tasp_schedule_t* s, const tasp_attn_bwd_args* b, void* hip_stream,
+                                tasp_bwd_profile* out) {
+  if (out == nullptr) return TASP_EINVAL;
+  *out = tasp_bwd_profile{};
+  try {
+    Profiler prof;
+    prof.stream = static_cast<hipStream_t>(hip_stream);
+    const int st = run_chunk_attn_bwd(s, b, hip_stream, &prof);
+    if (tasp::note_hip(hipStreamSynchronize(prof.stream)) != hipSuccess) return TASP_EHIP;
+    if (st != TASP_OK) return st;
+    if (prof.failed) return TASP_EHIP;
+    for (const auto& sp : prof.spans) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, sp.beg, sp.end) != hipSuccess) return TASP_EHIP;
+      if (sp.kind == BwdSpans::kDq) { out->dq_ms += ms; ++out->dq_launches; }
+      else if (sp.kind == BwdSpans::kDkv) { out->dkv_ms += ms; ++out->dkv_launches; }
+      else { out->other_ms += ms; ++out->other_launches; }
+    }
+  } catch (...) {
+    return TASP_ENOMEM;
+  }
+  return TASP_OK;
 }
 
 int tasp_chunk_attn_profile(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream,

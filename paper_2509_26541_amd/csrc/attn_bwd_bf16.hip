@@ -1,0 +1,562 @@
+// Backward pass of one step of the chunked attention on gfx950: bf16 inputs, fp32 accumulation.
+//
+// The paper measures the forward pass (Sec. 5.1.2); the backward pass of a rank is the gradient of
+// the same computation and visits the KV sub-chunks in the same arrival order (Algorithm 3).  With
+// the final lse of the forward pass the probabilities of any (query, key) pair can be recomputed on
+// their own,  p = exp(scale q.k - lse),  so a step needs nothing from the other steps:
+//     delta_i = sum_d dout_i out_i                      (once per call)
+//     ds_ij   = p_ij (dout_i . v_j - delta_i)
+//     dq_i   += scale sum_j ds_ij k_j                   (accumulated over the steps)
+//     dk_j    = scale sum_i ds_ij q_i,   dv_j = sum_i p_ij dout_i      (complete after the key's step)
+//
+// Two kernels per step, both built the same way.  One operand pair is stationary: a wavefront keeps
+// the rows of 32 queries (Q, dout) or of 32 keys (K, V) in registers as B operands.  The other pair
+// is streamed through LDS in 64-row tiles (direct global->LDS loads, two stages).  With X the
+// stationary and Y the streamed side the products are
+//     T1 = Y1 X1^T,  T2 = Y2 X2^T      (scores and dout.v, one stationary row per lane column)
+//     acc += Y^T E                     (E = ds or p in bf16, already in B-operand layout)
+// all with v_mfma_f32_32x32x16_bf16; Y is read from LDS both row-wise (16-byte reads) and
+// transposed (ds_read_b64_tr_b16) out of the same tile, whose 16-byte units are XOR-swizzled so
+// that neither read pattern conflicts on banks.
+//   dq kernel:  X = (Q, dout) of 128 queries per workgroup, Y = (K, V) tiles of the step's keys the
+//               query tile can see, E = ds^T, acc = dq^T.
+//   dkv kernel: X = (K, V) of 128 keys of the step per workgroup, Y = (Q, dout) tiles of every query
+//               head of the group and every local query row that can see them, E = p and ds,
+//               acc = dv^T and dk^T.
+// Sub-chunk lengths are no tile multiples, so both walk a virtual concatenation of key ranges and
+// gather rows, as the forward kernel does.
+#include <hip/hip_runtime.h>
+
+#include <climits>
+
+#include "internal.hpp"
+
+namespace tasp {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+
+constexpr int BT = 64;             // streamed rows per tile
+constexpr int BS = 128;            // stationary rows per workgroup (32 per wavefront)
+constexpr int NTHREADS = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <int D>
+struct BCfg {
+  static constexpr int UNITS = D / 8;                   // 16-byte units per row
+  static constexpr int RPP = NTHREADS / UNITS;          // rows filled per pass (16 or 32)
+  static constexpr int PASSES = BT / RPP;
+  static constexpr int ROWS_PER_LINE = 16 / UNITS;      // rows per 256-byte bank line (1 or 2)
+  static constexpr int TILE_BYTES = BT * D * 2;
+  static constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // (Y1 tile, Y2 tile)
+  // Physical unit of logical unit `unit` of row `row`.  x counts bank lines; the XOR value is a
+  // bijection of 16 consecutive lines (row-wise reads: 32 lanes, one row each, same logical unit)
+  // and differs in its upper bits between neighbouring lines (transposed reads: 4 rows, 2 units).
+  __device__ static int swz(int row, int unit) {
+    const int x = (row / ROWS_PER_LINE) % UNITS;
+    return unit ^ ((x % (UNITS / 4)) * 4 + x / (UNITS / 4));
+  }
+};
+
+// One direct global->LDS load of 16 bytes per lane: lane l reads base + off, its bytes land at
+// lds_base + 16 l.  The compiler does not see it as a memory operation; every use is followed by
+// s_waitcnt vmcnt(0) and a barrier before the tile is read.
+__device__ inline void dma16(const unsigned char* base, unsigned off, unsigned char* lds_base) {
+  const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)lds_base));
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(off), "s"(base)
+               : "m0", "memory");
+}
+__device__ inline void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+__device__ inline bf16x8 lds_row8(const unsigned char* p) {
+  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(p));
+}
+// A operand of Y^T E: 32 columns of Y (rows of Y^T) by 16 rows of Y, from two transposing reads
+// eight rows apart.
+__device__ inline bf16x8 lds_tr8(const unsigned char* lo, const unsigned char* hi) {
+  const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds_void_ptr)const_cast<unsigned char*>(lo));
+  const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds_void_ptr)const_cast<unsigned char*>(hi));
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+__device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ inline unsigned pack2(float lo, float hi) {
+  const bf16x2 pk = {static_cast<__bf16>(lo), static_cast<__bf16>(hi)};
+  return __builtin_bit_cast(unsigned, pk);
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs; remap so that each XCD gets a contiguous run.
+__device__ inline int xcd_contiguous(int block, int nblocks) {
+  const int xcd = block & 7, slot = block >> 3;
+  const int q8 = nblocks >> 3, r8 = nblocks & 7;
+  return xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
+}
+
+// Per-lane byte offsets inside a tile for the two LDS read patterns.
+template <int D>
+struct ReadAddr {
+  using C = BCfg<D>;
+  unsigned row[D / 16];        // row lq (+32 per block), logical unit 2 ks + h
+  unsigned tr[D / 32][2];      // transposed: 16-row group at +16 rows per group, rows +0 and +8
+  __device__ void init(int lane) {
+    const int lq = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) row[ks] = (lq * C::UNITS + C::swz(lq, 2 * ks + h)) * 16;
+    // 16-lane group a = lane/16 serves columns 16 (a%2) .. +16 of a 32-wide block for lane half
+    // a/2; lane jj of the group points at row 4 (a/2) + jj/4, 4 columns.
+    const int ga = lane >> 4, jj = lane & 15;
+    const int r0 = 4 * (ga >> 1) + (jj >> 2);
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) {
+      const int unit = 4 * db + 2 * (ga & 1) + ((jj & 3) >> 1);
+      tr[db][0] = (r0 * C::UNITS + C::swz(r0, unit)) * 16 + 8 * (jj & 1);
+      tr[db][1] = ((r0 + 8) * C::UNITS + C::swz(r0 + 8, unit)) * 16 + 8 * (jj & 1);
+    }
+  }
+};
+
+// ------------------------------------------------------------------------------------------------
+// dq kernel
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(NTHREADS) void bwd_dq_kernel(const BwdLaunch p) {
+  using C = BCfg<D>;
+  constexpr int KS = D / 16, DB = D / 32;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE_BYTES];   // stage: K tile, V tile
+  __shared__ __attribute__((aligned(16))) int s_tok[2][BT];   // global position of every key row (INT_MAX: none)
+  __shared__ int e_vbeg[kMaxSeg + 1];   // effective segments: start in the virtual concatenation
+  __shared__ int e_goff[kMaxSeg];       //   global position minus virtual position
+  __shared__ int e_n;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, lq = lane & 31;
+
+  // ---- which (sequence, KV head, task, query tile, query head): KV-head-major inside an XCD
+  const int G = p.Hq / p.Hkv;
+  const int tiles0 = (p.task[0].n_q + BS - 1) / BS;
+  const int tiles1 = p.n_tasks > 1 ? (p.task[1].n_q + BS - 1) / BS : 0;
+  const int per_g = (tiles0 + tiles1) * G, per_b = per_g * p.Hkv;
+  const int w_all = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int bi = w_all / per_b;
+  const int w = w_all - bi * per_b;
+  const int g = w / per_g;
+  int rem = w - g * per_g;
+  const int tsk = rem >= tiles0 * G ? 1 : 0;
+  if (tsk) rem -= tiles0 * G;
+  const int tile_q = rem / G;
+  const int hq = g * G + rem % G;
+  const AttnTask& T = p.task[tsk];
+  const int q_tile_row0 = tile_q * BS;
+  const int q_rows_here = min(BS, T.n_q - q_tile_row0);
+  const int q_last = T.q_pos0 + q_tile_row0 + q_rows_here - 1;
+
+  // ---- effective segments of this query tile: drop what the causal mask hides from every row
+  if (tid == 0) {
+    int n = 0, vpos = 0;
+    for (int s = 0; s < T.n_seg; ++s) {
+      const int a = T.seg_start[s];
+      const int b = p.causal ? min(T.seg_end[s], q_last + 1) : T.seg_end[s];
+      if (a >= b) continue;
+      e_vbeg[n] = vpos; e_goff[n] = a - vpos; vpos += b - a; ++n;
+    }
+    e_vbeg[n] = vpos;
+    e_n = n;
+  }
+  __syncthreads();
+  const int n_eff = e_n;
+  const int total_keys = e_vbeg[n_eff];
+  const int n_tiles = (total_keys + BT - 1) / BT;
+
+  // ---- stationary side: this lane's query (column lq of the wave's strip), d = 16 ks + 8 h .. +8
+  const int my_q = q_tile_row0 + wave * 32 + lq;
+  const bool q_valid = my_q < T.n_q;
+  const int64_t q_row = T.q_row0 + (q_valid ? my_q : T.n_q - 1);
+  const int64_t qoff = bi * p.q_bstride + (q_row * p.Hq + hq) * D;
+  bf16x8 qf[KS], dof[KS];
+  {
+    const __bf16* qs = static_cast<const __bf16*>(p.q) + qoff + 8 * h;
+    const __bf16* ds = static_cast<const __bf16*>(p.dout) + qoff + 8 * h;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qf[ks] = *reinterpret_cast<const bf16x8*>(qs + 16 * ks);
+      dof[ks] = *reinterpret_cast<const bf16x8*>(ds + 16 * ks);
+    }
+  }
+  const int64_t loff = bi * p.lse_bstride + q_row * p.Hq + hq;
+  const float lse_raw = p.lse[loff];
+  // a row that saw no key (lse = -inf) contributes nothing; exp2(x - inf) = 0 does that
+  const float lse2 = (q_valid && lse_raw > -__builtin_inff()) ? lse_raw * kLog2e : __builtin_inff();
+  const float dl = p.delta[loff];
+  const int q_pos = p.causal ? T.q_pos0 + my_q : INT_MAX - 1;
+  const float c = p.scale * kLog2e;
+
+  // ---- loader: this thread fills rows fr + RPP i, physical unit fu of the K and the V tile
+  const int fr = tid / C::UNITS, fu = tid % C::UNITS;
+  const unsigned row_bytes = static_cast<unsigned>(p.Hkv) * D * 2;
+  const unsigned col = C::swz(fr, fu) * 16;    // the same for every pass: RPP is a multiple of 16
+  static_assert(C::RPP % 16 == 0, "");
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const unsigned char* Kg = static_cast<const unsigned char*>(p.k) + (bi * p.kv_bstride + static_cast<int64_t>(g) * D) * 2;
+  const unsigned char* Vg = static_cast<const unsigned char*>(p.v) + (bi * p.kv_bstride + static_cast<int64_t>(g) * D) * 2;
+  int segi[C::PASSES];
+#pragma unroll
+  for (int i = 0; i < C::PASSES; ++i) segi[i] = 0;
+  auto fetch = [&](int t, int stage) __attribute__((always_inline)) {
+    unsigned char* dst = smem + stage * C::STAGE_BYTES + wave_u * 1024;
+#pragma unroll
+    for (int i = 0; i < C::PASSES; ++i) {
+      const int r = fr + C::RPP * i, v = t * BT + r;
+      int j = segi[i];
+      while (j < n_eff && v >= e_vbeg[j + 1]) ++j;       // rows only move forward
+      segi[i] = j;
+      const int tok = j < n_eff ? v + e_goff[j] : INT_MAX;
+      s_tok[stage][r] = tok;                              // the UNITS lanes of a row write the same value
+      const unsigned off = (tok == INT_MAX ? 0u : static_cast<unsigned>(tok)) * row_bytes + col;
+      dma16(Kg, off, dst + i * NTHREADS * 16);
+      dma16(Vg, off, dst + C::TILE_BYTES + i * NTHREADS * 16);
+    }
+  };
+
+  ReadAddr<D> ra;
+  ra.init(lane);
+
+  f32x16 dq[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
+
+  if (n_tiles > 0) fetch(0, 0);
+  for (int t = 0; t < n_tiles; ++t) {
+    const int stage = t & 1;
+    wait_all_loads();
+    __syncthreads();                 // tile t is complete; nobody reads the other stage any more
+    if (t + 1 < n_tiles) fetch(t + 1, stage ^ 1);
+    const unsigned char* kt = smem + stage * C::STAGE_BYTES;
+    const unsigned char* vt = kt + C::TILE_BYTES;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16 S, dP;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { S[i] = 0.f; dP[i] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) S = mfma(lds_row8(kt + ra.row[ks] + kb * 32 * D * 2), qf[ks], S);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) dP = mfma(lds_row8(vt + ra.row[ks] + kb * 32 * D * 2), dof[ks], dP);
+      // ds^T for the 32 keys of this block (register 4 i4 + e: key 8 i4 + 4 h + e)
+      float ds[16];
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const i32x4 tk = *reinterpret_cast<const i32x4*>(&s_tok[stage][32 * kb + 8 * i4 + 4 * h]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * i4 + e;
+          const float x = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c, -lse2));
+          const float pr = tk[e] > q_pos ? 0.f : x;
+          ds[i] = pr * (dP[i] - dl);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const u32x4 ef = {pack2(ds[8 * j + 0], ds[8 * j + 1]), pack2(ds[8 * j + 2], ds[8 * j + 3]),
+                          pack2(ds[8 * j + 4], ds[8 * j + 5]), pack2(ds[8 * j + 6], ds[8 * j + 7])};
+        const bf16x8 eb = __builtin_bit_cast(bf16x8, ef);
+        const int grp = (2 * kb + j) * 16 * D * 2;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          dq[db] = mfma(lds_tr8(kt + ra.tr[db][0] + grp, kt + ra.tr[db][1] + grp), eb, dq[db]);
+      }
+    }
+  }
+  wait_all_loads();
+
+  // ---- epilogue: dq_acc += scale dq.  A lane owns one query row; per (db, i4) it holds 4
+  // consecutive columns and its partner lane (+32) the next 4.
+  if (q_valid) {
+    float* dst0 = p.dq_acc + qoff + 4 * h;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        f32x4* dst = reinterpret_cast<f32x4*>(dst0 + 32 * db + 8 * i4);
+        f32x4 val = *dst;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) val[e] = __builtin_fmaf(dq[db][4 * i4 + e], p.scale, val[e]);
+        *dst = val;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dk / dv kernel
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(NTHREADS) void bwd_dkv_kernel(const BwdLaunch p) {
+  using C = BCfg<D>;
+  constexpr int KS = D / 16, DB = D / 32;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE_BYTES];   // stage: Q tile, dout tile
+  __shared__ __attribute__((aligned(16))) float s_l2[2][BT];    // lse log2(e) of the tile's queries (+inf: row contributes nothing)
+  __shared__ __attribute__((aligned(16))) float s_dl[2][BT];    // delta of the tile's queries
+  __shared__ int s_tmin;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, lq = lane & 31;
+
+  // ---- which (sequence, KV head, key tile)
+  const int G = p.Hq / p.Hkv;
+  const int total_keys = p.rng_vbeg[p.n_rng];
+  const int ktiles = (total_keys + BS - 1) / BS;
+  const int w_all = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int bi = w_all / (ktiles * p.Hkv);
+  const int w = w_all - bi * (ktiles * p.Hkv);
+  const int g = w / ktiles;
+  const int v0 = (w - g * ktiles) * BS;        // first key of the tile in the virtual concatenation
+
+  // smallest global position among the keys of the tile: queries before it see none of them
+  if (tid == 0) {
+    int tmin = INT_MAX;
+    for (int j = 0; j < p.n_rng; ++j) {
+      const int a = max(v0, p.rng_vbeg[j]), b = min(v0 + BS, p.rng_vbeg[j + 1]);
+      if (a < b) tmin = min(tmin, p.rng_start[j] + (a - p.rng_vbeg[j]));
+    }
+    s_tmin = tmin;
+  }
+
+  // ---- stationary side: this lane's key (column lq of the wave's strip)
+  const int my_v = v0 + wave * 32 + lq;
+  int key_tok = INT_MAX;
+  for (int j = 0; j < p.n_rng; ++j)
+    if (my_v >= p.rng_vbeg[j] && my_v < p.rng_vbeg[j + 1]) key_tok = p.rng_start[j] + (my_v - p.rng_vbeg[j]);
+  const bool key_valid = key_tok != INT_MAX;
+  const int64_t koff = bi * p.kv_bstride + (static_cast<int64_t>(key_valid ? key_tok : p.rng_start[0]) * p.Hkv + g) * D;
+  bf16x8 kf[KS], vf[KS];
+  {
+    const __bf16* ks_ = static_cast<const __bf16*>(p.k) + koff + 8 * h;
+    const __bf16* vs_ = static_cast<const __bf16*>(p.v) + koff + 8 * h;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      kf[ks] = *reinterpret_cast<const bf16x8*>(ks_ + 16 * ks);
+      vf[ks] = *reinterpret_cast<const bf16x8*>(vs_ + 16 * ks);
+    }
+  }
+  const float c = p.scale * kLog2e;
+  __syncthreads();
+  const int tmin = s_tmin;
+
+  // ---- the streamed side: for every query head of the group and every query block, the 64-row
+  // tiles from the first one that holds a row at or after tmin.  Iteration state (head, block, tile).
+  auto first_tile = [&](int blk) __attribute__((always_inline)) {
+    return p.causal ? max(0, (tmin - p.blk[blk].pos0) / BT) : 0;
+  };
+  auto tiles_of = [&](int blk) __attribute__((always_inline)) { return (p.blk[blk].n + BT - 1) / BT; };
+  struct It { int hh, blk, qt; };
+  // the first state at or after (hh, blk, qt) that has work; hh == G means done
+  auto settle = [&](It it) __attribute__((always_inline)) {
+    while (it.hh < G) {
+      if (it.blk < p.n_blk && it.qt < tiles_of(it.blk)) return it;
+      ++it.blk;
+      if (it.blk >= p.n_blk) { it.blk = 0; ++it.hh; }
+      it.qt = first_tile(it.blk);
+    }
+    return it;
+  };
+
+  const int fr = tid / C::UNITS, fu = tid % C::UNITS;
+  const unsigned col = C::swz(fr, fu) * 16;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const unsigned char* Qg = static_cast<const unsigned char*>(p.q) + bi * p.q_bstride * 2;
+  const unsigned char* Og = static_cast<const unsigned char*>(p.dout) + bi * p.q_bstride * 2;
+  const unsigned q_row_bytes = static_cast<unsigned>(p.Hq) * D * 2;
+  auto fetch = [&](const It& it, int stage) __attribute__((always_inline)) {
+    const BwdBlock& B = p.blk[it.blk];
+    const int hq = g * G + it.hh;
+    unsigned char* dst = smem + stage * C::STAGE_BYTES + wave_u * 1024;
+#pragma unroll
+    for (int i = 0; i < C::PASSES; ++i) {
+      const int r = min(it.qt * BT + fr + C::RPP * i, B.n - 1);      // rows past the end repeat the last one and are switched off below
+      const unsigned off = static_cast<unsigned>(B.row0 + r) * q_row_bytes + static_cast<unsigned>(hq) * D * 2 + col;
+      dma16(Qg, off, dst + i * NTHREADS * 16);
+      dma16(Og, off, dst + C::TILE_BYTES + i * NTHREADS * 16);
+    }
+    if (tid < BT) {
+      const int r = it.qt * BT + tid;
+      float l2 = __builtin_inff(), dl = 0.f;
+      if (r < B.n) {
+        const int64_t o = bi * p.lse_bstride + static_cast<int64_t>(B.row0 + r) * p.Hq + hq;
+        const float l = p.lse[o];
+        if (l > -__builtin_inff()) l2 = l * kLog2e;
+        dl = p.delta[o];
+      }
+      s_l2[stage][tid] = l2;
+      s_dl[stage][tid] = dl;
+    }
+  };
+
+  ReadAddr<D> ra;
+  ra.init(lane);
+
+  f32x16 dk[DB], dv[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { dk[db][i] = 0.f; dv[db][i] = 0.f; }
+
+  It cur = settle(It{0, 0, first_tile(0)});
+  if (cur.hh < G) fetch(cur, 0);
+  int stage = 0;
+  while (cur.hh < G) {
+    const It nxt = settle(It{cur.hh, cur.blk, cur.qt + 1});
+    wait_all_loads();
+    __syncthreads();                 // the current tile is complete; nobody reads the other stage any more
+    if (nxt.hh < G) fetch(nxt, stage ^ 1);
+    const unsigned char* qt_ = smem + stage * C::STAGE_BYTES;
+    const unsigned char* ot_ = qt_ + C::TILE_BYTES;
+    const int pos0 = p.causal ? p.blk[cur.blk].pos0 + cur.qt * BT : 0;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      f32x16 S, dP;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { S[i] = 0.f; dP[i] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) S = mfma(lds_row8(qt_ + ra.row[ks] + qb * 32 * D * 2), kf[ks], S);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) dP = mfma(lds_row8(ot_ + ra.row[ks] + qb * 32 * D * 2), vf[ks], dP);
+      // p and ds for the 32 queries of this block (register 4 i4 + e: query 8 i4 + 4 h + e)
+      float pr[16], ds[16];
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int r0 = 32 * qb + 8 * i4 + 4 * h;
+        const f32x4 l2 = *reinterpret_cast<const f32x4*>(&s_l2[stage][r0]);
+        const f32x4 dl = *reinterpret_cast<const f32x4*>(&s_dl[stage][r0]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * i4 + e;
+          const int q_pos = p.causal ? pos0 + r0 + e : INT_MAX - 1;
+          const float x = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c, -l2[e]));
+          pr[i] = key_tok > q_pos ? 0.f : x;
+          ds[i] = pr[i] * (dP[i] - dl[e]);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const u32x4 pf = {pack2(pr[8 * j + 0], pr[8 * j + 1]), pack2(pr[8 * j + 2], pr[8 * j + 3]),
+                          pack2(pr[8 * j + 4], pr[8 * j + 5]), pack2(pr[8 * j + 6], pr[8 * j + 7])};
+        const u32x4 ef = {pack2(ds[8 * j + 0], ds[8 * j + 1]), pack2(ds[8 * j + 2], ds[8 * j + 3]),
+                          pack2(ds[8 * j + 4], ds[8 * j + 5]), pack2(ds[8 * j + 6], ds[8 * j + 7])};
+        const bf16x8 pb = __builtin_bit_cast(bf16x8, pf), eb = __builtin_bit_cast(bf16x8, ef);
+        const int grp = (2 * qb + j) * 16 * D * 2;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          dv[db] = mfma(lds_tr8(ot_ + ra.tr[db][0] + grp, ot_ + ra.tr[db][1] + grp), pb, dv[db]);
+          dk[db] = mfma(lds_tr8(qt_ + ra.tr[db][0] + grp, qt_ + ra.tr[db][1] + grp), eb, dk[db]);
+        }
+      }
+    }
+    cur = nxt;
+    stage ^= 1;
+  }
+  wait_all_loads();
+
+  // ---- epilogue: a lane owns one key row; per (db, i4) it holds 4 consecutive columns
+  if (key_valid) {
+    __bf16* dkp = static_cast<__bf16*>(p.dk) + koff + 4 * h;
+    __bf16* dvp = static_cast<__bf16*>(p.dv) + koff + 4 * h;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        bf16x4 a, b;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          a[e] = static_cast<__bf16>(dk[db][4 * i4 + e] * p.scale);
+          b[e] = static_cast<__bf16>(dv[db][4 * i4 + e]);
+        }
+        *reinterpret_cast<bf16x4*>(dkp + 32 * db + 8 * i4) = a;
+        *reinterpret_cast<bf16x4*>(dvp + 32 * db + 8 * i4) = b;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// delta = sum_d dout * out per (row, head); D / 8 lanes per row
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
+                                                        float* __restrict__ delta, int64_t n_rows) {
+  constexpr int LPR = D / 8;                    // lanes per (row, head)
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const int64_t row = idx / LPR;
+  const int part = static_cast<int>(idx % LPR);
+  float s = 0.f;
+  if (row < n_rows) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(out + row * D + 8 * part);
+    const bf16x8 b = *reinterpret_cast<const bf16x8*>(dout + row * D + 8 * part);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s = __builtin_fmaf(static_cast<float>(a[e]), static_cast<float>(b[e]), s);
+  }
+#pragma unroll
+  for (int m = LPR / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
+  if (row < n_rows && part == 0) delta[row] = s;
+}
+
+__global__ __launch_bounds__(256) void bwd_zero_kernel(f32x4* __restrict__ dst, int64_t n4) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i < n4) dst[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+}
+
+}  // namespace
+
+hipError_t launch_bwd_dq_bf16(const BwdLaunch& p, int d, hipStream_t stream) {
+  int64_t tiles = 0;
+  for (int t = 0; t < p.n_tasks; ++t) tiles += (p.task[t].n_q + BS - 1) / BS;
+  const int64_t blocks = tiles * p.Hq * p.batch;
+  if (blocks == 0) return hipSuccess;
+  if (blocks > INT_MAX) return hipErrorInvalidValue;
+  if (d == 128) return TASP_LAUNCH((bwd_dq_kernel<128>), dim3(static_cast<unsigned>(blocks)), dim3(NTHREADS), stream, p);
+  if (d == 64) return TASP_LAUNCH((bwd_dq_kernel<64>), dim3(static_cast<unsigned>(blocks)), dim3(NTHREADS), stream, p);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_bwd_dkv_bf16(const BwdLaunch& p, int d, hipStream_t stream) {
+  const int64_t total = p.rng_vbeg[p.n_rng];
+  const int64_t blocks = (total + BS - 1) / BS * p.Hkv * p.batch;
+  if (blocks == 0) return hipSuccess;
+  if (blocks > INT_MAX) return hipErrorInvalidValue;
+  if (d == 128) return TASP_LAUNCH((bwd_dkv_kernel<128>), dim3(static_cast<unsigned>(blocks)), dim3(NTHREADS), stream, p);
+  if (d == 64) return TASP_LAUNCH((bwd_dkv_kernel<64>), dim3(static_cast<unsigned>(blocks)), dim3(NTHREADS), stream, p);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_bwd_delta_bf16(const void* out, const void* dout, float* delta, int64_t n_rows, int d,
+                                 hipStream_t stream) {
+  if (n_rows == 0) return hipSuccess;
+  const int64_t threads = n_rows * (d / 8);
+  const int64_t blocks = (threads + 255) / 256;
+  if (blocks > INT_MAX) return hipErrorInvalidValue;
+  const __bf16* o = static_cast<const __bf16*>(out);
+  const __bf16* g = static_cast<const __bf16*>(dout);
+  if (d == 128) return TASP_LAUNCH((bwd_delta_kernel<128>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, o, g, delta, n_rows);
+  if (d == 64) return TASP_LAUNCH((bwd_delta_kernel<64>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, o, g, delta, n_rows);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_zero_f32(float* dst, int64_t n, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  if (n % 4 != 0) return hipErrorInvalidValue;
+  const int64_t blocks = (n / 4 + 255) / 256;
+  if (blocks > INT_MAX) return hipErrorInvalidValue;
+  return TASP_LAUNCH(bwd_zero_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), stream,
+                     reinterpret_cast<f32x4*>(dst), n / 4);
+}
+
+}  // namespace tasp

@@ -36,6 +36,38 @@ struct AttnLaunch {
   AttnTask task[kMaxTasks];
 };
 
+// One contiguous run of local query rows (a half-chunk of the zig-zag layout, or all rows).
+struct BwdBlock {
+  int32_t row0, n, pos0;   // first local row, rows, global position of the first row
+};
+
+// One step of the backward pass.  The dq kernel uses the forward's tasks (query block + the key
+// segments it can see); the dk/dv kernel uses every key range that arrives at the step, laid end to
+// end (rng_vbeg = start of each range in that concatenation), and the query blocks.
+struct BwdLaunch {
+  const void* q;        // [B, L, Hq, d] bf16
+  const void* k;        // [B, S, Hkv, d]
+  const void* v;
+  const void* dout;     // [B, L, Hq, d]
+  const float* lse;     // [B, L, Hq] final lse of the forward pass
+  const float* delta;   // [B, L, Hq] sum_d dout * out
+  float* dq_acc;        // [B, L, Hq, d] fp32, accumulated into
+  void* dk;             // [B, S, Hkv, d] bf16; the rows of this step's keys are written
+  void* dv;
+  int32_t Hq, Hkv;
+  int32_t causal;
+  float scale;
+  int32_t batch;
+  int64_t q_bstride, kv_bstride, lse_bstride;   // elements between sequences
+  int32_t n_tasks;
+  AttnTask task[kMaxTasks];
+  int32_t n_blk;
+  BwdBlock blk[kMaxTasks];
+  int32_t n_rng;
+  int32_t rng_start[kMaxSeg];
+  int32_t rng_vbeg[kMaxSeg + 1];
+};
+
 // Last HIP error this thread saw inside the library (hipSuccess if none); see tasp_last_hip_error().
 extern thread_local hipError_t g_last_hip_error;
 inline hipError_t note_hip(hipError_t e) {
@@ -62,5 +94,11 @@ hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const
 hipError_t launch_fill_empty(float* o, float* lse, int64_t row0, int64_t rows, int32_t heads, int32_t d,
                              int32_t batch, int64_t L, hipStream_t stream);
 hipError_t launch_cast_bf16(const float* src, void* dst, int64_t n, hipStream_t stream);
+// Implemented in attn_bwd_bf16.hip.
+hipError_t launch_bwd_dq_bf16(const BwdLaunch& p, int d, hipStream_t stream);
+hipError_t launch_bwd_dkv_bf16(const BwdLaunch& p, int d, hipStream_t stream);
+hipError_t launch_bwd_delta_bf16(const void* out, const void* dout, float* delta, int64_t n_rows, int d,
+                                 hipStream_t stream);
+hipError_t launch_zero_f32(float* dst, int64_t n, hipStream_t stream);   // n a multiple of 4, dst 16-byte aligned
 
 }  // namespace tasp

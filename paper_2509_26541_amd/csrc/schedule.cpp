@@ -122,20 +122,23 @@ static int subchunk(const tasp_schedule& s, int64_t S, int32_t mask_mode, int32_
   return 2;
 }
 
-int step_segments(const tasp_schedule& s, int64_t S, int32_t mask_mode, int32_t order, int32_t step,
-                  int32_t q_block, std::vector<Segment>* out) {
-  QueryBlock qb;
-  int st = query_block(s, S, mask_mode, q_block, &qb);
+// The key ranges a rank holds at `step`, in concatenation order.  With a query block they are
+// filtered and marked by what the block can see; without one (q_block < 0) every range is listed.
+static int arriving_ranges(const tasp_schedule& s, int64_t S, int32_t mask_mode, int32_t order, int32_t step,
+                           int32_t q_block, std::vector<Segment>* out) {
+  QueryBlock qb{0, 0, 0};
+  int st = q_block >= 0 ? query_block(s, S, mask_mode, q_block, &qb) : check_sequence(s, S, mask_mode);
   if (st != TASP_OK) return st;
   if (step < 0 || step >= s.n) return TASP_EINVAL;
   if (order != TASP_ORDER_TASP && order != TASP_ORDER_RING) return TASP_EINVAL;
   const bool causal = mask_mode == TASP_MASK_ZIGZAG_CAUSAL;
+  const bool filter = causal && q_block >= 0;
   const int64_t q_first = qb.pos0, q_last = qb.pos0 + qb.rows - 1;
   out->clear();
   auto push = [&](int64_t a, int64_t b) {
     if (a >= b) return;
     int32_t diag = 0;
-    if (causal) {
+    if (filter) {
       if (a > q_last) return;                 // hidden from every row of the block
       diag = (b - 1 > q_first) ? 1 : 0;       // some row sees only part of it
     }
@@ -163,6 +166,17 @@ int step_segments(const tasp_schedule& s, int64_t S, int32_t mask_mode, int32_t 
     }
   }
   return TASP_OK;
+}
+
+int step_segments(const tasp_schedule& s, int64_t S, int32_t mask_mode, int32_t order, int32_t step,
+                  int32_t q_block, std::vector<Segment>* out) {
+  if (q_block < 0) return TASP_EINVAL;
+  return arriving_ranges(s, S, mask_mode, order, step, q_block, out);
+}
+
+int step_key_ranges(const tasp_schedule& s, int64_t S, int32_t mask_mode, int32_t order, int32_t step,
+                    std::vector<Segment>* out) {
+  return arriving_ranges(s, S, mask_mode, order, step, -1, out);
 }
 
 }  // namespace tasp

@@ -38,6 +38,10 @@ int query_block(const tasp_schedule& s, int64_t S, int32_t mask_mode, int32_t q_
 int step_segments(const tasp_schedule& s, int64_t S, int32_t mask_mode, int32_t order, int32_t step,
                   int32_t q_block, std::vector<Segment>* out);
 
+// Every key range the rank holds at `step` (visible or not), in concatenation order, diag = 0.
+int step_key_ranges(const tasp_schedule& s, int64_t S, int32_t mask_mode, int32_t order, int32_t step,
+                    std::vector<Segment>* out);
+
 int check_sequence(const tasp_schedule& s, int64_t S, int32_t mask_mode);
 
 }  // namespace tasp

@@ -88,6 +88,13 @@ def make_qkv(w):
     return q, k, v
 
 
+def make_dout(w):
+    """Upstream gradient of the local output, [L, Hq, d]: N(0,1) in the workload's dtype."""
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(w.seed + 104729)
+    return _normal((w.L, w.Hq, w.d), gen, w.torch_dtype)
+
+
 def sample_rows(w, n_random, seed_offset=0):
     """Local row indices worth checking: ends of each half, rows next to 32/64/128/256-row tile
     edges, plus seeded random rows.  Sorted, unique."""

@@ -27,6 +27,29 @@ def oracle_rows(w, q, k, v, rows, heads=None):
     return out, lse
 
 
+def oracle_grads(w, q, k, v, dout, rows=None, out=None):
+    """Dense fp64 gradients (oracle) of sum(dout * out) for workload w, all heads; `rows` restricts the
+    local query rows that take part (the gradient is linear in dout, so this equals zeroing dout
+    elsewhere); `out` [L, Hq, d] is the stored forward output delta is taken from (None: the exact
+    one).  Returns (dq [len(rows), Hq, d], dk [S, Hkv, d], dv [S, Hkv, d])."""
+    from oracle import attention_bwd as bwd
+    rows = list(range(w.L)) if rows is None else list(rows)
+    pos = np.asarray(sch.local_positions(w.n_ranks, w.rank, w.S, w.mask_mode), dtype=np.int64)[rows]
+    causal = w.mask_mode == sch.ZIGZAG_CAUSAL
+    dq = np.zeros((len(rows), w.Hq, w.d))
+    dk = np.zeros((w.S, w.Hkv, w.d))
+    dv = np.zeros((w.S, w.Hkv, w.d))
+    for h in range(w.Hq):
+        g = h * w.Hkv // w.Hq
+        a, b, c = bwd.dense_grads(q[rows, h].double().numpy(), pos, k[:, g].double().numpy(), v[:, g].double().numpy(),
+                                  dout[rows, h].double().numpy(), causal,
+                                  out_rows=None if out is None else out[rows, h].double().numpy())
+        dq[:, h] = a
+        dk[:, g] += b
+        dv[:, g] += c
+    return dq, dk, dv
+
+
 def max_abs(a, b):
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)

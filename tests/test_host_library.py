@@ -7,6 +7,7 @@ import re
 
 import pytest
 
+from oracle import attention as att
 from oracle import schedule as sch
 from paper_2509_26541_amd import binding as tb
 
@@ -250,3 +251,35 @@ def test_flops_and_workspace():
         a.batch = -1
         assert tb.lib.tasp_chunk_attn_workspace_bytes(s.handle, C.byref(a)) == 0
         assert tb.lib.tasp_chunk_attn(s.handle, C.byref(a), None) == tb.EINVAL
+
+
+def test_backward_argument_checks_and_sizes():
+    """tasp_chunk_attn_bwd: argument checks that return before any HIP call, workspace size (an fp32 dq
+    and the delta vector) and the flops convention (2.5 times the forward's)."""
+    s = tb.tasp_schedule(8, 3)
+    b = tb.AttnBwdArgs()
+    assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EINVAL
+    assert tb.lib.tasp_chunk_attn_bwd(None, C.byref(b), None) == tb.EINVAL
+    assert tb.lib.tasp_chunk_attn_bwd_profile(s.handle, C.byref(b), None, None) == tb.EINVAL
+    b.q = b.k = b.v = 4096
+    b.S, b.Hq, b.Hkv, b.d, b.dtype, b.mask_mode = 4096, 8, 2, 128, tb.DTYPE_BF16, tb.MASK_ZIGZAG_CAUSAL
+    assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EINVAL           # out, lse, dout, dq, dk, dv missing
+    b.out = b.lse = b.dout = b.dq = b.dk = b.dv = 4096
+    assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EWORKSPACE
+    b.dtype = tb.DTYPE_FP32
+    assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EUNSUPPORTED_SHAPE
+    b.dtype, b.dk = tb.DTYPE_BF16, 4104
+    assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EALIGN
+    b.dk, b.batch = 4096, -1
+    assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EINVAL
+    b.batch = 0
+    L = 4096 // 8
+    pad = lambda x: (x + 255) // 256 * 256
+    assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == pad(L * 8 * 128 * 4) + pad(L * 8 * 4)
+    fwd = att.attention_flops(8, 3, 4096, sch.ZIGZAG_CAUSAL, 8, 128)
+    assert tb.lib.tasp_chunk_attn_bwd_flops(s.handle, C.byref(b)) == 2.5 * fwd
+    from oracle import attention_bwd as bwd
+    assert bwd.attention_bwd_flops(8, 3, 4096, sch.ZIGZAG_CAUSAL, 8, 128) == 2.5 * fwd
+    b.batch = 4
+    assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == pad(4 * L * 8 * 128 * 4) + pad(4 * L * 8 * 4)
+    assert tb.lib.tasp_chunk_attn_bwd_flops(s.handle, C.byref(b)) == 4 * 2.5 * fwd

@@ -137,6 +137,28 @@ def test_invariants(causal):
     np.testing.assert_allclose(dv2, dv3, rtol=0, atol=1e-14)
 
 
+def test_stored_output_only_enters_through_delta():
+    """Reading B5: with the exact output passed in, nothing changes; a perturbed stored output changes
+    ds by -p * (dout . perturbation) and leaves dv alone."""
+    S, d, R = 14, 4, 3
+    q, k, v, do = rand((R, d), 70), rand((S, d), 71), rand((S, d), 72), rand((R, d), 73)
+    pos = np.arange(R) + 9
+    out, lse = att.dense_rows(q, pos, k, v, True)
+    base = bwd.dense_grads(q, pos, k, v, do, True)
+    same = bwd.dense_grads(q, pos, k, v, do, True, out_rows=out)
+    for a, b in zip(base, same):
+        np.testing.assert_allclose(a, b, rtol=0, atol=1e-15)
+    bump = rand((R, d), 74) * 1e-2
+    dq2, dk2, dv2 = bwd.dense_grads(q, pos, k, v, do, True, out_rows=out + bump)
+    np.testing.assert_allclose(dv2, base[2], rtol=0, atol=1e-15)
+    c = 1 / math.sqrt(d)
+    s = np.where(np.arange(S)[None] <= pos[:, None], q @ k.T * c, -np.inf)
+    p = np.exp(s - lse[:, None])
+    shift = -(do * bump).sum(1, keepdims=True) * p                # change of ds
+    np.testing.assert_allclose(dq2 - base[0], shift @ k * c, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(dk2 - base[1], shift.T @ q * c, rtol=0, atol=1e-14)
+
+
 def test_shift_of_the_scores_changes_nothing():
     """Softmax is invariant under a per-row shift: adding a constant vector u to every key shifts the
     scores of row i by scale * q_i.u; out, dv and dq's ds stay, so dv is unchanged."""
