@@ -82,6 +82,7 @@ def main():
     ap.add_argument("--grid", default="",
                     help="HEADS,SEQ: a shape of the paper's own grid (Sec. 5.1.2: MHA, d = 64, bf16) on 8 ranks "
                          "instead of --config; combine with --batch")
+    ap.add_argument("--no-backward", action="store_true", help="skip the leg that times the backward pass (bf16 workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-mode", action="store_true",
                     help="skip the leg that runs the other merge mode (profiler runs: one kind of launch only)")
@@ -237,6 +238,37 @@ def main():
                       "pairwise_fold_ms": fold_ms, "pairwise_fold_GB/s": 3 * (n_parts - 1) * unit / (fold_ms * 1e-3) / 1e9}
         del po, pl, oo, ol
 
+    # the backward pass of the same call (same schedule and order), timed the same way
+    backward = None
+    if is_bf16 and not args.no_backward:
+        out_f, lse_f = plan.run()
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed + 104729)
+        dout = torch.randn(qd.shape, generator=gen, device=dev, dtype=torch.float32).to(qd.dtype)
+        bplan = tb.ChunkAttnBwdPlan(sched, qd, kd, vd, out_f, lse_f, dout, w.mask_mode, order=order)
+        for _ in range(max(1, args.warmup)):
+            bplan.run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            bplan.run()
+        torch.cuda.synchronize()
+        b_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        bp = bplan.profile()
+        b_flops = bplan.flops()                  # 2.5 x forward: five products
+        backward = {
+            "value": b_flops / (b_ms * 1e-3) / 1e12, "unit": "TFLOP/s", "ms_per_step": b_ms, "flops_per_call": b_flops,
+            "frac_of_bf16_mfma_peak": b_flops / (b_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            # executed matrix work: the dq kernel forms three products per (query, key) pair (1.5 x the
+            # forward's flops), the dk/dv kernel four (2 x): both recompute the scores
+            "dq_kernel": {"avg_launch_ms": bp.dq_ms / max(bp.dq_launches, 1), "launches_per_call": bp.dq_launches,
+                          "executed_TFLOP/s": 1.5 * flops / (bp.dq_ms * 1e-3) / 1e12},
+            "dkv_kernel": {"avg_launch_ms": bp.dkv_ms / max(bp.dkv_launches, 1), "launches_per_call": bp.dkv_launches,
+                           "executed_TFLOP/s": 2.0 * flops / (bp.dkv_ms * 1e-3) / 1e12},
+            "other_ms": bp.other_ms,
+        }
+        del bplan, dout
+
     value = flops / (ms_per_step * 1e-3) / 1e12
     line = {
         "metric": "per-rank chunked-attention TFLOP/s on 1 MI355X", "value": value, "unit": "TFLOP/s",
@@ -254,6 +286,7 @@ def main():
         "ms_breakdown": {"attn": attn_ms / n_prof, "merge": merge_ms / n_prof, "cast": other_ms / n_prof},
         "other_merge_mode": other,
         "merge_many": merge_many,
+        "backward": backward,
     }
     if not args.no_cpu_baseline:
         del plan, qd, kd, vd

@@ -357,6 +357,11 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
       st = tasp::step_key_ranges(*s, b->S, b->mask_mode, b->order, step, &ranges);
       if (st != TASP_OK) return st;
       if (ranges.size() > static_cast<size_t>(tasp::kMaxSeg)) return TASP_EUNSUPPORTED_SHAPE;
+      // The dk/dv kernel treats every key on its own, so the order of the ranges is free: by
+      // position, which under the causal mask is by falling work (early keys are seen by more
+      // queries), so that the workgroups with the most work start first.
+      std::sort(ranges.begin(), ranges.end(),
+                [](const tasp::Segment& x, const tasp::Segment& y) { return x.start < y.start; });
       bp.n_rng = static_cast<int32_t>(ranges.size());
       int64_t vpos = 0;
       for (size_t i = 0; i < ranges.size(); ++i) {

@@ -46,14 +46,14 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
 
 constexpr int BT = 64;             // streamed rows per tile
-constexpr int BS = 128;            // stationary rows per workgroup (32 per wavefront)
-constexpr int NTHREADS = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <int D>
+template <int D, int NW>
 struct BCfg {
+  static constexpr int NTHREADS = 64 * NW;
+  static constexpr int BS = 32 * NW;                    // stationary rows per workgroup (32 per wavefront)
   static constexpr int UNITS = D / 8;                   // 16-byte units per row
-  static constexpr int RPP = NTHREADS / UNITS;          // rows filled per pass (16 or 32)
+  static constexpr int RPP = NTHREADS / UNITS;          // rows filled per pass
   static constexpr int PASSES = BT / RPP;
   static constexpr int ROWS_PER_LINE = 16 / UNITS;      // rows per 256-byte bank line (1 or 2)
   static constexpr int TILE_BYTES = BT * D * 2;
@@ -107,7 +107,7 @@ __device__ inline int xcd_contiguous(int block, int nblocks) {
 // Per-lane byte offsets inside a tile for the two LDS read patterns.
 template <int D>
 struct ReadAddr {
-  using C = BCfg<D>;
+  using C = BCfg<D, 4>;      // the swizzle does not depend on the number of wavefronts
   unsigned row[D / 16];        // row lq (+32 per block), logical unit 2 ks + h
   unsigned tr[D / 32][2];      // transposed: 16-row group at +16 rows per group, rows +0 and +8
   __device__ void init(int lane) {
@@ -131,9 +131,9 @@ struct ReadAddr {
 // dq kernel
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(NTHREADS) void bwd_dq_kernel(const BwdLaunch p) {
-  using C = BCfg<D>;
-  constexpr int KS = D / 16, DB = D / 32;
+__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const BwdLaunch p) {
+  using C = BCfg<D, 4>;
+  constexpr int KS = D / 16, DB = D / 32, BS = C::BS, NTHREADS = C::NTHREADS;
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE_BYTES];   // stage: K tile, V tile
   __shared__ __attribute__((aligned(16))) int s_tok[2][BT];   // global position of every key row (INT_MAX: none)
   __shared__ int e_vbeg[kMaxSeg + 1];   // effective segments: start in the virtual concatenation
@@ -301,11 +301,15 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dq_kernel(const BwdLaunch p) {
 // ------------------------------------------------------------------------------------------------
 // dk / dv kernel
 // ------------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(NTHREADS) void bwd_dkv_kernel(const BwdLaunch p) {
-  using C = BCfg<D>;
-  constexpr int KS = D / 16, DB = D / 32;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE_BYTES];   // stage: Q tile, dout tile
+// NW wavefronts of 32 keys each.  The K rows of a wavefront's keys stay in registers; with VLDS the
+// V rows stay in LDS instead (read as B operand when needed), which is what lets a wavefront with
+// two 32 x D accumulators fit the 256 registers of two wavefronts per SIMD at D = 128.
+template <int D, int NW, bool VLDS>
+__global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const BwdLaunch p) {
+  using C = BCfg<D, NW>;
+  constexpr int KS = D / 16, DB = D / 32, BS = C::BS, NTHREADS = C::NTHREADS;
+  constexpr int VST_BYTES = VLDS ? BS * D * 2 : 0;        // stationary V rows, same row layout as a tile
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE_BYTES + VST_BYTES];   // stage: Q tile, dout tile
   __shared__ __attribute__((aligned(16))) float s_l2[2][BT];    // lse log2(e) of the tile's queries (+inf: row contributes nothing)
   __shared__ __attribute__((aligned(16))) float s_dl[2][BT];    // delta of the tile's queries
   __shared__ int s_tmin;
@@ -333,20 +337,23 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dkv_kernel(const BwdLaunch p) {
   }
 
   // ---- stationary side: this lane's key (column lq of the wave's strip)
-  const int my_v = v0 + wave * 32 + lq;
-  int key_tok = INT_MAX;
-  for (int j = 0; j < p.n_rng; ++j)
-    if (my_v >= p.rng_vbeg[j] && my_v < p.rng_vbeg[j + 1]) key_tok = p.rng_start[j] + (my_v - p.rng_vbeg[j]);
+  auto token_of = [&](int vi) __attribute__((always_inline)) {     // global position of virtual key vi (INT_MAX: past the end)
+    int tok = INT_MAX;
+    for (int j = 0; j < p.n_rng; ++j)
+      if (vi >= p.rng_vbeg[j] && vi < p.rng_vbeg[j + 1]) tok = p.rng_start[j] + (vi - p.rng_vbeg[j]);
+    return tok;
+  };
+  const int key_tok = token_of(v0 + wave * 32 + lq);
   const bool key_valid = key_tok != INT_MAX;
   const int64_t koff = bi * p.kv_bstride + (static_cast<int64_t>(key_valid ? key_tok : p.rng_start[0]) * p.Hkv + g) * D;
-  bf16x8 kf[KS], vf[KS];
+  bf16x8 kf[KS], vf[VLDS ? 1 : KS];
   {
     const __bf16* ks_ = static_cast<const __bf16*>(p.k) + koff + 8 * h;
     const __bf16* vs_ = static_cast<const __bf16*>(p.v) + koff + 8 * h;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       kf[ks] = *reinterpret_cast<const bf16x8*>(ks_ + 16 * ks);
-      vf[ks] = *reinterpret_cast<const bf16x8*>(vs_ + 16 * ks);
+      if constexpr (!VLDS) vf[ks] = *reinterpret_cast<const bf16x8*>(vs_ + 16 * ks);
     }
   }
   const float c = p.scale * kLog2e;
@@ -411,6 +418,20 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dkv_kernel(const BwdLaunch p) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) { dk[db][i] = 0.f; dv[db][i] = 0.f; }
 
+  // the V rows of the workgroup's keys, laid out like a tile (rows past the end repeat a valid row)
+  const unsigned char* vst = smem + 2 * C::STAGE_BYTES + wave * 32 * D * 2;   // this wave's 32 rows
+  if constexpr (VLDS) {
+    const unsigned char* Vg = static_cast<const unsigned char*>(p.v) + (bi * p.kv_bstride + static_cast<int64_t>(g) * D) * 2;
+    const unsigned kv_row_bytes = static_cast<unsigned>(p.Hkv) * D * 2;
+    unsigned char* dst = smem + 2 * C::STAGE_BYTES + wave_u * 1024;
+#pragma unroll
+    for (int i = 0; i < BS / C::RPP; ++i) {
+      const int tok = token_of(v0 + fr + C::RPP * i);
+      const unsigned off = static_cast<unsigned>(tok == INT_MAX ? p.rng_start[0] : tok) * kv_row_bytes + col;
+      dma16(Vg, off, dst + i * NTHREADS * 16);
+    }
+  }
+
   It cur = settle(It{0, 0, first_tile(0)});
   if (cur.hh < G) fetch(cur, 0);
   int stage = 0;
@@ -424,43 +445,77 @@ __global__ __launch_bounds__(NTHREADS) void bwd_dkv_kernel(const BwdLaunch p) {
     const int pos0 = p.causal ? p.blk[cur.blk].pos0 + cur.qt * BT : 0;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-      f32x16 S, dP;
+      // Five phases in a fixed order (the compiler may not mix them: that would keep S, dP, p and
+      // ds alive at once, more than the registers hold):  S -> p (in place) -> dv -> dP -> ds (in
+      // place) -> dk.  The other wavefront of the SIMD fills the matrix pipe meanwhile.
+      f32x16 S;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) { S[i] = 0.f; dP[i] = 0.f; }
+      for (int i = 0; i < 16; ++i) S[i] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) S = mfma(lds_row8(qt_ + ra.row[ks] + qb * 32 * D * 2), kf[ks], S);
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) dP = mfma(lds_row8(ot_ + ra.row[ks] + qb * 32 * D * 2), vf[ks], dP);
-      // p and ds for the 32 queries of this block (register 4 i4 + e: query 8 i4 + 4 h + e)
-      float pr[16], ds[16];
+      __builtin_amdgcn_sched_barrier(0);
+      // p for the 32 queries of this block (register 4 i4 + e: query 8 i4 + 4 h + e)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         const int r0 = 32 * qb + 8 * i4 + 4 * h;
         const f32x4 l2 = *reinterpret_cast<const f32x4*>(&s_l2[stage][r0]);
-        const f32x4 dl = *reinterpret_cast<const f32x4*>(&s_dl[stage][r0]);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * i4 + e;
           const int q_pos = p.causal ? pos0 + r0 + e : INT_MAX - 1;
           const float x = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c, -l2[e]));
-          pr[i] = key_tok > q_pos ? 0.f : x;
-          ds[i] = pr[i] * (dP[i] - dl[e]);
+          S[i] = key_tok > q_pos ? 0.f : x;
         }
       }
+      bf16x8 pb[2];
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        const u32x4 pf = {pack2(pr[8 * j + 0], pr[8 * j + 1]), pack2(pr[8 * j + 2], pr[8 * j + 3]),
-                          pack2(pr[8 * j + 4], pr[8 * j + 5]), pack2(pr[8 * j + 6], pr[8 * j + 7])};
-        const u32x4 ef = {pack2(ds[8 * j + 0], ds[8 * j + 1]), pack2(ds[8 * j + 2], ds[8 * j + 3]),
-                          pack2(ds[8 * j + 4], ds[8 * j + 5]), pack2(ds[8 * j + 6], ds[8 * j + 7])};
-        const bf16x8 pb = __builtin_bit_cast(bf16x8, pf), eb = __builtin_bit_cast(bf16x8, ef);
+        const u32x4 pf = {pack2(S[8 * j + 0], S[8 * j + 1]), pack2(S[8 * j + 2], S[8 * j + 3]),
+                          pack2(S[8 * j + 4], S[8 * j + 5]), pack2(S[8 * j + 6], S[8 * j + 7])};
+        pb[j] = __builtin_bit_cast(bf16x8, pf);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
         const int grp = (2 * qb + j) * 16 * D * 2;
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          dv[db] = mfma(lds_tr8(ot_ + ra.tr[db][0] + grp, ot_ + ra.tr[db][1] + grp), pb, dv[db]);
-          dk[db] = mfma(lds_tr8(qt_ + ra.tr[db][0] + grp, qt_ + ra.tr[db][1] + grp), eb, dk[db]);
-        }
+        for (int db = 0; db < DB; ++db)
+          dv[db] = mfma(lds_tr8(ot_ + ra.tr[db][0] + grp, ot_ + ra.tr[db][1] + grp), pb[j], dv[db]);
       }
+      f32x16 dP;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dP[i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 vb;
+        if constexpr (VLDS) vb = lds_row8(vst + ra.row[ks]);
+        else vb = vf[ks];
+        dP = mfma(lds_row8(ot_ + ra.row[ks] + qb * 32 * D * 2), vb, dP);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int r0 = 32 * qb + 8 * i4 + 4 * h;
+        const f32x4 dl = *reinterpret_cast<const f32x4*>(&s_dl[stage][r0]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dP[4 * i4 + e] = S[4 * i4 + e] * (dP[4 * i4 + e] - dl[e]);
+      }
+      bf16x8 eb[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const u32x4 ef = {pack2(dP[8 * j + 0], dP[8 * j + 1]), pack2(dP[8 * j + 2], dP[8 * j + 3]),
+                          pack2(dP[8 * j + 4], dP[8 * j + 5]), pack2(dP[8 * j + 6], dP[8 * j + 7])};
+        eb[j] = __builtin_bit_cast(bf16x8, ef);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int grp = (2 * qb + j) * 16 * D * 2;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          dk[db] = mfma(lds_tr8(qt_ + ra.tr[db][0] + grp, qt_ + ra.tr[db][1] + grp), eb[j], dk[db]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
     cur = nxt;
     stage ^= 1;
@@ -518,22 +573,29 @@ __global__ __launch_bounds__(256) void bwd_zero_kernel(f32x4* __restrict__ dst, 
 
 hipError_t launch_bwd_dq_bf16(const BwdLaunch& p, int d, hipStream_t stream) {
   int64_t tiles = 0;
+  constexpr int BS = 128;
   for (int t = 0; t < p.n_tasks; ++t) tiles += (p.task[t].n_q + BS - 1) / BS;
   const int64_t blocks = tiles * p.Hq * p.batch;
   if (blocks == 0) return hipSuccess;
   if (blocks > INT_MAX) return hipErrorInvalidValue;
-  if (d == 128) return TASP_LAUNCH((bwd_dq_kernel<128>), dim3(static_cast<unsigned>(blocks)), dim3(NTHREADS), stream, p);
-  if (d == 64) return TASP_LAUNCH((bwd_dq_kernel<64>), dim3(static_cast<unsigned>(blocks)), dim3(NTHREADS), stream, p);
+  if (d == 128) return TASP_LAUNCH((bwd_dq_kernel<128>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, p);
+  if (d == 64) return TASP_LAUNCH((bwd_dq_kernel<64>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, p);
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_bwd_dkv_bf16(const BwdLaunch& p, int d, hipStream_t stream) {
+template <int D, int NW, bool VLDS>
+hipError_t launch_dkv_variant(const BwdLaunch& p, hipStream_t stream) {
+  constexpr int BS = 32 * NW;
   const int64_t total = p.rng_vbeg[p.n_rng];
   const int64_t blocks = (total + BS - 1) / BS * p.Hkv * p.batch;
   if (blocks == 0) return hipSuccess;
   if (blocks > INT_MAX) return hipErrorInvalidValue;
-  if (d == 128) return TASP_LAUNCH((bwd_dkv_kernel<128>), dim3(static_cast<unsigned>(blocks)), dim3(NTHREADS), stream, p);
-  if (d == 64) return TASP_LAUNCH((bwd_dkv_kernel<64>), dim3(static_cast<unsigned>(blocks)), dim3(NTHREADS), stream, p);
+  return TASP_LAUNCH((bwd_dkv_kernel<D, NW, VLDS>), dim3(static_cast<unsigned>(blocks)), dim3(64 * NW), stream, p);
+}
+
+hipError_t launch_bwd_dkv_bf16(const BwdLaunch& p, int d, hipStream_t stream) {
+  if (d == 128) return launch_dkv_variant<128, 8, true>(p, stream);
+  if (d == 64) return launch_dkv_variant<64, 4, false>(p, stream);
   return hipErrorInvalidValue;
 }
 
