@@ -245,19 +245,27 @@ def main():
         gen = torch.Generator(device=dev)
         gen.manual_seed(w.seed + 104729)
         dout = torch.randn(qd.shape, generator=gen, device=dev, dtype=torch.float32).to(qd.dtype)
-        bplan = tb.ChunkAttnBwdPlan(sched, qd, kd, vd, out_f, lse_f, dout, w.mask_mode, order=order)
-        for _ in range(max(1, args.warmup)):
-            bplan.run()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            bplan.run()
-        torch.cuda.synchronize()
-        b_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        def time_bwd(aux):
+            pl = tb.ChunkAttnBwdPlan(sched, qd, kd, vd, out_f, lse_f, dout, w.mask_mode, order=order, aux_stream=aux)
+            for _ in range(max(1, args.warmup)):
+                pl.run()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                pl.run()
+            torch.cuda.synchronize()
+            return pl, (time.perf_counter() - t0) * 1e3 / args.steps
+
+        # one stream, and the dk/dv kernels on a second stream beside the dq kernels
+        bplan, one_ms = time_bwd(None)
+        aux_plan, two_ms = time_bwd(torch.cuda.Stream())
+        del aux_plan
+        b_ms = min(one_ms, two_ms)
         bp = bplan.profile()
         b_flops = bplan.flops()                  # 2.5 x forward: five products
         backward = {
             "value": b_flops / (b_ms * 1e-3) / 1e12, "unit": "TFLOP/s", "ms_per_step": b_ms, "flops_per_call": b_flops,
+            "ms_one_stream": one_ms, "ms_two_streams": two_ms,
             "frac_of_bf16_mfma_peak": b_flops / (b_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             # executed matrix work: the dq kernel forms three products per (query, key) pair (1.5 x the
             # forward's flops), the dk/dv kernel four (2 x): both recompute the scores

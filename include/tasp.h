@@ -255,6 +255,12 @@ typedef struct tasp_attn_bwd_args {
   int32_t      order;
   float        softmax_scale;   /* 0: 1/sqrt(d) */
   int32_t      batch;           /* 0 counts as 1 */
+  void*        aux_stream;      /* optional second HIP stream of the caller (default priority, same device),
+                                   or NULL.  The dq and the dk/dv kernels of a step are independent; given a
+                                   second stream the dk/dv kernels run there, forked from and joined back
+                                   into hip_stream with events, so that each fills the idle compute units at
+                                   the other's tail.  Results are identical.  The call must then not be
+                                   recorded into a HIP graph. */
 } tasp_attn_bwd_args;
 
 size_t tasp_chunk_attn_bwd_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_bwd_args* a);

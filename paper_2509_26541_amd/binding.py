@@ -60,6 +60,7 @@ class AttnBwdArgs(C.Structure):
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("S", C.c_int64),
         ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32), ("dtype", C.c_int32),
         ("mask_mode", C.c_int32), ("order", C.c_int32), ("softmax_scale", C.c_float), ("batch", C.c_int32),
+        ("aux_stream", C.c_void_p),
     ]
 
 
@@ -257,7 +258,9 @@ def tasp_chunk_attn(q, k, v, schedule, mask_mode, order=ORDER_TASP, fuse_merge=F
 class ChunkAttnBwdPlan:
     """Buffers of one tasp_chunk_attn_bwd shape (dq, dk, dv, workspace), so that repeated calls allocate nothing."""
 
-    def __init__(self, schedule, q, k, v, out, lse, dout, mask_mode, order=ORDER_TASP, softmax_scale=0.0):
+    def __init__(self, schedule, q, k, v, out, lse, dout, mask_mode, order=ORDER_TASP, softmax_scale=0.0,
+                 aux_stream=None):
+        """aux_stream: a torch.cuda.Stream for the dk/dv kernels (None: everything on one stream)."""
         torch = _torch()
         fa = _args(q, k, v, mask_mode, order, True, softmax_scale)
         if q.shape[-3] * schedule.n_ranks != k.shape[-3]:
@@ -277,8 +280,9 @@ class ChunkAttnBwdPlan:
         nbytes = lib.tasp_chunk_attn_bwd_workspace_bytes(schedule.handle, C.byref(a))
         self.workspace = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=q.device)
         a.workspace, a.workspace_bytes = self.workspace.data_ptr(), nbytes
+        a.aux_stream = aux_stream.cuda_stream if aux_stream is not None else None
         self.args = a
-        self._keep = (q, k, v, out, lse, dout)
+        self._keep = (q, k, v, out, lse, dout, aux_stream)
 
     def run(self, stream=None):
         torch = _torch()
@@ -298,10 +302,11 @@ class ChunkAttnBwdPlan:
         return lib.tasp_chunk_attn_bwd_flops(self.schedule.handle, C.byref(self.args))
 
 
-def tasp_chunk_attn_bwd(q, k, v, out, lse, dout, schedule, mask_mode, order=ORDER_TASP, softmax_scale=0.0):
+def tasp_chunk_attn_bwd(q, k, v, out, lse, dout, schedule, mask_mode, order=ORDER_TASP, softmax_scale=0.0,
+                        aux_stream=None):
     """One rank's backward pass in the forward's arrival order.  out, lse: what tasp_chunk_attn returned
     for the same inputs.  Returns (dq like q, dk like k, dv like v); dk, dv are this rank's contribution."""
-    return ChunkAttnBwdPlan(schedule, q, k, v, out, lse, dout, mask_mode, order, softmax_scale).run()
+    return ChunkAttnBwdPlan(schedule, q, k, v, out, lse, dout, mask_mode, order, softmax_scale, aux_stream).run()
 
 
 def tasp_step_attn(q, k, v, schedule, mask_mode, step, order=ORDER_TASP, softmax_scale=0.0):

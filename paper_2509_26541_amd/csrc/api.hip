@@ -321,6 +321,14 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
   if (b->workspace == nullptr || b->workspace_bytes < need) return TASP_EWORKSPACE;
   if (reinterpret_cast<uintptr_t>(b->workspace) & (kAlign - 1)) return TASP_EALIGN;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  // With a second stream from the caller the dk/dv kernels run beside the dq kernels: fork after
+  // delta is on its way, join before returning.  The profiled run keeps one stream (its events
+  // bracket launches on `stream`).
+  hipStream_t kv_stream = (b->aux_stream != nullptr && prof == nullptr) ? static_cast<hipStream_t>(b->aux_stream) : stream;
+  struct Ev {
+    hipEvent_t e = nullptr;
+    ~Ev() { if (e) (void)hipEventDestroy(e); }
+  } fork, join;
   float* dq_acc = static_cast<float*>(b->workspace);
   float* delta = reinterpret_cast<float*>(static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes));
   const int64_t n_q_elems = static_cast<int64_t>(sh.B) * sh.L * b->Hq * b->d;
@@ -332,6 +340,13 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
           hipSuccess)
         return TASP_EHIP;
       if (tasp::launch_zero_f32(dq_acc, n_q_elems, stream) != hipSuccess) return TASP_EHIP;
+    }
+    if (kv_stream != stream) {
+      if (tasp::note_hip(hipEventCreateWithFlags(&fork.e, hipEventDisableTiming)) != hipSuccess ||
+          tasp::note_hip(hipEventCreateWithFlags(&join.e, hipEventDisableTiming)) != hipSuccess ||
+          tasp::note_hip(hipEventRecord(fork.e, stream)) != hipSuccess ||
+          tasp::note_hip(hipStreamWaitEvent(kv_stream, fork.e, 0)) != hipSuccess)
+        return TASP_EHIP;
     }
     std::vector<tasp::QueryBlock> empty;
     std::vector<tasp::Segment> ranges;
@@ -376,8 +391,13 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
       }
       {
         Scope sc(prof, BwdSpans::kDkv);
-        if (tasp::launch_bwd_dkv_bf16(bp, b->d, stream) != hipSuccess) return TASP_EHIP;
+        if (tasp::launch_bwd_dkv_bf16(bp, b->d, kv_stream) != hipSuccess) return TASP_EHIP;
       }
+    }
+    if (kv_stream != stream) {
+      if (tasp::note_hip(hipEventRecord(join.e, kv_stream)) != hipSuccess ||
+          tasp::note_hip(hipStreamWaitEvent(stream, join.e, 0)) != hipSuccess)
+        return TASP_EHIP;
     }
     {
       Scope sc(prof, BwdSpans::kOther);

@@ -129,6 +129,23 @@ def test_batched_equals_separate_calls(tb):
         assert torch.equal(one[0], dq[b]) and torch.equal(one[1], dk[b]) and torch.equal(one[2], dv[b])
 
 
+def test_second_stream_gives_the_same_bits(tb):
+    """dk/dv kernels on a second stream of the caller: same results, and the caller's stream alone
+    orders everything that follows (the results are read right after synchronising it)."""
+    w = small_workload(SMALL[0])
+    q, k, v = (x.cuda() for x in wl.make_qkv(w))
+    do = wl.make_dout(w).cuda()
+    s = tb.tasp_schedule(w.n_ranks, w.rank)
+    out, lse = tb.tasp_chunk_attn(q, k, v, s, w.mask_mode, fuse_merge=True)
+    one = tb.tasp_chunk_attn_bwd(q, k, v, out, lse, do, s, w.mask_mode)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    for _ in range(3):
+        two = tb.tasp_chunk_attn_bwd(q, k, v, out, lse, do, s, w.mask_mode, aux_stream=side)
+        torch.cuda.current_stream().synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(one, two))
+
+
 def test_rows_without_upstream_gradient_get_none(tb):
     """dout = 0 on a row: its dq is exactly zero and it adds nothing to dk, dv (linearity in dout)."""
     w = small_workload(SMALL[0])

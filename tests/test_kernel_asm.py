@@ -52,3 +52,34 @@ def test_no_spills(attn_asm):
     assert len(rep) == 2
     for name, spills, scratch in rep:
         assert spills == 0 and scratch == 0, (name, spills, scratch)
+
+
+# ---------------------------------------------------------------- backward kernels (compiler-scheduled)
+@pytest.fixture(scope="module")
+def bwd_asm(tmp_path_factory):
+    out = tmp_path_factory.mktemp("asm") / "attn_bwd_bf16.s"
+    return asm_checks.compile_to_asm("attn_bwd_bf16.hip", str(out))
+
+
+def test_backward_kernels_shape_and_register_budget(bwd_asm):
+    """Four instantiations; each reads its LDS tiles with LDS instructions (no flat loads: the address
+    space was inferred), fills them with direct global->LDS loads, fits the 256 registers that let two
+    wavefronts share a SIMD, and keeps register spills out of the loop that holds the matrix
+    instructions."""
+    import re
+    ks = {k: v for k, v in asm_checks.kernels(bwd_asm).items() if "bwd_dq_kernel" in k or "bwd_dkv_kernel" in k}
+    assert len(ks) == 4, list(ks)
+    budget = dict((m.group(1), int(m.group(2))) for m in re.finditer(
+        r"\.name:\s+(\S+)\n(?:.*\n)*?\s+\.vgpr_count:\s+(\d+)", bwd_asm))
+    for name, ins in ks.items():
+        ops = [s.split()[0] for _, s in ins]
+        mf = [i for i, o in enumerate(ops) if o.startswith("v_mfma_f32_32x32x16_bf16")]
+        assert len(mf) >= 24, (name, len(mf))
+        assert "ds_read_b64_tr_b16" in ops and "ds_read_b128" in ops and "global_load_lds_dwordx4" in ops
+        assert not any(o.startswith("flat_load") or o.startswith("flat_store") for o in ops), name
+        assert budget[name] <= 256, (name, budget[name])
+        spills = [i for i, o in enumerate(ops) if o.startswith("scratch_")]
+        assert all(i < mf[0] or i > mf[-1] for i in spills), (name, "spill inside the matrix loop")
+    for name, n_spill, _ in asm_checks.spill_report(bwd_asm):
+        if name in ks:
+            assert n_spill <= 2, (name, n_spill)
