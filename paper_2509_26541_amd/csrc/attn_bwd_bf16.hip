@@ -136,6 +136,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const BwdLaunch p) {
   constexpr int KS = D / 16, DB = D / 32, BS = C::BS, NTHREADS = C::NTHREADS;
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE_BYTES];   // stage: K tile, V tile
   __shared__ __attribute__((aligned(16))) int s_tok[2][BT];   // global position of every key row (INT_MAX: none)
+  __shared__ __attribute__((aligned(16))) int s_msk[2][4];    // per loading wavefront: the tile holds a key some query row of the workgroup must not see
   __shared__ int e_vbeg[kMaxSeg + 1];   // effective segments: start in the virtual concatenation
   __shared__ int e_goff[kMaxSeg];       //   global position minus virtual position
   __shared__ int e_n;
@@ -160,6 +161,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const BwdLaunch p) {
   const int q_tile_row0 = tile_q * BS;
   const int q_rows_here = min(BS, T.n_q - q_tile_row0);
   const int q_last = T.q_pos0 + q_tile_row0 + q_rows_here - 1;
+  const int q_first = p.causal ? T.q_pos0 + q_tile_row0 : INT_MAX - 1;   // a key at or before it is seen by every row
 
   // ---- effective segments of this query tile: drop what the causal mask hides from every row
   if (tid == 0) {
@@ -214,6 +216,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const BwdLaunch p) {
   for (int i = 0; i < C::PASSES; ++i) segi[i] = 0;
   auto fetch = [&](int t, int stage) __attribute__((always_inline)) {
     unsigned char* dst = smem + stage * C::STAGE_BYTES + wave_u * 1024;
+    bool hidden = false;
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
       const int r = fr + C::RPP * i, v = t * BT + r;
@@ -221,11 +224,14 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const BwdLaunch p) {
       while (j < n_eff && v >= e_vbeg[j + 1]) ++j;       // rows only move forward
       segi[i] = j;
       const int tok = j < n_eff ? v + e_goff[j] : INT_MAX;
+      hidden |= tok > q_first;
       s_tok[stage][r] = tok;                              // the UNITS lanes of a row write the same value
       const unsigned off = (tok == INT_MAX ? 0u : static_cast<unsigned>(tok)) * row_bytes + col;
       dma16(Kg, off, dst + i * NTHREADS * 16);
       dma16(Vg, off, dst + C::TILE_BYTES + i * NTHREADS * 16);
     }
+    const int any_hidden = __builtin_amdgcn_ballot_w64(hidden) != 0 ? 1 : 0;
+    if (lane == 0) s_msk[stage][wave] = any_hidden;
   };
 
   ReadAddr<D> ra;
@@ -245,6 +251,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const BwdLaunch p) {
     if (t + 1 < n_tiles) fetch(t + 1, stage ^ 1);
     const unsigned char* kt = smem + stage * C::STAGE_BYTES;
     const unsigned char* vt = kt + C::TILE_BYTES;
+    // most tiles are seen completely by every row: the element-wise mask is skipped for them
+    const i32x4 mk = *reinterpret_cast<const i32x4*>(&s_msk[stage][0]);
+    const bool need_mask = __builtin_amdgcn_readfirstlane(mk[0] | mk[1] | mk[2] | mk[3]) != 0;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       f32x16 S, dP;
@@ -257,16 +266,18 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const BwdLaunch p) {
       // ds^T for the 32 keys of this block (register 4 i4 + e: key 8 i4 + 4 h + e)
       float ds[16];
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const i32x4 tk = *reinterpret_cast<const i32x4*>(&s_tok[stage][32 * kb + 8 * i4 + 4 * h]);
+      for (int i = 0; i < 16; ++i) S[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c, -lse2));
+      if (need_mask) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * i4 + e;
-          const float x = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c, -lse2));
-          const float pr = tk[e] > q_pos ? 0.f : x;
-          ds[i] = pr * (dP[i] - dl);
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const i32x4 tk = *reinterpret_cast<const i32x4*>(&s_tok[stage][32 * kb + 8 * i4 + 4 * h]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (tk[e] > q_pos) S[4 * i4 + e] = 0.f;
         }
       }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) ds[i] = S[i] * (dP[i] - dl);
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const u32x4 ef = {pack2(ds[8 * j + 0], ds[8 * j + 1]), pack2(ds[8 * j + 2], ds[8 * j + 3]),
@@ -312,7 +323,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE_BYTES + VST_BYTES];   // stage: Q tile, dout tile
   __shared__ __attribute__((aligned(16))) float s_l2[2][BT];    // lse log2(e) of the tile's queries (+inf: row contributes nothing)
   __shared__ __attribute__((aligned(16))) float s_dl[2][BT];    // delta of the tile's queries
-  __shared__ int s_tmin;
+  __shared__ int s_tmin, s_tmax;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, lq = lane & 31;
 
@@ -328,12 +339,16 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
 
   // smallest global position among the keys of the tile: queries before it see none of them
   if (tid == 0) {
-    int tmin = INT_MAX;
+    int tmin = INT_MAX, tmax = -1;
     for (int j = 0; j < p.n_rng; ++j) {
       const int a = max(v0, p.rng_vbeg[j]), b = min(v0 + BS, p.rng_vbeg[j + 1]);
-      if (a < b) tmin = min(tmin, p.rng_start[j] + (a - p.rng_vbeg[j]));
+      if (a < b) {
+        tmin = min(tmin, p.rng_start[j] + (a - p.rng_vbeg[j]));
+        tmax = max(tmax, p.rng_start[j] + (b - 1 - p.rng_vbeg[j]));
+      }
     }
     s_tmin = tmin;
+    s_tmax = tmax;
   }
 
   // ---- stationary side: this lane's key (column lq of the wave's strip)
@@ -359,6 +374,9 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
   const float c = p.scale * kLog2e;
   __syncthreads();
   const int tmin = s_tmin;
+  // the element-wise mask is needed for tiles with a query before the last key of the workgroup,
+  // and everywhere if the workgroup holds padding keys
+  const int tmax = (v0 + BS > total_keys) ? INT_MAX : (p.causal ? s_tmax : -1);
 
   // ---- the streamed side: for every query head of the group and every query block, the 64-row
   // tiles from the first one that holds a row at or after tmin.  Iteration state (head, block, tile).
@@ -443,6 +461,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
     const unsigned char* qt_ = smem + stage * C::STAGE_BYTES;
     const unsigned char* ot_ = qt_ + C::TILE_BYTES;
     const int pos0 = p.causal ? p.blk[cur.blk].pos0 + cur.qt * BT : 0;
+    const bool need_mask = tmax > pos0;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       // Five phases in a fixed order (the compiler may not mix them: that would keep S, dP, p and
@@ -460,12 +479,16 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
         const int r0 = 32 * qb + 8 * i4 + 4 * h;
         const f32x4 l2 = *reinterpret_cast<const f32x4*>(&s_l2[stage][r0]);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * i4 + e;
-          const int q_pos = p.causal ? pos0 + r0 + e : INT_MAX - 1;
-          const float x = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c, -l2[e]));
-          S[i] = key_tok > q_pos ? 0.f : x;
-        }
+        for (int e = 0; e < 4; ++e) S[4 * i4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[4 * i4 + e], c, -l2[e]));
+      }
+      if (need_mask) {
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int q_pos = p.causal ? pos0 + 32 * qb + 8 * i4 + 4 * h + e : INT_MAX - 1;
+            if (key_tok > q_pos) S[4 * i4 + e] = 0.f;
+          }
       }
       bf16x8 pb[2];
 #pragma unroll
