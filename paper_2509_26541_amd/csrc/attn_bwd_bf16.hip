@@ -28,6 +28,8 @@
 #include <hip/hip_runtime.h>
 
 #include <climits>
+#include <type_traits>
+#include <utility>
 
 #include "internal.hpp"
 
@@ -95,6 +97,16 @@ __device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
 __device__ inline unsigned pack2(float lo, float hi) {
   const bf16x2 pk = {static_cast<__bf16>(lo), static_cast<__bf16>(hi)};
   return __builtin_bit_cast(unsigned, pk);
+}
+
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
 }
 
 // Workgroups are dealt round-robin to the 8 XCDs; remap so that each XCD gets a contiguous run.
@@ -243,6 +255,20 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const BwdLaunch p) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
 
+  constexpr int NFB = 2 * KS + 2 * DB, NFT = 2 * NFB, PD = 3;
+  bf16x8 ring[PD];        // operand fragments in flight (slot = fragment % PD)
+  auto issue = [&](auto ff, const unsigned char* kt, const unsigned char* vt) __attribute__((always_inline)) {
+    constexpr int F = decltype(ff)::value, kb = F / NFB, f = F % NFB, slot = F % PD;
+    if constexpr (f < KS) {
+      ring[slot] = lds_row8(kt + ra.row[f] + kb * 32 * D * 2);
+    } else if constexpr (f < 2 * KS) {
+      ring[slot] = lds_row8(vt + ra.row[f - KS] + kb * 32 * D * 2);
+    } else {
+      constexpr int j = (f - 2 * KS) / DB, db = (f - 2 * KS) % DB, grp = (2 * kb + j) * 16 * D * 2;
+      ring[slot] = lds_tr8(kt + ra.tr[db][0] + grp, kt + ra.tr[db][1] + grp);
+    }
+  };
+
   if (n_tiles > 0) fetch(0, 0);
   for (int t = 0; t < n_tiles; ++t) {
     const int stage = t & 1;
@@ -254,41 +280,58 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const BwdLaunch p) {
     // most tiles are seen completely by every row: the element-wise mask is skipped for them
     const i32x4 mk = *reinterpret_cast<const i32x4*>(&s_msk[stage][0]);
     const bool need_mask = __builtin_amdgcn_readfirstlane(mk[0] | mk[1] | mk[2] | mk[3]) != 0;
+    // The matrix instructions of a tile as one stream of operand fragments, per 32-key block kb:
+    // KS row fragments of K (scores), KS of V (dout.v), 2 DB transposed fragments of K (dq).  The
+    // read of fragment F + PD is issued right after the instruction that consumed fragment F; the
+    // scheduling barrier after every instruction keeps that order (the compiler still places the
+    // waits itself: these are ordinary loads).  p is formed under the dout.v instructions, ds for
+    // the second 16 keys under the first dq instructions.
+    f32x16 S, dP;
+    u32x4 ef[2];
+    static_for<PD>([&](auto ff) __attribute__((always_inline)) { issue(ff, kt, vt); });
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<NFT>([&](auto ff) __attribute__((always_inline)) {
+      constexpr int F = decltype(ff)::value, kb = F / NFB, f = F % NFB, slot = F % PD;
+      if constexpr (f < KS) {
+        if constexpr (f == 0) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      f32x16 S, dP;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { S[i] = 0.f; dP[i] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) S = mfma(lds_row8(kt + ra.row[ks] + kb * 32 * D * 2), qf[ks], S);
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) dP = mfma(lds_row8(vt + ra.row[ks] + kb * 32 * D * 2), dof[ks], dP);
-      // ds^T for the 32 keys of this block (register 4 i4 + e: key 8 i4 + 4 h + e)
-      float ds[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) S[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c, -lse2));
-      if (need_mask) {
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const i32x4 tk = *reinterpret_cast<const i32x4*>(&s_tok[stage][32 * kb + 8 * i4 + 4 * h]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (tk[e] > q_pos) S[4 * i4 + e] = 0.f;
+          for (int i = 0; i < 16; ++i) S[i] = 0.f;
         }
+        S = mfma(ring[slot], qf[f], S);
+      } else if constexpr (f < 2 * KS) {
+        constexpr int ks = f - KS;
+        if constexpr (ks == 0) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) dP[i] = 0.f;
+        }
+        dP = mfma(ring[slot], dof[ks], dP);
+        constexpr int per = 16 / KS;
+#pragma unroll
+        for (int i = ks * per; i < (ks + 1) * per; ++i) S[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c, -lse2));
+        if constexpr (ks == KS - 1) {
+          if (need_mask) {
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+              const i32x4 tk = *reinterpret_cast<const i32x4*>(&s_tok[stage][32 * kb + 8 * i4 + 4 * h]);
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (tk[e] > q_pos) S[4 * i4 + e] = 0.f;
+            }
+          }
+        }
+      } else {
+        constexpr int j = (f - 2 * KS) / DB, db = (f - 2 * KS) % DB;
+        if constexpr (db == 0) {          // ds^T of the 16 keys of group j (registers 8 j .. 8 j + 7), packed to bf16
+          float ds[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) ds[e] = S[8 * j + e] * (dP[8 * j + e] - dl);
+          ef[j] = u32x4{pack2(ds[0], ds[1]), pack2(ds[2], ds[3]), pack2(ds[4], ds[5]), pack2(ds[6], ds[7])};
+        }
+        dq[db] = mfma(ring[slot], __builtin_bit_cast(bf16x8, ef[j]), dq[db]);
       }
-#pragma unroll
-      for (int i = 0; i < 16; ++i) ds[i] = S[i] * (dP[i] - dl);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const u32x4 ef = {pack2(ds[8 * j + 0], ds[8 * j + 1]), pack2(ds[8 * j + 2], ds[8 * j + 3]),
-                          pack2(ds[8 * j + 4], ds[8 * j + 5]), pack2(ds[8 * j + 6], ds[8 * j + 7])};
-        const bf16x8 eb = __builtin_bit_cast(bf16x8, ef);
-        const int grp = (2 * kb + j) * 16 * D * 2;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-          dq[db] = mfma(lds_tr8(kt + ra.tr[db][0] + grp, kt + ra.tr[db][1] + grp), eb, dq[db]);
-      }
-    }
+      if constexpr (F + PD < NFT) issue(std::integral_constant<int, F + PD>{}, kt, vt);
+      __builtin_amdgcn_sched_barrier(0);
+    });
   }
   wait_all_loads();
 
