@@ -230,10 +230,11 @@ double tasp_chunk_attn_flops(const tasp_schedule_t* s, const tasp_attn_args* a);
  *
  * All tensor pointers are DEVICE pointers, 16-byte aligned, dense row-major, laid out as for
  * tasp_chunk_attn: q, out, dout, dq [B, L, Hq, d]; k, v, dk, dv [B, S, Hkv, d]; lse [B, L, Hq] fp32
- * (out and lse as written by tasp_chunk_attn on the same inputs).  dtype must be TASP_DTYPE_BF16
- * (anything else: TASP_EUNSUPPORTED_SHAPE); d is 64 or 128.  Every row of dq, dk and dv is written.
- * workspace: device, 256-byte aligned, at least tasp_chunk_attn_bwd_workspace_bytes() (an fp32 copy
- * of dq and the delta vector); contents are scratch.  Kernels are enqueued on hip_stream; the call
+ * (out and lse as written by tasp_chunk_attn on the same inputs).  dtype is TASP_DTYPE_BF16 (matrix
+ * instructions, the measured path) or TASP_DTYPE_FP32 (a plain small-shape path, all arithmetic
+ * fp32); d is 64 or 128.  Every row of dq, dk and dv is written.
+ * workspace: device, 256-byte aligned, at least tasp_chunk_attn_bwd_workspace_bytes() (the delta
+ * vector and, for bf16, an fp32 copy of dq); contents are scratch.  Kernels are enqueued on hip_stream; the call
  * returns without synchronising.  Errors as for tasp_chunk_attn.
  * ---------------------------------------------------------------------------------------------- */
 typedef struct tasp_attn_bwd_args {

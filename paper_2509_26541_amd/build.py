@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtasp.so")
-SOURCES = ["schedule.cpp", "attn_bf16.hip", "attn_fp32.hip", "attn_bwd_bf16.hip", "merge.hip", "calib.hip", "api.hip"]
+SOURCES = ["schedule.cpp", "attn_bf16.hip", "attn_fp32.hip", "attn_bwd_bf16.hip", "attn_bwd_fp32.hip", "merge.hip", "calib.hip", "api.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

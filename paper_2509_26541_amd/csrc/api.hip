@@ -150,12 +150,12 @@ int validate_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args* b, tasp_att
   *a = as_forward(b);
   int st = validate(s, a, sh);
   if (st != TASP_OK) return st;
-  if (b->dtype != TASP_DTYPE_BF16) return TASP_EUNSUPPORTED_SHAPE;      // the backward kernels are bf16 only
   if (b->out == nullptr || b->lse == nullptr || b->dout == nullptr || b->dq == nullptr || b->dk == nullptr ||
       b->dv == nullptr)
     return TASP_EINVAL;
-  // the kernels address Q and dout with 32-bit byte offsets
-  if (static_cast<int64_t>(sh->L) * b->Hq * b->d * 2 > (int64_t{1} << 32)) return TASP_EUNSUPPORTED_SHAPE;
+  // the bf16 kernels address Q and dout with 32-bit byte offsets
+  if (b->dtype == TASP_DTYPE_BF16 && static_cast<int64_t>(sh->L) * b->Hq * b->d * 2 > (int64_t{1} << 32))
+    return TASP_EUNSUPPORTED_SHAPE;
   const uintptr_t all = reinterpret_cast<uintptr_t>(b->out) | reinterpret_cast<uintptr_t>(b->dout) |
                         reinterpret_cast<uintptr_t>(b->dq) | reinterpret_cast<uintptr_t>(b->dk) |
                         reinterpret_cast<uintptr_t>(b->dv);
@@ -303,7 +303,9 @@ size_t tasp_chunk_attn_bwd_workspace_bytes(const tasp_schedule_t* s, const tasp_
   if (s == nullptr || b == nullptr || b->S <= 0 || b->Hq <= 0 || b->d <= 0 || s->n <= 0 || b->batch < 0) return 0;
   const int64_t L = b->S / s->n;
   const size_t B = static_cast<size_t>(b->batch == 0 ? 1 : b->batch);
-  return align_up(B * L * b->Hq * b->d * sizeof(float)) + align_up(B * L * b->Hq * sizeof(float));   // fp32 dq, delta
+  const size_t delta_bytes = align_up(B * L * b->Hq * sizeof(float));
+  if (b->dtype == TASP_DTYPE_FP32) return delta_bytes;                   // dq itself is the fp32 accumulator
+  return align_up(B * L * b->Hq * b->d * sizeof(float)) + delta_bytes;   // fp32 dq, delta
 }
 
 double tasp_chunk_attn_bwd_flops(const tasp_schedule_t* s, const tasp_attn_bwd_args* b) {
@@ -329,15 +331,18 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
     hipEvent_t e = nullptr;
     ~Ev() { if (e) (void)hipEventDestroy(e); }
   } fork, join;
-  float* dq_acc = static_cast<float*>(b->workspace);
-  float* delta = reinterpret_cast<float*>(static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes));
+  const bool bf16 = b->dtype == TASP_DTYPE_BF16;
+  float* dq_acc = bf16 ? static_cast<float*>(b->workspace) : static_cast<float*>(b->dq);
+  float* delta = bf16 ? reinterpret_cast<float*>(static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes))
+                      : static_cast<float*>(b->workspace);
   const int64_t n_q_elems = static_cast<int64_t>(sh.B) * sh.L * b->Hq * b->d;
 
   try {
     {
       Scope sc(prof, BwdSpans::kOther);
-      if (tasp::launch_bwd_delta_bf16(b->out, b->dout, delta, static_cast<int64_t>(sh.B) * sh.L * b->Hq, b->d, stream) !=
-          hipSuccess)
+      const int64_t n_rows = static_cast<int64_t>(sh.B) * sh.L * b->Hq;
+      if ((bf16 ? tasp::launch_bwd_delta_bf16(b->out, b->dout, delta, n_rows, b->d, stream)
+                : tasp::launch_bwd_delta_fp32(b->out, b->dout, delta, n_rows, b->d, stream)) != hipSuccess)
         return TASP_EHIP;
       if (tasp::launch_zero_f32(dq_acc, n_q_elems, stream) != hipSuccess) return TASP_EHIP;
     }
@@ -387,11 +392,14 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
       bp.rng_vbeg[ranges.size()] = static_cast<int32_t>(vpos);
       {
         Scope sc(prof, BwdSpans::kDq);
-        if (tasp::launch_bwd_dq_bf16(bp, b->d, stream) != hipSuccess) return TASP_EHIP;
+        if ((bf16 ? tasp::launch_bwd_dq_bf16(bp, b->d, stream) : tasp::launch_bwd_dq_fp32(bp, b->d, stream)) != hipSuccess)
+          return TASP_EHIP;
       }
       {
         Scope sc(prof, BwdSpans::kDkv);
-        if (tasp::launch_bwd_dkv_bf16(bp, b->d, kv_stream) != hipSuccess) return TASP_EHIP;
+        if ((bf16 ? tasp::launch_bwd_dkv_bf16(bp, b->d, kv_stream) : tasp::launch_bwd_dkv_fp32(bp, b->d, kv_stream)) !=
+            hipSuccess)
+          return TASP_EHIP;
       }
     }
     if (kv_stream != stream) {
@@ -399,7 +407,7 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
           tasp::note_hip(hipStreamWaitEvent(stream, join.e, 0)) != hipSuccess)
         return TASP_EHIP;
     }
-    {
+    if (bf16) {
       Scope sc(prof, BwdSpans::kOther);
       if (tasp::launch_cast_bf16(dq_acc, b->dq, n_q_elems, stream) != hipSuccess) return TASP_EHIP;
     }

@@ -45,7 +45,7 @@ struct BwdBlock {
 // segments it can see); the dk/dv kernel uses every key range that arrives at the step, laid end to
 // end (rng_vbeg = start of each range in that concatenation), and the query blocks.
 struct BwdLaunch {
-  const void* q;        // [B, L, Hq, d] bf16
+  const void* q;        // [B, L, Hq, d] bf16 (fp32 for the fp32 kernels, as k, v, dout, dk, dv)
   const void* k;        // [B, S, Hkv, d]
   const void* v;
   const void* dout;     // [B, L, Hq, d]
@@ -100,5 +100,10 @@ hipError_t launch_bwd_dkv_bf16(const BwdLaunch& p, int d, hipStream_t stream);
 hipError_t launch_bwd_delta_bf16(const void* out, const void* dout, float* delta, int64_t n_rows, int d,
                                  hipStream_t stream);
 hipError_t launch_zero_f32(float* dst, int64_t n, hipStream_t stream);   // n a multiple of 4, dst 16-byte aligned
+// Implemented in attn_bwd_fp32.hip (all tensors fp32; dq_acc is dq itself).
+hipError_t launch_bwd_dq_fp32(const BwdLaunch& p, int d, hipStream_t stream);
+hipError_t launch_bwd_dkv_fp32(const BwdLaunch& p, int d, hipStream_t stream);
+hipError_t launch_bwd_delta_fp32(const void* out, const void* dout, float* delta, int64_t n_rows, int d,
+                                 hipStream_t stream);
 
 }  // namespace tasp

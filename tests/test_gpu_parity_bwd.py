@@ -199,3 +199,32 @@ def test_full_size_128k_dense_upstream_gradient(tb):
     slack_k = 6 * 2.0 ** -9 * float(np.sqrt((dk.double().cpu().numpy() ** 2).sum(axis=0)).max())
     assert np.abs(got_v - want).max() <= slack_v + 2.0 ** -8 * np.abs(want).max(), (np.abs(got_v - want).max(), slack_v)
     assert np.abs(got_k).max() <= slack_k + 1e-2, (np.abs(got_k).max(), slack_k)
+
+
+# ------------------------------------------------------------------ fp32 inputs (the plain path): tight bar, no bf16 noise
+FP32 = [
+    ("cfg1", None),
+    ("fp32_zz_n8", (8, 4, 8 * 2 * 40, 2, 2, 64, wl.ZIGZAG_CAUSAL)),
+    ("fp32_full_d128_gqa", (4, 1, 4 * 70, 2, 1, 128, wl.FULL)),
+    ("fp32_zz_n8_d128", (8, 7, 8 * 2 * 33, 4, 2, 128, wl.ZIGZAG_CAUSAL)),
+]
+
+
+@pytest.mark.parametrize("case", FP32, ids=[c[0] for c in FP32])
+def test_fp32_all_outputs(tb, case):
+    """fp32 in, fp32 out: forward then backward on the GPU against the exact gradient, every element,
+    max-abs error at most 1e-4 of max(1, max|ref|) (the forward's bar for fp32)."""
+    name, shape = case
+    if shape is None:
+        w = wl.CONFIGS[0]
+    else:
+        n, rank, S, Hq, Hkv, d, mode = shape
+        w = wl.Workload("bwd_" + name, n, rank, S, Hq, Hkv, d, "fp32", mode, seed=wl.BASE_SEED + 950 + S % 89)
+    q, k, v = wl.make_qkv(w)
+    do = wl.make_dout(w)
+    dq, dk, dv = forward_backward(tb, w, q, k, v, do)
+    assert dq.dtype == torch.float32 and dk.dtype == torch.float32
+    for nm, got, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), oracle_grads(w, q, k, v, do)):
+        got = got.cpu().numpy().astype(np.float64)
+        err = float(np.abs(got - ref).max())
+        assert err <= 1e-4 * max(1.0, float(np.abs(ref).max())), (w.name, nm, err)

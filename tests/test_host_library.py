@@ -266,8 +266,10 @@ def test_backward_argument_checks_and_sizes():
     assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EINVAL           # out, lse, dout, dq, dk, dv missing
     b.out = b.lse = b.dout = b.dq = b.dk = b.dv = 4096
     assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EWORKSPACE
-    b.dtype = tb.DTYPE_FP32
+    b.d = 96
     assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EUNSUPPORTED_SHAPE
+    b.d, b.dtype = 128, tb.DTYPE_FP32
+    assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == (4096 // 8 * 8 * 4 + 255) // 256 * 256   # delta only
     b.dtype, b.dk = tb.DTYPE_BF16, 4104
     assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EALIGN
     b.dk, b.batch = 4096, -1
