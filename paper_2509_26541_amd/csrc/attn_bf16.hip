@@ -29,26 +29,12 @@
 #include <hip/hip_runtime.h>
 
 #include <climits>
-#include <type_traits>
-#include <utility>
 
+#include "gfx950.hpp"
 #include "internal.hpp"
 
 namespace tasp {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-typedef const __attribute__((address_space(1))) void* global_void_ptr;
 
 constexpr int BN = 64;           // keys per tile
 constexpr float kLog2e = 1.4426950408889634f;
@@ -79,26 +65,12 @@ __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float max2(float a, float b) { float r; asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
 __device__ __forceinline__ float max3(float a, float b, float c) { float r; asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c)); return r; }
 
-// One direct global->LDS load of 16 bytes per lane: lane l reads base + off and its bytes land at
-// lds_base + 16 l.  Written as inline assembly so that the wait for it is placed by hand (s_waitcnt
-// vmcnt before the barrier that publishes the tile) instead of in front of the next LDS read; no
-// other vector memory instruction is in flight while these are.  It carries no memory clobber: the
-// stage it fills is not read before the next barrier, and barriers and waits are ordered against
-// volatile assembly.
+// Tile fetches use the direct global->LDS load without a compiler-level fence: the wait for it is
+// placed by hand (s_waitcnt vmcnt before the barrier that publishes the tile), no other vector
+// memory instruction is in flight while these are, the stage it fills is not read before the next
+// barrier, and barriers and waits are ordered against volatile assembly.
 __device__ inline void dma16(const unsigned char* base, unsigned off, unsigned char* lds_base) {
-  const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)lds_base));
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_addr), "v"(off), "s"(base));
-}
-// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
-template <class F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
-  (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+  global_to_lds_16<false>(base, off, lds_base);
 }
 
 // LDS operand reads whose wait is placed by hand.  A read is volatile assembly (issued in program
@@ -199,10 +171,7 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
   const int tiles0 = (p.task[0].n_q + BM - 1) / BM;
   const int tiles1 = p.n_tasks > 1 ? (p.task[1].n_q + BM - 1) / BM : 0;
   const int per_g = (tiles0 + tiles1) * G;
-  const int nblocks = gridDim.x;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int q8 = nblocks >> 3, r8 = nblocks & 7;
-  const int w_all = xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
+  const int w_all = xcd_contiguous(blockIdx.x, gridDim.x);
   const int per_b = per_g * p.Hkv;                            // workgroups of one sequence of the batch
   const int bi = w_all / per_b;
   const int w = w_all - bi * per_b;

@@ -28,24 +28,12 @@
 #include <hip/hip_runtime.h>
 
 #include <climits>
-#include <type_traits>
-#include <utility>
 
+#include "gfx950.hpp"
 #include "internal.hpp"
 
 namespace tasp {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
 
 constexpr int BT = 64;             // streamed rows per tile
 constexpr float kLog2e = 1.4426950408889634f;
@@ -69,15 +57,10 @@ struct BCfg {
   }
 };
 
-// One direct global->LDS load of 16 bytes per lane: lane l reads base + off, its bytes land at
-// lds_base + 16 l.  The compiler does not see it as a memory operation; every use is followed by
-// s_waitcnt vmcnt(0) and a barrier before the tile is read.
+// Tile fetches: direct global->LDS loads with a compiler-level fence (the LDS reads here are
+// ordinary loads); every use is followed by s_waitcnt vmcnt(0) and a barrier before the tile is read.
 __device__ inline void dma16(const unsigned char* base, unsigned off, unsigned char* lds_base) {
-  const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)lds_base));
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_addr), "v"(off), "s"(base)
-               : "m0", "memory");
+  global_to_lds_16<true>(base, off, lds_base);
 }
 __device__ inline void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -97,23 +80,6 @@ __device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
 __device__ inline unsigned pack2(float lo, float hi) {
   const bf16x2 pk = {static_cast<__bf16>(lo), static_cast<__bf16>(hi)};
   return __builtin_bit_cast(unsigned, pk);
-}
-
-// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
-template <class F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
-  (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
-}
-
-// Workgroups are dealt round-robin to the 8 XCDs; remap so that each XCD gets a contiguous run.
-__device__ inline int xcd_contiguous(int block, int nblocks) {
-  const int xcd = block & 7, slot = block >> 3;
-  const int q8 = nblocks >> 3, r8 = nblocks & 7;
-  return xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
 }
 
 // Per-lane byte offsets inside a tile for the two LDS read patterns.

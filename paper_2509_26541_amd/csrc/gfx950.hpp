@@ -1,0 +1,56 @@
+// Small pieces shared by the gfx950 kernels of this library: vector types, a compile-time loop, the
+// direct global->LDS load and the workgroup-to-XCD remap.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+#include <utility>
+
+namespace tasp {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
+
+// One direct global->LDS load of 16 bytes per lane (global_load_lds_dwordx4): lane l reads
+// base + off and its bytes land at lds_base + 16 l, so the 64 lanes of a wavefront fill 1 KiB of
+// consecutive LDS.  No registers and no LDS write instruction are involved; it counts in vmcnt only.
+// The compiler does not see it as a memory operation: the caller waits (s_waitcnt vmcnt) and
+// publishes the data with a barrier before anybody reads it.  FENCE adds a compiler-level memory
+// clobber for callers whose LDS reads are ordinary loads the compiler could otherwise move across.
+template <bool FENCE>
+__device__ inline void global_to_lds_16(const unsigned char* base, unsigned off, unsigned char* lds_base) {
+  const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)lds_base));
+  if constexpr (FENCE)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "m0", "memory");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "m0");
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); this maps the hardware
+// index to a work index such that every XCD gets one contiguous run of the work list.
+__device__ inline int xcd_contiguous(int block, int nblocks) {
+  const int xcd = block & 7, slot = block >> 3;
+  const int q8 = nblocks >> 3, r8 = nblocks & 7;
+  return xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
+}
+
+}  // namespace tasp
