@@ -133,6 +133,15 @@ int tasp_step_segments(const tasp_schedule_t* s, int64_t S, int32_t mask_mode, i
  *                 (update_out_lse of Algorithm 3);  1: the attention kernel folds it in itself.
  *   workspace device, >= tasp_chunk_attn_workspace_bytes() bytes, 256-byte aligned, caller-owned,
  *             contents undefined on entry and exit.
+ *   fuse_steps 0: one attention launch per step, each followed by update_out_lse as above (the
+ *                 form in which a step can start as soon as its sub-chunks have arrived);
+ *              1: ONE launch walks the sub-chunks of all N steps in arrival order and carries the
+ *                 running max / sum / output across them, so no partial pair is ever written or
+ *                 merged (the log-sum-exp rescale happens in registers).  For callers whose K and V
+ *                 are resident when the call is made; it removes the per-step launch, set-up and
+ *                 merge costs, which dominate for short sequences.  bf16 only, at most
+ *                 TASP_MAX_FUSED_SEGMENTS visible segments per query block over all steps
+ *                 (otherwise TASP_EUNSUPPORTED_SHAPE); fuse_merge is ignored.
  *   batch    B independent sequences handled in one call (0 counts as 1, at most 65535): every
  *            tensor gets a leading dimension, q/out [B, L, Hq, d], k/v [B, S, Hkv, d], lse
  *            [B, L, Hq]; all sequences share S, the schedule and the mask (the shape grid of the
@@ -158,7 +167,9 @@ typedef struct tasp_attn_args {
   int32_t     fuse_merge;
   float       softmax_scale;
   int32_t     batch;
+  int32_t     fuse_steps;
 } tasp_attn_args;
+#define TASP_MAX_FUSED_SEGMENTS 1024
 
 size_t tasp_chunk_attn_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_args* a);
 int    tasp_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream);

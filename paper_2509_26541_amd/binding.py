@@ -44,7 +44,7 @@ class AttnArgs(C.Structure):
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("S", C.c_int64),
         ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32), ("dtype", C.c_int32),
         ("mask_mode", C.c_int32), ("order", C.c_int32), ("fuse_merge", C.c_int32), ("softmax_scale", C.c_float),
-        ("batch", C.c_int32),
+        ("batch", C.c_int32), ("fuse_steps", C.c_int32),
     ]
 
 
@@ -193,7 +193,7 @@ def _torch():
     return torch
 
 
-def _args(q, k, v, mask_mode, order, fuse_merge, softmax_scale):
+def _args(q, k, v, mask_mode, order, fuse_merge, softmax_scale, fuse_steps=False):
     torch = _torch()
     if not (q.is_cuda and k.is_cuda and v.is_cuda):
         raise ValueError("q, k, v must be device tensors")
@@ -211,16 +211,18 @@ def _args(q, k, v, mask_mode, order, fuse_merge, softmax_scale):
     a.batch = q.shape[0] if q.dim() == 4 else 1
     a.dtype = DTYPE_FP32 if q.dtype == torch.float32 else DTYPE_BF16
     a.mask_mode, a.order, a.fuse_merge, a.softmax_scale = mask_mode, order, int(bool(fuse_merge)), softmax_scale
+    a.fuse_steps = int(bool(fuse_steps))
     return a
 
 
 class ChunkAttnPlan:
     """Buffers of one tasp_chunk_attn shape (out, lse, workspace), so that repeated calls allocate nothing."""
 
-    def __init__(self, schedule, q, k, v, mask_mode, order=ORDER_TASP, fuse_merge=False, softmax_scale=0.0):
+    def __init__(self, schedule, q, k, v, mask_mode, order=ORDER_TASP, fuse_merge=False, softmax_scale=0.0,
+                 fuse_steps=False):
         torch = _torch()
         self.schedule = schedule
-        self.args = _args(q, k, v, mask_mode, order, fuse_merge, softmax_scale)
+        self.args = _args(q, k, v, mask_mode, order, fuse_merge, softmax_scale, fuse_steps)
         if q.shape[-3] * schedule.n_ranks != k.shape[-3]:
             raise ValueError("q must hold S / N local rows")
         self.out = torch.empty_like(q)
@@ -250,9 +252,10 @@ class ChunkAttnPlan:
         return lib.tasp_chunk_attn_flops(self.schedule.handle, C.byref(self.args))
 
 
-def tasp_chunk_attn(q, k, v, schedule, mask_mode, order=ORDER_TASP, fuse_merge=False, softmax_scale=0.0):
+def tasp_chunk_attn(q, k, v, schedule, mask_mode, order=ORDER_TASP, fuse_merge=False, softmax_scale=0.0,
+                    fuse_steps=False):
     """One rank's forward pass (Algorithm 3).  Returns (out [L, Hq, d] in q's dtype, lse [L, Hq] fp32)."""
-    return ChunkAttnPlan(schedule, q, k, v, mask_mode, order, fuse_merge, softmax_scale).run()
+    return ChunkAttnPlan(schedule, q, k, v, mask_mode, order, fuse_merge, softmax_scale, fuse_steps).run()
 
 
 class ChunkAttnBwdPlan:

@@ -17,6 +17,7 @@ using tasp::AttnLaunch;
 using tasp::AttnTask;
 
 constexpr size_t kAlign = 256;
+constexpr size_t kFusedTableBytes = static_cast<size_t>(tasp::kMaxTasks) * 2 * tasp::kMaxSegAll * sizeof(int32_t);
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Shape {
@@ -47,6 +48,8 @@ int validate(const tasp_schedule_t* s, const tasp_attn_args* a, Shape* sh) {
   }
   if (2 * s->n_rings > tasp::kMaxSeg) return TASP_EUNSUPPORTED_SHAPE;
   if (a->batch < 0 || a->batch > 65535) return TASP_EINVAL;
+  if (a->fuse_steps != 0 && a->fuse_steps != 1) return TASP_EINVAL;
+  if (a->fuse_steps && a->dtype != TASP_DTYPE_BF16) return TASP_EUNSUPPORTED_SHAPE;
   if ((reinterpret_cast<uintptr_t>(a->q) | reinterpret_cast<uintptr_t>(a->k) | reinterpret_cast<uintptr_t>(a->v)) & 15)
     return TASP_EALIGN;
   sh->L = a->S / s->n;
@@ -183,6 +186,7 @@ size_t tasp_chunk_attn_workspace_bytes(const tasp_schedule_t* s, const tasp_attn
   const size_t lse_bytes = align_up(B * L * a->Hq * sizeof(float));
   size_t total = 0;
   if (a->dtype == TASP_DTYPE_BF16) total += o_bytes;              // running fp32 output
+  if (a->fuse_steps) return total + align_up(kFusedTableBytes);   // the segment lists of the single launch
   if (!a->fuse_merge) total += o_bytes + lse_bytes;               // partial (out_s, lse_s) of a step
   return total;
 }
@@ -244,14 +248,63 @@ static int run_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, voi
   if (a->dtype == TASP_DTYPE_BF16) { o_run = reinterpret_cast<float*>(ws); ws += align_up(sh.o_bytes); }
   float* o_part = nullptr;
   float* lse_part = nullptr;
-  if (!a->fuse_merge) {
+  if (!a->fuse_merge && !a->fuse_steps) {
     o_part = reinterpret_cast<float*>(ws); ws += align_up(sh.o_bytes);
     lse_part = reinterpret_cast<float*>(ws);
   }
 
   try {
     std::vector<tasp::QueryBlock> empty;
-    for (int step = 0; step < s->n; ++step) {
+    if (a->fuse_steps) {
+      // One launch over the segments of every step, in arrival order, per query block.
+      AttnLaunch all{};
+      std::vector<int32_t> table[tasp::kMaxTasks];
+      int64_t keys[tasp::kMaxTasks] = {0, 0};
+      for (int step = 0; step < s->n; ++step) {
+        AttnLaunch lp{};
+        empty.clear();
+        st = build_step(s, a, step, &lp, &empty);
+        if (st != TASP_OK) return st;
+        if (step == 0) {
+          // every query block sees its own diagonal at step 0, so step 0 defines the blocks
+          if (!empty.empty()) return TASP_EUNSUPPORTED_SHAPE;
+          all = lp;
+          for (int t = 0; t < all.n_tasks; ++t) all.task[t].n_seg = 0;
+        }
+        for (int t = 0; t < lp.n_tasks; ++t) {
+          int dst = -1;
+          for (int u = 0; u < all.n_tasks; ++u)
+            if (all.task[u].q_row0 == lp.task[t].q_row0) dst = u;
+          if (dst < 0) return TASP_EUNSUPPORTED_SHAPE;
+          for (int i = 0; i < lp.task[t].n_seg; ++i) {
+            table[dst].push_back(lp.task[t].seg_start[i]);
+            table[dst].push_back(lp.task[t].seg_end[i]);
+            keys[dst] += lp.task[t].seg_end[i] - lp.task[t].seg_start[i];
+          }
+        }
+      }
+      int32_t* dev_table = reinterpret_cast<int32_t*>(ws);
+      for (int t = 0; t < all.n_tasks; ++t) {
+        const size_t n_seg = table[t].size() / 2;
+        if (n_seg > static_cast<size_t>(tasp::kMaxSegAll)) return TASP_EUNSUPPORTED_SHAPE;
+        all.task[t].n_seg = static_cast<int32_t>(n_seg);
+        all.seg_ext[t] = dev_table + static_cast<size_t>(t) * 2 * tasp::kMaxSegAll;
+        Scope sc(prof, Profiler::kOther);
+        if (tasp::launch_write_i32(dev_table + static_cast<size_t>(t) * 2 * tasp::kMaxSegAll, table[t].data(),
+                                   static_cast<int64_t>(table[t].size()), stream) != hipSuccess)
+          return TASP_EHIP;
+      }
+      if (all.n_tasks == 2 && keys[1] > keys[0]) {
+        std::swap(all.task[0], all.task[1]);
+        std::swap(all.seg_ext[0], all.seg_ext[1]);
+      }
+      all.o_dst = o_run; all.lse_dst = a->lse; all.merge = 0;
+      {
+        Scope sc(prof, Profiler::kAttn);
+        if (launch_attn(all, a, stream) != hipSuccess) return TASP_EHIP;
+      }
+    }
+    for (int step = 0; step < s->n && !a->fuse_steps; ++step) {
       AttnLaunch lp{};
       empty.clear();
       st = build_step(s, a, step, &lp, &empty);

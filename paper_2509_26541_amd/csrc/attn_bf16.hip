@@ -151,12 +151,14 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
 
   __shared__ __attribute__((aligned(16))) unsigned char smem[C::SMEM];   // ring of stages, each a K tile then a V tile
   __shared__ __attribute__((aligned(16))) int s_tok[C::STAGES][BN];   // global position of every key row of a tile (INT_MAX: none)
-  __shared__ int e_vbeg[2 * kMaxSeg + 1];  // effective segments: start in the virtual concatenation
-  __shared__ int e_goff[2 * kMaxSeg];      //   global position minus virtual position
-  __shared__ int e_diag[2 * kMaxSeg];      //   straddles the diagonal of this query tile
+  // Effective segments: the segments are disjoint ranges of the sequence, so at most one of them
+  // holds the first position of the query tile and is split in two; hence kMaxSegAll + 2 entries.
+  __shared__ int e_vbeg[kMaxSegAll + 2];   // start in the virtual concatenation
+  __shared__ int e_goff[kMaxSegAll + 2];   //   global position minus virtual position
+  __shared__ int e_diag[kMaxSegAll + 2];   //   straddles the diagonal of this query tile
   __shared__ int e_n;
-  __shared__ int m_lo[2 * kMaxSeg + 2];    // runs of tiles that need the element-wise mask (sorted, the
-  __shared__ int m_hi[2 * kMaxSeg + 2];    //   last run is open-ended: m_hi = INT_MAX)
+  __shared__ int m_lo[kMaxSegAll + 2];     // runs of tiles that need the element-wise mask (sorted, the
+  __shared__ int m_hi[kMaxSegAll + 2];     //   last run is open-ended: m_hi = INT_MAX)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -189,34 +191,71 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
 
   // ---- effective segment list of this query tile: drop what the causal mask hides from every
   // row, split the rest into a part every row sees and a part that straddles the diagonal.
-  if (tid == 0) {
-    int n = 0, vpos = 0;
-    for (int s = 0; s < T.n_seg; ++s) {
-      const int a = T.seg_start[s], b = T.seg_end[s];
-      if (!p.causal) {
-        e_vbeg[n] = vpos; e_goff[n] = a - vpos; e_diag[n] = 0; vpos += b - a; ++n;
-        continue;
+  // In single-launch mode the list comes from device memory; it is staged in the (still unused)
+  // tile ring first.
+  const int32_t* seg_ext = p.seg_ext[tsk];
+  const int* seg_raw = reinterpret_cast<const int*>(smem);
+  if (seg_ext != nullptr) {
+    for (int i = tid; i < 2 * T.n_seg; i += C::NTHREADS) reinterpret_cast<int*>(smem)[i] = seg_ext[i];
+    __syncthreads();
+  }
+  // The first wavefront builds the list, 64 segments per round: every lane classifies one segment
+  // on its own; only the positions in the list and in the virtual concatenation are running sums
+  // (wavefront scans).  The tile ranges of the diagonal parts go to m_lo / m_hi first and are
+  // merged into runs in place by one lane.
+  if (wave == 0) {
+    int n_base = 0, v_base = 0, d_base = 0;      // entries, keys and diagonal entries so far (uniform)
+    for (int s0 = 0; s0 < T.n_seg; s0 += 64) {
+      const int s = s0 + lane;
+      int a = 0, len_f = 0, len_d = 0, start_d = 0;
+      if (s < T.n_seg) {
+        a = seg_ext ? seg_raw[2 * s] : T.seg_start[s];
+        const int b = seg_ext ? seg_raw[2 * s + 1] : T.seg_end[s];
+        if (!p.causal) {
+          len_f = b - a;
+        } else if (a <= qb) {
+          const int b_vis = min(b, qb + 1);
+          const int full_end = min(b_vis, qa + 1);        // keys before it are seen by every row of the tile
+          len_f = max(0, full_end - a);
+          start_d = max(a, full_end);
+          len_d = max(0, b_vis - start_d);
+        }
       }
-      if (a > qb) continue;
-      const int b_vis = min(b, qb + 1);
-      const int full_end = min(b_vis, qa + 1);
-      if (a < full_end) { e_vbeg[n] = vpos; e_goff[n] = a - vpos; e_diag[n] = 0; vpos += full_end - a; ++n; }
-      const int ds = max(a, full_end);
-      if (ds < b_vis) { e_vbeg[n] = vpos; e_goff[n] = ds - vpos; e_diag[n] = 1; vpos += b_vis - ds; ++n; }
+      const int cnt = (len_f > 0 ? 1 : 0) + (len_d > 0 ? 1 : 0), len = len_f + len_d, dg = len_d > 0 ? 1 : 0;
+      int sc = cnt, sl = len, sd = dg;                      // inclusive scans
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int t1 = __shfl_up(sc, o), t2 = __shfl_up(sl, o), t3 = __shfl_up(sd, o);
+        if (lane >= o) { sc += t1; sl += t2; sd += t3; }
+      }
+      int idx = n_base + sc - cnt, vpos = v_base + sl - len;
+      const int didx = d_base + sd - dg;
+      if (len_f > 0) { e_vbeg[idx] = vpos; e_goff[idx] = a - vpos; e_diag[idx] = 0; ++idx; vpos += len_f; }
+      if (len_d > 0) {
+        e_vbeg[idx] = vpos; e_goff[idx] = start_d - vpos; e_diag[idx] = 1;
+        m_lo[didx] = vpos / BN; m_hi[didx] = (vpos + len_d - 1) / BN;
+      }
+      n_base += __shfl(sc, 63); v_base += __shfl(sl, 63); d_base += __shfl(sd, 63);
     }
-    e_vbeg[n] = vpos;
-    e_n = n;
-    // tiles that touch a diagonal segment, and everything from the first tile that runs past the last key
-    int mn = 0;
-    for (int j = 0; j < n; ++j) {
-      if (!e_diag[j]) continue;
-      const int lo = e_vbeg[j] / BN, hi = (e_vbeg[j + 1] - 1) / BN;
-      if (mn > 0 && lo <= m_hi[mn - 1]) m_hi[mn - 1] = max(m_hi[mn - 1], hi);
-      else { m_lo[mn] = lo; m_hi[mn] = hi; ++mn; }
+    if (lane == 0) {
+      e_vbeg[n_base] = v_base;
+      e_n = n_base;
+      // runs of tiles that touch a diagonal part, and everything from the first tile that runs past the last key
+      int mn = 0, cur_lo = -1, cur_hi = -1;
+      for (int k = 0; k < d_base; ++k) {
+        const int lo = m_lo[k], hi = m_hi[k];
+        if (cur_lo >= 0 && lo <= cur_hi) { cur_hi = max(cur_hi, hi); continue; }
+        if (cur_lo >= 0) { m_lo[mn] = cur_lo; m_hi[mn] = cur_hi; ++mn; }    // mn <= k: entry k has been read
+        cur_lo = lo; cur_hi = hi;
+      }
+      const int tail = v_base / BN;
+      if (cur_lo >= 0 && tail <= cur_hi) {
+        m_lo[mn] = cur_lo; m_hi[mn] = INT_MAX;
+      } else {
+        if (cur_lo >= 0) { m_lo[mn] = cur_lo; m_hi[mn] = cur_hi; ++mn; }
+        m_lo[mn] = tail; m_hi[mn] = INT_MAX;
+      }
     }
-    const int tail = vpos / BN;
-    if (mn > 0 && tail <= m_hi[mn - 1]) m_hi[mn - 1] = INT_MAX;
-    else { m_lo[mn] = tail; m_hi[mn] = INT_MAX; ++mn; }
   }
   __syncthreads();
   const int n_eff = e_n;

@@ -8,6 +8,7 @@ namespace tasp {
 
 constexpr int kMaxSeg = 64;      // KV segments one query block can see in one step (2(N-1) for zig-zag)
 constexpr int kMaxTasks = 2;     // query blocks per step (the two half-chunks of the zig-zag layout)
+constexpr int kMaxSegAll = 1024; // segments of one query block over ALL steps (single-launch mode)
 
 // One query block of one step: rows [q_row0, q_row0 + n_q) of the local Q, contiguous in the
 // sequence from q_pos0, attending to the concatenation of seg[0..n_seg).
@@ -34,6 +35,9 @@ struct AttnLaunch {
   int64_t q_bstride, kv_bstride, o_bstride, lse_bstride;
   int32_t n_tasks;
   AttnTask task[kMaxTasks];
+  // Single-launch mode: the segment list of task t does not fit the descriptor and lives in device
+  // memory as task[t].n_seg (start, end) pairs; task[t].seg_start / seg_end are then unused.
+  const int32_t* seg_ext[kMaxTasks];
 };
 
 // One contiguous run of local query rows (a half-chunk of the zig-zag layout, or all rows).
@@ -94,6 +98,9 @@ hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const
 hipError_t launch_fill_empty(float* o, float* lse, int64_t row0, int64_t rows, int32_t heads, int32_t d,
                              int32_t batch, int64_t L, hipStream_t stream);
 hipError_t launch_cast_bf16(const float* src, void* dst, int64_t n, hipStream_t stream);
+// Writes n host integers to device memory with small kernels that carry them as arguments (no copy
+// from host memory is enqueued, so the call can be recorded into a graph).
+hipError_t launch_write_i32(int32_t* dst, const int32_t* host_vals, int64_t n, hipStream_t stream);
 // Implemented in attn_bwd_bf16.hip.
 hipError_t launch_bwd_dq_bf16(const BwdLaunch& p, int d, hipStream_t stream);
 hipError_t launch_bwd_dkv_bf16(const BwdLaunch& p, int d, hipStream_t stream);

@@ -154,6 +154,28 @@ hipError_t launch_cast_bf16(const float* src, void* dst, int64_t n, hipStream_t 
                      static_cast<__bf16*>(dst), n4);
 }
 
+namespace {
+constexpr int kI32PerLaunch = 896;
+struct I32Chunk {
+  int32_t n;
+  int32_t v[kI32PerLaunch];
+};
+__global__ __launch_bounds__(256) void write_i32_kernel(int32_t* __restrict__ dst, const I32Chunk c) {
+  for (int i = threadIdx.x; i < c.n; i += 256) dst[i] = c.v[i];
+}
+}  // namespace
+
+hipError_t launch_write_i32(int32_t* dst, const int32_t* host_vals, int64_t n, hipStream_t stream) {
+  for (int64_t i0 = 0; i0 < n; i0 += kI32PerLaunch) {
+    I32Chunk c{};
+    c.n = static_cast<int32_t>(n - i0 < kI32PerLaunch ? n - i0 : kI32PerLaunch);
+    for (int i = 0; i < c.n; ++i) c.v[i] = host_vals[i0 + i];
+    const hipError_t e = TASP_LAUNCH(write_i32_kernel, dim3(1), dim3(256), stream, dst + i0, c);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 }  // namespace tasp
 
 extern "C" int tasp_calibration_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {

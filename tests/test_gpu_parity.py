@@ -82,6 +82,32 @@ def test_small_all_rows(tb, case, fuse):
     check(w, out, lse, ref_o, ref_l, rows)
 
 
+SMALL_BF16 = [c for c in SMALL if not c[0].startswith("fp32")]
+
+
+@pytest.mark.parametrize("case", SMALL_BF16, ids=[c[0] for c in SMALL_BF16])
+def test_small_all_rows_single_launch(tb, case):
+    """fuse_steps: one launch walks the sub-chunks of all steps in arrival order."""
+    name, base, n, rank, S, Hq, Hkv, d = case
+    b = wl.CONFIGS[base]
+    w = wl.Workload(name, n, rank, S, Hq, Hkv, d, "bf16", wl.ZIGZAG_CAUSAL if "_zz_" in name else wl.FULL,
+                    k_scale=b.k_scale, outlier_frac=0.05 if "outliers" in name else 0.0, seed=b.seed + 100)
+    q, k, v = wl.make_qkv(w)
+    rows = list(range(w.L))
+    ref_o, ref_l = oracle_rows(w, q, k, v, rows)
+    for kw in ({}, {"order": tb.ORDER_RING}):
+        out, lse = run_gpu(tb, w, q, k, v, fuse_steps=True, **kw)
+        check(w, out, lse, ref_o, ref_l, rows)
+
+
+def test_single_launch_refuses_what_it_cannot_do(tb):
+    w = wl.CONFIGS[0]                                    # fp32
+    q, k, v = (x.cuda() for x in wl.make_qkv(w))
+    with pytest.raises(tb.TaspError) as e:
+        tb.tasp_chunk_attn(q, k, v, tb.tasp_schedule(w.n_ranks, w.rank), w.mask_mode, fuse_steps=True)
+    assert e.value.status == tb.EUNSUPPORTED_SHAPE
+
+
 def test_ring_order_gives_the_same_result(tb):
     w = wl.Workload("ring", 8, 3, 4096, 8, 2, 128, "bf16", wl.ZIGZAG_CAUSAL, seed=wl.BASE_SEED + 77)
     q, k, v = wl.make_qkv(w)
@@ -322,10 +348,10 @@ def test_full_size_sampled_rows(tb, idx, n_all_heads, n_one_head):
     q, k, v = wl.make_qkv(w)
     s = tb.tasp_schedule(w.n_ranks, w.rank)
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
-    say("running tasp_chunk_attn (merge kernel, then fused merge)")
+    say("running tasp_chunk_attn (merge kernel, fused merge, all steps in one launch)")
     results = {}
-    for fuse in (False, True):
-        out, lse = tb.tasp_chunk_attn(qd, kd, vd, s, w.mask_mode, fuse_merge=fuse)
+    for fuse in (False, True, "one launch"):
+        out, lse = tb.tasp_chunk_attn(qd, kd, vd, s, w.mask_mode, fuse_merge=bool(fuse), fuse_steps=fuse == "one launch")
         torch.cuda.synchronize()
         results[fuse] = (out.float().cpu().numpy(), lse.cpu().numpy())
     del qd, kd, vd
@@ -346,3 +372,4 @@ def test_full_size_sampled_rows(tb, idx, n_all_heads, n_one_head):
     for out, lse in results.values():
         assert np.all(np.isfinite(lse)) and np.all(np.isfinite(out))
     assert max_abs(results[False][1], results[True][1]) <= 1e-4
+    assert max_abs(results["one launch"][1], results[True][1]) <= 1e-4
