@@ -204,6 +204,26 @@ def main():
                 merge = merge_stats(a_ms, a_n, n_prof)
         del alt
 
+    # all steps in one launch (no per-step launch, set-up or merge); reported beside `value`, which
+    # stays the step-by-step form with a merge after every block
+    single = None
+    if is_bf16 and not args.no_other_mode:
+        try:
+            one = tb.ChunkAttnPlan(sched, qd, kd, vd, w.mask_mode, order=order, fuse_steps=True)
+            for _ in range(max(1, args.warmup)):
+                one.run()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                one.run()
+            torch.cuda.synchronize()
+            one_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+            single = {"fuse_steps": 1, "ms_per_step": one_ms, "value": flops / (one_ms * 1e-3) / 1e12,
+                      "frac_of_bf16_mfma_peak": flops / (one_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+            del one
+        except tb.TaspError as e:                 # more segments than the single launch takes
+            single = {"fuse_steps": 1, "error": str(e)}
+
     def event_ms(fn, reps):
         fn()
         torch.cuda.synchronize()
@@ -293,6 +313,7 @@ def main():
         "merge": merge,
         "ms_breakdown": {"attn": attn_ms / n_prof, "merge": merge_ms / n_prof, "cast": other_ms / n_prof},
         "other_merge_mode": other,
+        "single_launch": single,
         "merge_many": merge_many,
         "backward": backward,
     }

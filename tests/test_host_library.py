@@ -251,6 +251,14 @@ def test_flops_and_workspace():
         a.batch = -1
         assert tb.lib.tasp_chunk_attn_workspace_bytes(s.handle, C.byref(a)) == 0
         assert tb.lib.tasp_chunk_attn(s.handle, C.byref(a), None) == tb.EINVAL
+        # all steps in one launch: the running output (bf16 only) and the segment table
+        a.batch, a.fuse_steps = 1, 1
+        assert tb.lib.tasp_chunk_attn_workspace_bytes(s.handle, C.byref(a)) == (o if dt else 0) + 2 * 2 * 1024 * 4
+        a.q = a.k = a.v = a.out = a.lse = 4096
+        a.fuse_steps = 2
+        assert tb.lib.tasp_chunk_attn(s.handle, C.byref(a), None) == tb.EINVAL
+        a.fuse_steps = 1
+        assert tb.lib.tasp_chunk_attn(s.handle, C.byref(a), None) == (tb.EWORKSPACE if dt else tb.EUNSUPPORTED_SHAPE)
 
 
 def test_backward_argument_checks_and_sizes():
