@@ -383,9 +383,15 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[s][db][i] = 0.f;
-  float m_run[NS], l_run[NS];   // running max in the exp2 domain (scaled scores times log2 e); this lane's share of the running sum
+  // Running max in the exp2 domain (scaled scores times log2 e) and this lane's share of the
+  // running sum.  The sum is kept in two levels - the last (up to) 64 tiles in l_lo, everything
+  // before in l_run - because a single fp32 accumulator that already holds a few large terms
+  // swallows the many small ones that follow (each below half an ulp of it): with a million keys
+  // and outlier scores that alone costs up to 1e-3 in lse.  The sum of 64 tiles is large enough to
+  // register, and a large term sits in l_lo for 64 tiles at most.
+  float m_run[NS], l_run[NS], l_lo[NS];
 #pragma unroll
-  for (int s = 0; s < NS; ++s) { m_run[s] = kNegBig; l_run[s] = 0.f; }
+  for (int s = 0; s < NS; ++s) { m_run[s] = kNegBig; l_run[s] = 0.f; l_lo[s] = 0.f; }
   const float c = p.scale * kLog2e;
   auto fence_o = [&]() __attribute__((always_inline)) {
     fence_o_first<ACC>(o[0][0]);
@@ -455,6 +461,7 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
         const float alpha = fast_exp2(m_run[s] - m_cand[s]);
         m_run[s] = m_cand[s];
         l_run[s] *= alpha;
+        l_lo[s] *= alpha;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
 #pragma unroll
@@ -473,8 +480,8 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
   auto use_exp = [&](auto ei) __attribute__((always_inline)) {      // consume element EI, whose exp is x_late (x_later holds EI-1)
     constexpr int EI = decltype(ei)::value;
     constexpr int gg = EI / (8 * NS), s = (EI % (8 * NS)) / 8, e = EI % 8;
-    l_run[s] += x_late;
-    asm volatile("" : "+v"(l_run[s]));           // keeps the addition here instead of in a later block
+    l_lo[s] += x_late;
+    asm volatile("" : "+v"(l_lo[s]));            // keeps the addition here instead of in a later block
     if constexpr (e % 2 == 1) {
       const bf16x2 pk = {static_cast<__bf16>(x_later), static_cast<__bf16>(x_late)};
       pf[s][gg][e / 2] = __builtin_bit_cast(unsigned, pk);
@@ -642,6 +649,10 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
     for (int t = 0; t < n_tiles; t += 2) {
       body(t, Sa, Sb);
       body(t + 1, Sb, Sa);
+      if ((t & 62) == 62) {                      // every 64 tiles
+#pragma unroll
+        for (int s = 0; s < NS; ++s) { l_run[s] += l_lo[s]; l_lo[s] = 0.f; }
+      }
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // no fetch may still be writing LDS when the workgroup ends
@@ -652,7 +663,8 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
   // 32-byte pieces of 32 rows per store and the 16 stores of a lane complete its 512-byte row.
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
-    const float l_tot = l_run[s] + __shfl_xor(l_run[s], 32);
+    const float l_mine = l_run[s] + l_lo[s];
+    const float l_tot = l_mine + __shfl_xor(l_mine, 32);
     const bool seen = l_tot > 0.f;
     const float inv = seen ? 1.f / l_tot : 0.f;
     float lse_new = seen ? (m_run[s] + __builtin_amdgcn_logf(l_tot)) * kLn2 : -__builtin_inff();
