@@ -373,3 +373,28 @@ def test_full_size_sampled_rows(tb, idx, n_all_heads, n_one_head):
         assert np.all(np.isfinite(lse)) and np.all(np.isfinite(out))
     assert max_abs(results[False][1], results[True][1]) <= 1e-4
     assert max_abs(results["one launch"][1], results[True][1]) <= 1e-4
+
+
+@pytest.mark.timeout(600)
+def test_long_row_with_one_dominant_early_key(tb):
+    """Half a million keys, the very first of which outweighs each of the others by e^20 while all
+    the others together still make up 1e-3 of the sum: a single fp32 accumulator would swallow every
+    one of them (each is below half an ulp of it) and lose 1e-3 in lse.  The bar here is 1e-4."""
+    n, rank, S, d = 8, 0, 8 * 65536, 64
+    w = wl.Workload("dominant_first_key", n, rank, S, 1, 1, d, "bf16", wl.FULL, seed=wl.BASE_SEED + 4242)
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(w.seed)
+    u = torch.full((d,), 1.0 / 8.0)                                   # unit vector
+    q = (torch.randn((w.L, 1, d), generator=gen) + 4.0 * u).to(torch.bfloat16)
+    k = (0.3 * torch.randn((S, 1, d), generator=gen)).to(torch.bfloat16)
+    v = torch.randn((S, 1, d), generator=gen).to(torch.bfloat16)
+    k[0, 0] = (40.0 * u).to(torch.bfloat16)                           # score 40 * 4 / sqrt(64) = 20 above the rest
+    rows = wl.sample_rows(w, 12)[:20]
+    ref_o, ref_l = oracle_rows(w, q, k, v, rows)
+    s = tb.tasp_schedule(n, rank)
+    for kw in (dict(fuse_merge=True), dict(fuse_steps=True)):
+        out, lse = tb.tasp_chunk_attn(q.cuda(), k.cuda(), v.cuda(), s, w.mask_mode, **kw)
+        torch.cuda.synchronize()
+        err = max_abs(lse.cpu().numpy()[rows], ref_l)
+        assert err <= 1e-4, (kw, err)
+        assert max_abs(out.float().cpu().numpy()[rows], ref_o) <= 2e-2
