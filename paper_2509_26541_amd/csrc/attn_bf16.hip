@@ -189,6 +189,21 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
   const int qa = T.q_pos0 + q_tile_row0;                      // first and last position of the tile
   const int qb = qa + q_rows_here - 1;
 
+  // ---- Q fragments (B operand of K Q^T), strip s: lane holds query 32 s + lq, d = 16 ks + 8 h .. +8.
+  // Issued first: their way from memory overlaps the construction of the segment list below.
+  int my_q[NS], q_pos[NS];
+  bool q_valid[NS];
+  u32x4 qf[NS][KS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    my_q[s] = q_tile_row0 + wave * (32 * NS) + 32 * s + lq;          // row inside the task
+    q_valid[s] = my_q[s] < T.n_q;
+    const int64_t q_row = T.q_row0 + (q_valid[s] ? my_q[s] : T.n_q - 1);
+    const __bf16* src = static_cast<const __bf16*>(p.q) + bi * p.q_bstride + (q_row * p.Hq + hq) * D + 8 * h;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[s][ks] = *reinterpret_cast<const u32x4*>(src + 16 * ks);
+    q_pos[s] = p.causal ? T.q_pos0 + my_q[s] : INT_MAX - 1;
+  }
   // ---- effective segment list of this query tile: drop what the causal mask hides from every
   // row, split the rest into a part every row sees and a part that straddles the diagonal.
   // In single-launch mode the list comes from device memory; it is staged in the (still unused)
@@ -262,20 +277,6 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
   const int total_keys = e_vbeg[n_eff];
   const int n_tiles = (total_keys + BN - 1) / BN;
 
-  // ---- Q fragments (B operand of K Q^T), strip s: lane holds query 32 s + lq, d = 16 ks + 8 h .. +8
-  int my_q[NS], q_pos[NS];
-  bool q_valid[NS];
-  u32x4 qf[NS][KS];
-#pragma unroll
-  for (int s = 0; s < NS; ++s) {
-    my_q[s] = q_tile_row0 + wave * (32 * NS) + 32 * s + lq;          // row inside the task
-    q_valid[s] = my_q[s] < T.n_q;
-    const int64_t q_row = T.q_row0 + (q_valid[s] ? my_q[s] : T.n_q - 1);
-    const __bf16* src = static_cast<const __bf16*>(p.q) + bi * p.q_bstride + (q_row * p.Hq + hq) * D + 8 * h;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[s][ks] = *reinterpret_cast<const u32x4*>(src + 16 * ks);
-    q_pos[s] = p.causal ? T.q_pos0 + my_q[s] : INT_MAX - 1;
-  }
   // Land the Q fragments now (vmcnt(0)): the waits for the tile fetches below count vector memory
   // instructions and assume that nothing else is in flight.
   __builtin_amdgcn_s_waitcnt(0x0F70);
