@@ -265,8 +265,9 @@ def main():
         gen = torch.Generator(device=dev)
         gen.manual_seed(w.seed + 104729)
         dout = torch.randn(qd.shape, generator=gen, device=dev, dtype=torch.float32).to(qd.dtype)
-        def time_bwd(aux):
-            pl = tb.ChunkAttnBwdPlan(sched, qd, kd, vd, out_f, lse_f, dout, w.mask_mode, order=order, aux_stream=aux)
+        def time_bwd(aux, fuse_steps=False):
+            pl = tb.ChunkAttnBwdPlan(sched, qd, kd, vd, out_f, lse_f, dout, w.mask_mode, order=order, aux_stream=aux,
+                                     fuse_steps=fuse_steps)
             for _ in range(max(1, args.warmup)):
                 pl.run()
             torch.cuda.synchronize()
@@ -280,12 +281,18 @@ def main():
         bplan, one_ms = time_bwd(None)
         aux_plan, two_ms = time_bwd(torch.cuda.Stream())
         del aux_plan
+        try:                                       # all steps in one dq and one dk/dv launch
+            fs_plan, fs_ms = time_bwd(None, fuse_steps=True)
+            del fs_plan
+        except tb.TaspError:
+            fs_ms = None
         b_ms = min(one_ms, two_ms)
         bp = bplan.profile()
         b_flops = bplan.flops()                  # 2.5 x forward: five products
         backward = {
             "value": b_flops / (b_ms * 1e-3) / 1e12, "unit": "TFLOP/s", "ms_per_step": b_ms, "flops_per_call": b_flops,
             "ms_one_stream": one_ms, "ms_two_streams": two_ms,
+            "single_launch": None if fs_ms is None else {"ms_per_step": fs_ms, "value": b_flops / (fs_ms * 1e-3) / 1e12},
             "frac_of_bf16_mfma_peak": b_flops / (b_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             # executed matrix work: the dq kernel forms three products per (query, key) pair (1.5 x the
             # forward's flops), the dk/dv kernel four (2 x): both recompute the scores

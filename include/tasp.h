@@ -273,6 +273,9 @@ typedef struct tasp_attn_bwd_args {
                                    into hip_stream with events, so that each fills the idle compute units at
                                    the other's tail.  Results are identical.  The call must then not be
                                    recorded into a HIP graph. */
+  int32_t      fuse_steps;      /* 0: one dq and one dk/dv launch per step; 1: one of each for all steps (as
+                                   fuse_steps of tasp_chunk_attn: K, V resident; bf16 only; at most
+                                   TASP_MAX_FUSED_SEGMENTS segments per query block) */
 } tasp_attn_bwd_args;
 
 size_t tasp_chunk_attn_bwd_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_bwd_args* a);

@@ -60,7 +60,7 @@ class AttnBwdArgs(C.Structure):
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("S", C.c_int64),
         ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32), ("dtype", C.c_int32),
         ("mask_mode", C.c_int32), ("order", C.c_int32), ("softmax_scale", C.c_float), ("batch", C.c_int32),
-        ("aux_stream", C.c_void_p),
+        ("aux_stream", C.c_void_p), ("fuse_steps", C.c_int32),
     ]
 
 
@@ -262,7 +262,7 @@ class ChunkAttnBwdPlan:
     """Buffers of one tasp_chunk_attn_bwd shape (dq, dk, dv, workspace), so that repeated calls allocate nothing."""
 
     def __init__(self, schedule, q, k, v, out, lse, dout, mask_mode, order=ORDER_TASP, softmax_scale=0.0,
-                 aux_stream=None):
+                 aux_stream=None, fuse_steps=False):
         """aux_stream: a torch.cuda.Stream for the dk/dv kernels (None: everything on one stream)."""
         torch = _torch()
         fa = _args(q, k, v, mask_mode, order, True, softmax_scale)
@@ -278,6 +278,7 @@ class ChunkAttnBwdPlan:
         a.q, a.k, a.v, a.out, a.lse, a.dout = (t.data_ptr() for t in (q, k, v, out, lse, dout))
         a.S, a.Hq, a.Hkv, a.d, a.batch, a.dtype = fa.S, fa.Hq, fa.Hkv, fa.d, fa.batch, fa.dtype
         a.mask_mode, a.order, a.softmax_scale = mask_mode, order, softmax_scale
+        a.fuse_steps = int(bool(fuse_steps))
         self.dq, self.dk, self.dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
         a.dq, a.dk, a.dv = self.dq.data_ptr(), self.dk.data_ptr(), self.dv.data_ptr()
         nbytes = lib.tasp_chunk_attn_bwd_workspace_bytes(schedule.handle, C.byref(a))
@@ -306,10 +307,11 @@ class ChunkAttnBwdPlan:
 
 
 def tasp_chunk_attn_bwd(q, k, v, out, lse, dout, schedule, mask_mode, order=ORDER_TASP, softmax_scale=0.0,
-                        aux_stream=None):
+                        aux_stream=None, fuse_steps=False):
     """One rank's backward pass in the forward's arrival order.  out, lse: what tasp_chunk_attn returned
     for the same inputs.  Returns (dq like q, dk like k, dv like v); dk, dv are this rank's contribution."""
-    return ChunkAttnBwdPlan(schedule, q, k, v, out, lse, dout, mask_mode, order, softmax_scale, aux_stream).run()
+    return ChunkAttnBwdPlan(schedule, q, k, v, out, lse, dout, mask_mode, order, softmax_scale, aux_stream,
+                            fuse_steps).run()
 
 
 def tasp_step_attn(q, k, v, schedule, mask_mode, step, order=ORDER_TASP, softmax_scale=0.0):

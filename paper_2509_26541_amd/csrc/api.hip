@@ -101,6 +101,54 @@ int build_step(const tasp_schedule_t* s, const tasp_attn_args* a, int step, Attn
   return TASP_OK;
 }
 
+// Single-launch mode: the tasks of all steps joined per query block, in arrival order.  The segment
+// lists go to `dev_table` (kMaxTasks x 2 kMaxSegAll integers of device memory, written by small
+// kernels on `stream`); the descriptor points at them.
+int build_all_steps(const tasp_schedule_t* s, const tasp_attn_args* a, int32_t* dev_table, hipStream_t stream,
+                    AttnLaunch* all) {
+  std::vector<int32_t> table[tasp::kMaxTasks];
+  std::vector<tasp::QueryBlock> empty;
+  int64_t keys[tasp::kMaxTasks] = {0, 0};
+  for (int step = 0; step < s->n; ++step) {
+    AttnLaunch lp{};
+    empty.clear();
+    const int st = build_step(s, a, step, &lp, &empty);
+    if (st != TASP_OK) return st;
+    if (step == 0) {
+      // every query block sees its own diagonal at step 0, so step 0 defines the blocks
+      if (!empty.empty()) return TASP_EUNSUPPORTED_SHAPE;
+      *all = lp;
+      for (int t = 0; t < all->n_tasks; ++t) all->task[t].n_seg = 0;
+    }
+    for (int t = 0; t < lp.n_tasks; ++t) {
+      int dst = -1;
+      for (int u = 0; u < all->n_tasks; ++u)
+        if (all->task[u].q_row0 == lp.task[t].q_row0) dst = u;
+      if (dst < 0) return TASP_EUNSUPPORTED_SHAPE;
+      for (int i = 0; i < lp.task[t].n_seg; ++i) {
+        table[dst].push_back(lp.task[t].seg_start[i]);
+        table[dst].push_back(lp.task[t].seg_end[i]);
+        keys[dst] += lp.task[t].seg_end[i] - lp.task[t].seg_start[i];
+      }
+    }
+  }
+  for (int t = 0; t < all->n_tasks; ++t) {
+    const size_t n_seg = table[t].size() / 2;
+    if (n_seg > static_cast<size_t>(tasp::kMaxSegAll)) return TASP_EUNSUPPORTED_SHAPE;
+    all->task[t].n_seg = static_cast<int32_t>(n_seg);
+    all->seg_ext[t] = dev_table + static_cast<size_t>(t) * 2 * tasp::kMaxSegAll;
+    if (tasp::launch_write_i32(dev_table + static_cast<size_t>(t) * 2 * tasp::kMaxSegAll, table[t].data(),
+                               static_cast<int64_t>(table[t].size()), stream) != hipSuccess)
+      return TASP_EHIP;
+  }
+  // the block with more keys goes first so that its workgroups are not the tail of the launch
+  if (all->n_tasks == 2 && keys[1] > keys[0]) {
+    std::swap(all->task[0], all->task[1]);
+    std::swap(all->seg_ext[0], all->seg_ext[1]);
+  }
+  return TASP_OK;
+}
+
 // Optional per-launch timing with HIP events on the caller's stream (tasp_chunk_attn_profile).
 struct Profiler {
   enum Kind { kAttn = 0, kMerge = 1, kOther = 2 };
@@ -145,6 +193,7 @@ tasp_attn_args as_forward(const tasp_attn_bwd_args* b) {
   a.S = b->S; a.Hq = b->Hq; a.Hkv = b->Hkv; a.d = b->d;
   a.dtype = b->dtype; a.mask_mode = b->mask_mode; a.order = b->order;
   a.fuse_merge = 1; a.softmax_scale = b->softmax_scale; a.batch = b->batch;
+  a.fuse_steps = b->fuse_steps;
   return a;
 }
 
@@ -256,47 +305,11 @@ static int run_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, voi
   try {
     std::vector<tasp::QueryBlock> empty;
     if (a->fuse_steps) {
-      // One launch over the segments of every step, in arrival order, per query block.
       AttnLaunch all{};
-      std::vector<int32_t> table[tasp::kMaxTasks];
-      int64_t keys[tasp::kMaxTasks] = {0, 0};
-      for (int step = 0; step < s->n; ++step) {
-        AttnLaunch lp{};
-        empty.clear();
-        st = build_step(s, a, step, &lp, &empty);
-        if (st != TASP_OK) return st;
-        if (step == 0) {
-          // every query block sees its own diagonal at step 0, so step 0 defines the blocks
-          if (!empty.empty()) return TASP_EUNSUPPORTED_SHAPE;
-          all = lp;
-          for (int t = 0; t < all.n_tasks; ++t) all.task[t].n_seg = 0;
-        }
-        for (int t = 0; t < lp.n_tasks; ++t) {
-          int dst = -1;
-          for (int u = 0; u < all.n_tasks; ++u)
-            if (all.task[u].q_row0 == lp.task[t].q_row0) dst = u;
-          if (dst < 0) return TASP_EUNSUPPORTED_SHAPE;
-          for (int i = 0; i < lp.task[t].n_seg; ++i) {
-            table[dst].push_back(lp.task[t].seg_start[i]);
-            table[dst].push_back(lp.task[t].seg_end[i]);
-            keys[dst] += lp.task[t].seg_end[i] - lp.task[t].seg_start[i];
-          }
-        }
-      }
-      int32_t* dev_table = reinterpret_cast<int32_t*>(ws);
-      for (int t = 0; t < all.n_tasks; ++t) {
-        const size_t n_seg = table[t].size() / 2;
-        if (n_seg > static_cast<size_t>(tasp::kMaxSegAll)) return TASP_EUNSUPPORTED_SHAPE;
-        all.task[t].n_seg = static_cast<int32_t>(n_seg);
-        all.seg_ext[t] = dev_table + static_cast<size_t>(t) * 2 * tasp::kMaxSegAll;
+      {
         Scope sc(prof, Profiler::kOther);
-        if (tasp::launch_write_i32(dev_table + static_cast<size_t>(t) * 2 * tasp::kMaxSegAll, table[t].data(),
-                                   static_cast<int64_t>(table[t].size()), stream) != hipSuccess)
-          return TASP_EHIP;
-      }
-      if (all.n_tasks == 2 && keys[1] > keys[0]) {
-        std::swap(all.task[0], all.task[1]);
-        std::swap(all.seg_ext[0], all.seg_ext[1]);
+        st = build_all_steps(s, a, reinterpret_cast<int32_t*>(ws), stream, &all);
+        if (st != TASP_OK) return st;
       }
       all.o_dst = o_run; all.lse_dst = a->lse; all.merge = 0;
       {
@@ -358,7 +371,8 @@ size_t tasp_chunk_attn_bwd_workspace_bytes(const tasp_schedule_t* s, const tasp_
   const size_t B = static_cast<size_t>(b->batch == 0 ? 1 : b->batch);
   const size_t delta_bytes = align_up(B * L * b->Hq * sizeof(float));
   if (b->dtype == TASP_DTYPE_FP32) return delta_bytes;                   // dq itself is the fp32 accumulator
-  return align_up(B * L * b->Hq * b->d * sizeof(float)) + delta_bytes;   // fp32 dq, delta
+  const size_t table = b->fuse_steps ? align_up(kFusedTableBytes) : 0;    // segment lists of the single launch
+  return align_up(B * L * b->Hq * b->d * sizeof(float)) + delta_bytes + table;   // fp32 dq, delta
 }
 
 double tasp_chunk_attn_bwd_flops(const tasp_schedule_t* s, const tasp_attn_bwd_args* b) {
@@ -406,43 +420,41 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
           tasp::note_hip(hipStreamWaitEvent(kv_stream, fork.e, 0)) != hipSuccess)
         return TASP_EHIP;
     }
-    std::vector<tasp::QueryBlock> empty;
-    std::vector<tasp::Segment> ranges;
-    for (int step = 0; step < s->n; ++step) {
-      AttnLaunch lp{};
-      empty.clear();
-      st = build_step(s, &a, step, &lp, &empty);
-      if (st != TASP_OK) return st;
+    // One unit = one dq launch and one dk/dv launch: a step, or all steps at once.
+    auto launch_unit = [&](const AttnLaunch& lp, std::vector<tasp::Segment>& ranges) -> int {
       tasp::BwdLaunch bp{};
       bp.q = b->q; bp.k = b->k; bp.v = b->v; bp.dout = b->dout; bp.lse = b->lse; bp.delta = delta;
       bp.dq_acc = dq_acc; bp.dk = b->dk; bp.dv = b->dv;
       bp.Hq = lp.Hq; bp.Hkv = lp.Hkv; bp.causal = lp.causal; bp.scale = lp.scale; bp.batch = lp.batch;
       bp.q_bstride = lp.q_bstride; bp.kv_bstride = lp.kv_bstride; bp.lse_bstride = lp.lse_bstride;
       bp.n_tasks = lp.n_tasks;
-      for (int t = 0; t < lp.n_tasks; ++t) bp.task[t] = lp.task[t];
+      for (int t = 0; t < lp.n_tasks; ++t) { bp.task[t] = lp.task[t]; bp.seg_ext[t] = lp.seg_ext[t]; }
       bp.n_blk = tasp::n_query_blocks(b->mask_mode);
       for (int qb = 0; qb < bp.n_blk; ++qb) {
         tasp::QueryBlock blk;
-        st = tasp::query_block(*s, b->S, b->mask_mode, qb, &blk);
-        if (st != TASP_OK) return st;
+        const int st2 = tasp::query_block(*s, b->S, b->mask_mode, qb, &blk);
+        if (st2 != TASP_OK) return st2;
         bp.blk[qb] = {static_cast<int32_t>(blk.local_row0), static_cast<int32_t>(blk.rows), static_cast<int32_t>(blk.pos0)};
       }
-      st = tasp::step_key_ranges(*s, b->S, b->mask_mode, b->order, step, &ranges);
-      if (st != TASP_OK) return st;
-      if (ranges.size() > static_cast<size_t>(tasp::kMaxSeg)) return TASP_EUNSUPPORTED_SHAPE;
       // The dk/dv kernel treats every key on its own, so the order of the ranges is free: by
       // position, which under the causal mask is by falling work (early keys are seen by more
-      // queries), so that the workgroups with the most work start first.
+      // queries), so that the workgroups with the most work start first.  Neighbours are joined.
       std::sort(ranges.begin(), ranges.end(),
                 [](const tasp::Segment& x, const tasp::Segment& y) { return x.start < y.start; });
-      bp.n_rng = static_cast<int32_t>(ranges.size());
-      int64_t vpos = 0;
+      size_t n = 0;
       for (size_t i = 0; i < ranges.size(); ++i) {
+        if (n > 0 && ranges[n - 1].end == ranges[i].start) ranges[n - 1].end = ranges[i].end;
+        else ranges[n++] = ranges[i];
+      }
+      if (n > static_cast<size_t>(tasp::kMaxSeg)) return TASP_EUNSUPPORTED_SHAPE;
+      bp.n_rng = static_cast<int32_t>(n);
+      int64_t vpos = 0;
+      for (size_t i = 0; i < n; ++i) {
         bp.rng_start[i] = static_cast<int32_t>(ranges[i].start);
         bp.rng_vbeg[i] = static_cast<int32_t>(vpos);
         vpos += ranges[i].end - ranges[i].start;
       }
-      bp.rng_vbeg[ranges.size()] = static_cast<int32_t>(vpos);
+      bp.rng_vbeg[n] = static_cast<int32_t>(vpos);
       {
         Scope sc(prof, BwdSpans::kDq);
         if ((bf16 ? tasp::launch_bwd_dq_bf16(bp, b->d, stream) : tasp::launch_bwd_dq_fp32(bp, b->d, stream)) != hipSuccess)
@@ -454,6 +466,36 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
             hipSuccess)
           return TASP_EHIP;
       }
+      return TASP_OK;
+    };
+    std::vector<tasp::QueryBlock> empty;
+    std::vector<tasp::Segment> ranges, step_ranges;
+    if (b->fuse_steps) {
+      AttnLaunch all{};
+      int32_t* dev_table = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes) +
+                                                      align_up(sh.lse_bytes));
+      {
+        Scope sc(prof, BwdSpans::kOther);
+        st = build_all_steps(s, &a, dev_table, stream, &all);
+        if (st != TASP_OK) return st;
+      }
+      for (int step = 0; step < s->n; ++step) {
+        st = tasp::step_key_ranges(*s, b->S, b->mask_mode, b->order, step, &step_ranges);
+        if (st != TASP_OK) return st;
+        ranges.insert(ranges.end(), step_ranges.begin(), step_ranges.end());
+      }
+      st = launch_unit(all, ranges);
+      if (st != TASP_OK) return st;
+    }
+    for (int step = 0; step < s->n && !b->fuse_steps; ++step) {
+      AttnLaunch lp{};
+      empty.clear();
+      st = build_step(s, &a, step, &lp, &empty);
+      if (st != TASP_OK) return st;
+      st = tasp::step_key_ranges(*s, b->S, b->mask_mode, b->order, step, &ranges);
+      if (st != TASP_OK) return st;
+      st = launch_unit(lp, ranges);
+      if (st != TASP_OK) return st;
     }
     if (kv_stream != stream) {
       if (tasp::note_hip(hipEventRecord(join.e, kv_stream)) != hipSuccess ||

@@ -206,14 +206,17 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
   }
   // ---- effective segment list of this query tile: drop what the causal mask hides from every
   // row, split the rest into a part every row sees and a part that straddles the diagonal.
-  // In single-launch mode the list comes from device memory; it is staged in the (still unused)
-  // tile ring first.
+  // The list - from the descriptor, or in single-launch mode from device memory - is staged in
+  // the (still unused) tile ring first.
   const int32_t* seg_ext = p.seg_ext[tsk];
-  const int* seg_raw = reinterpret_cast<const int*>(smem);
+  int* seg_raw = reinterpret_cast<int*>(smem);
   if (seg_ext != nullptr) {
-    for (int i = tid; i < 2 * T.n_seg; i += C::NTHREADS) reinterpret_cast<int*>(smem)[i] = seg_ext[i];
-    __syncthreads();
+    for (int i = tid; i < 2 * T.n_seg; i += C::NTHREADS) seg_raw[i] = seg_ext[i];
+  } else if (tid < T.n_seg) {
+    seg_raw[2 * tid] = T.seg_start[tid];
+    seg_raw[2 * tid + 1] = T.seg_end[tid];
   }
+  __syncthreads();
   // The first wavefront builds the list, 64 segments per round: every lane classifies one segment
   // on its own; only the positions in the list and in the virtual concatenation are running sums
   // (wavefront scans).  The tile ranges of the diagonal parts go to m_lo / m_hi first and are
@@ -224,8 +227,8 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
       const int s = s0 + lane;
       int a = 0, len_f = 0, len_d = 0, start_d = 0;
       if (s < T.n_seg) {
-        a = seg_ext ? seg_raw[2 * s] : T.seg_start[s];
-        const int b = seg_ext ? seg_raw[2 * s + 1] : T.seg_end[s];
+        a = seg_raw[2 * s];
+        const int b = seg_raw[2 * s + 1];
         if (!p.causal) {
           len_f = b - a;
         } else if (a <= qb) {

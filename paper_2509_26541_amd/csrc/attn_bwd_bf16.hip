@@ -115,8 +115,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const BwdLaunch p) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE_BYTES];   // stage: K tile, V tile
   __shared__ __attribute__((aligned(16))) int s_tok[2][BT];   // global position of every key row (INT_MAX: none)
   __shared__ __attribute__((aligned(16))) int s_msk[2][4];    // per loading wavefront: the tile holds a key some query row of the workgroup must not see
-  __shared__ int e_vbeg[kMaxSeg + 1];   // effective segments: start in the virtual concatenation
-  __shared__ int e_goff[kMaxSeg];       //   global position minus virtual position
+  __shared__ int e_vbeg[kMaxSegAll + 1];   // effective segments: start in the virtual concatenation
+  __shared__ int e_goff[kMaxSegAll];       //   global position minus virtual position
   __shared__ int e_n;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, lq = lane & 31;
@@ -141,17 +141,43 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const BwdLaunch p) {
   const int q_last = T.q_pos0 + q_tile_row0 + q_rows_here - 1;
   const int q_first = p.causal ? T.q_pos0 + q_tile_row0 : INT_MAX - 1;   // a key at or before it is seen by every row
 
-  // ---- effective segments of this query tile: drop what the causal mask hides from every row
-  if (tid == 0) {
-    int n = 0, vpos = 0;
-    for (int s = 0; s < T.n_seg; ++s) {
-      const int a = T.seg_start[s];
-      const int b = p.causal ? min(T.seg_end[s], q_last + 1) : T.seg_end[s];
-      if (a >= b) continue;
-      e_vbeg[n] = vpos; e_goff[n] = a - vpos; vpos += b - a; ++n;
+  // ---- effective segments of this query tile: drop what the causal mask hides from every row.
+  // The list - from the descriptor, or with all steps in one launch from device memory - is
+  // staged in the (still unused) tile stages first.  The first wavefront builds the list, 64 segments per round: every
+  // lane clips one segment, the positions are running sums (wavefront scans).
+  const int32_t* seg_ext = p.seg_ext[tsk];
+  int* seg_raw = reinterpret_cast<int*>(smem);
+  if (seg_ext != nullptr) {
+    for (int i = tid; i < 2 * T.n_seg; i += NTHREADS) seg_raw[i] = seg_ext[i];
+  } else if (tid < T.n_seg) {
+    seg_raw[2 * tid] = T.seg_start[tid];
+    seg_raw[2 * tid + 1] = T.seg_end[tid];
+  }
+  __syncthreads();
+  if (wave == 0) {
+    int n_base = 0, v_base = 0;
+    for (int s0 = 0; s0 < T.n_seg; s0 += 64) {
+      const int s = s0 + lane;
+      int a = 0, len = 0;
+      if (s < T.n_seg) {
+        a = seg_raw[2 * s];
+        const int e = seg_raw[2 * s + 1];
+        len = max(0, (p.causal ? min(e, q_last + 1) : e) - a);
+      }
+      const int cnt = len > 0 ? 1 : 0;
+      int sc = cnt, sl = len;                      // inclusive scans
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int t1 = __shfl_up(sc, o), t2 = __shfl_up(sl, o);
+        if (lane >= o) { sc += t1; sl += t2; }
+      }
+      if (len > 0) {
+        const int idx = n_base + sc - 1, vpos = v_base + sl - len;
+        e_vbeg[idx] = vpos; e_goff[idx] = a - vpos;
+      }
+      n_base += __shfl(sc, 63); v_base += __shfl(sl, 63);
     }
-    e_vbeg[n] = vpos;
-    e_n = n;
+    if (lane == 0) { e_vbeg[n_base] = v_base; e_n = n_base; }
   }
   __syncthreads();
   const int n_eff = e_n;

@@ -65,6 +65,7 @@ struct BwdLaunch {
   int64_t q_bstride, kv_bstride, lse_bstride;   // elements between sequences
   int32_t n_tasks;
   AttnTask task[kMaxTasks];
+  const int32_t* seg_ext[kMaxTasks];   // as in AttnLaunch (all steps in one launch)
   int32_t n_blk;
   BwdBlock blk[kMaxTasks];
   int32_t n_rng;

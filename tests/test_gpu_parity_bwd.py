@@ -98,6 +98,19 @@ def test_small_forward_then_backward(tb, case):
     close(w.name + " dv", dv, rv)
 
 
+@pytest.mark.parametrize("case", CHAIN, ids=[c[0] for c in CHAIN])
+def test_small_single_launch(tb, case):
+    """fuse_steps in both passes: one forward launch, then one dq and one dk/dv launch for all steps."""
+    w = small_workload(case)
+    q, k, v = wl.make_qkv(w)
+    do = wl.make_dout(w)
+    dq, dk, dv = forward_backward(tb, w, q, k, v, do, fuse_steps=True)
+    rq, rk, rv = oracle_grads(w, q, k, v, do)
+    close(w.name + " dq", dq, rq)
+    close(w.name + " dk", dk, rk)
+    close(w.name + " dv", dv, rv)
+
+
 def test_ring_order_and_multinode_schedule(tb):
     """The gradient does not depend on the order in which the sub-chunks arrive."""
     w = small_workload(SMALL[1])
@@ -172,12 +185,13 @@ def test_full_size_128k_sparse_upstream_gradient(tb):
     keep = wl.sample_rows(w, 24)
     sparse = torch.zeros_like(do)
     sparse[keep] = do[keep]
-    dq, dk, dv = forward_backward(tb, w, q, k, v, sparse)
     rq, rk, rv = oracle_grads(w, q, k, v, do, rows=keep)
-    close("dq kept rows", dq[keep], rq)
     rest = np.setdiff1d(np.arange(w.L), keep)
-    assert float(dq[rest].float().abs().max()) == 0.0
-    close("dk", dk, rk); close("dv", dv, rv)
+    for fuse_steps in (False, True):
+        dq, dk, dv = forward_backward(tb, w, q, k, v, sparse, fuse_steps=fuse_steps)
+        close("dq kept rows", dq[keep], rq)
+        assert float(dq[rest].float().abs().max()) == 0.0
+        close("dk", dk, rk); close("dv", dv, rv)
 
 
 def test_full_size_128k_dense_upstream_gradient(tb):

@@ -36,6 +36,7 @@ def test_attention_kernels_found(attn_asm):
         assert sum(o.startswith("v_mfma_f32_32x32x16_bf16") for o in ops) >= 32
         assert any(o == "ds_read_b64_tr_b16" for o in ops) and any(o == "ds_read_b128" for o in ops)
         assert any(o == "global_load_lds_dwordx4" for o in ops)
+        assert not any(o.startswith("flat_") for o in ops), k
 
 
 def test_no_register_of_a_pending_lds_read_is_touched(attn_asm):
