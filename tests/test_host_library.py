@@ -292,4 +292,9 @@ def test_backward_argument_checks_and_sizes():
     assert bwd.attention_bwd_flops(8, 3, 4096, sch.ZIGZAG_CAUSAL, 8, 128) == 2.5 * fwd
     b.batch = 4
     assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == pad(4 * L * 8 * 128 * 4) + pad(4 * L * 8 * 4)
+    b.fuse_steps = 1                                    # plus the segment table of the single launch
+    assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == pad(4 * L * 8 * 128 * 4) + pad(4 * L * 8 * 4) + 2 * 2 * 1024 * 4
+    b.fuse_steps = 3
+    assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EINVAL
+    b.fuse_steps = 0
     assert tb.lib.tasp_chunk_attn_bwd_flops(s.handle, C.byref(b)) == 4 * 2.5 * fwd
