@@ -398,3 +398,29 @@ def test_long_row_with_one_dominant_early_key(tb):
         err = max_abs(lse.cpu().numpy()[rows], ref_l)
         assert err <= 1e-4, (kw, err)
         assert max_abs(out.float().cpu().numpy()[rows], ref_o) <= 2e-2
+
+
+@pytest.mark.parametrize("mode", ["merge_kernel", "fused_merge", "single_launch"])
+def test_forward_call_recorded_into_a_graph(tb, mode):
+    """The forward call enqueues kernels only (no memset, no copy from host memory), so it can be
+    recorded into a HIP graph: three replays, with eager work and synchronisation between them and
+    fresh inputs each time, against the eager result."""
+    w = wl.Workload("graph", 8, 5, 8 * 2 * 160, 4, 2, 128, "bf16", wl.ZIGZAG_CAUSAL, seed=wl.BASE_SEED + 31)
+    q, k, v = (x.cuda() for x in wl.make_qkv(w))
+    s = tb.tasp_schedule(w.n_ranks, w.rank)
+    kw = dict(fuse_merge=mode != "merge_kernel", fuse_steps=mode == "single_launch")
+    plan = tb.ChunkAttnPlan(s, q, k, v, w.mask_mode, **kw)
+    plan.run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.run()
+    for rep in range(3):
+        q.copy_(torch.roll(q, shifts=rep + 1, dims=0))          # eager work between the replays: new inputs
+        eager_out, eager_lse = tb.tasp_chunk_attn(q, k, v, s, w.mask_mode, **kw)
+        torch.cuda.synchronize()
+        plan.out.zero_()
+        plan.lse.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(plan.out, eager_out) and torch.equal(plan.lse, eager_lse), (mode, rep)

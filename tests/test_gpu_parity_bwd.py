@@ -242,3 +242,29 @@ def test_fp32_all_outputs(tb, case):
         got = got.cpu().numpy().astype(np.float64)
         err = float(np.abs(got - ref).max())
         assert err <= 1e-4 * max(1.0, float(np.abs(ref).max())), (w.name, nm, err)
+
+
+@pytest.mark.parametrize("fuse_steps", [False, True])
+def test_backward_call_recorded_into_a_graph(tb, fuse_steps):
+    """On one stream the backward call, too, enqueues kernels only: three graph replays with eager
+    work between them against the eager result."""
+    w = small_workload(SMALL[1])
+    q, k, v = (x.cuda() for x in wl.make_qkv(w))
+    do = wl.make_dout(w).cuda()
+    s = tb.tasp_schedule(w.n_ranks, w.rank)
+    out, lse = tb.tasp_chunk_attn(q, k, v, s, w.mask_mode, fuse_merge=True)
+    plan = tb.ChunkAttnBwdPlan(s, q, k, v, out, lse, do, w.mask_mode, fuse_steps=fuse_steps)
+    plan.run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.run()
+    for rep in range(3):
+        do.copy_(torch.roll(do, shifts=rep + 1, dims=0))
+        eager = tb.tasp_chunk_attn_bwd(q, k, v, out, lse, do, s, w.mask_mode, fuse_steps=fuse_steps)
+        torch.cuda.synchronize()
+        for t in (plan.dq, plan.dk, plan.dv):
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip((plan.dq, plan.dk, plan.dv), eager)), rep
