@@ -259,6 +259,10 @@ def test_batched_call(tb, case, fuse):
     out, lse = tb.tasp_chunk_attn(q, k, v, s, mode, fuse_merge=fuse)
     torch.cuda.synchronize()
     assert tuple(out.shape) == tuple(q.shape) and tuple(lse.shape) == tuple(q.shape[:-1])
+    if dtype == "bf16":                      # all steps in one launch, batched: same bar (checked below via out1/lse1)
+        out1, lse1 = tb.tasp_chunk_attn(q, k, v, s, mode, fuse_steps=True)
+        torch.cuda.synchronize()
+        assert float((out1.float() - out.float()).abs().max()) <= 2e-2 and float((lse1 - lse).abs().max()) <= 1e-3
     rows = list(range(ws[0].L))
     for b in range(B):
         ref_o, ref_l = oracle_rows(ws[b], *qkv[b], rows)
@@ -292,11 +296,12 @@ def test_small_multinode_schedule_all_rows(tb, case, fuse):
     q, k, v = wl.make_qkv(w)
     s = tb.tasp_schedule_multinode(m, u, rank)
     assert s.n_rings == m
-    out, lse = tb.tasp_chunk_attn(q.cuda(), k.cuda(), v.cuda(), s, mode, fuse_merge=fuse)
-    torch.cuda.synchronize()
     rows = list(range(w.L))
     ref_o, ref_l = oracle_rows(w, q, k, v, rows)
-    check(w, out.float().cpu().numpy(), lse.cpu().numpy(), ref_o, ref_l, rows)
+    for fuse_steps in (False, True):
+        out, lse = tb.tasp_chunk_attn(q.cuda(), k.cuda(), v.cuda(), s, mode, fuse_merge=fuse, fuse_steps=fuse_steps)
+        torch.cuda.synchronize()
+        check(w, out.float().cpu().numpy(), lse.cpu().numpy(), ref_o, ref_l, rows)
     # the partial of one step against the oracle's partial over that step's tokens
     rings = sch.multinode_rings(m, u)
     step = 1 + (rank % (m * u - 1))

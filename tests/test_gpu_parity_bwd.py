@@ -133,9 +133,15 @@ def test_batched_equals_separate_calls(tb):
     out, lse = tb.tasp_chunk_attn(q, k, v, s, wl.ZIGZAG_CAUSAL, fuse_merge=True)
     dq, dk, dv = tb.tasp_chunk_attn_bwd(q, k, v, out, lse, do, s, wl.ZIGZAG_CAUSAL)
     torch.cuda.synchronize()
+    # the same batch with all steps in one launch and the dk/dv kernel on a second stream
+    dq1, dk1, dv1 = tb.tasp_chunk_attn_bwd(q, k, v, out, lse, do, s, wl.ZIGZAG_CAUSAL, fuse_steps=True,
+                                           aux_stream=torch.cuda.Stream())
+    torch.cuda.synchronize()
     for b in range(B):
         rq, rk, rv = oracle_grads(ws[b], *data[b])
         close("b%d dq" % b, dq[b], rq); close("b%d dk" % b, dk[b], rk); close("b%d dv" % b, dv[b], rv)
+        close("b%d dq one launch" % b, dq1[b], rq); close("b%d dk one launch" % b, dk1[b], rk)
+        close("b%d dv one launch" % b, dv1[b], rv)
         one = tb.tasp_chunk_attn_bwd(q[b].contiguous(), k[b].contiguous(), v[b].contiguous(), out[b].contiguous(),
                                      lse[b].contiguous(), do[b].contiguous(), s, wl.ZIGZAG_CAUSAL)
         torch.cuda.synchronize()
