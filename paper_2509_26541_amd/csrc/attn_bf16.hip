@@ -691,20 +691,27 @@ __global__ __launch_bounds__(64 * (8 / NS), 8 / NS / 4) void attn_bf16_kernel(co
           lse_new = mxl + __logf(ea + eb);
         }
       }
+      // All pieces of the old row are requested before the first one is written back: loads and
+      // stores through the same pointer are otherwise kept in program order, one round trip each.
+      f32x4 old[DB][4];
+      if (p.merge) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) old[db][i4] = *reinterpret_cast<const f32x4*>(od + 32 * db + 8 * i4);
+      }
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
-          f32x4* dst = reinterpret_cast<f32x4*>(od + 32 * db + 8 * i4);
           f32x4 val;
 #pragma unroll
           for (int e = 0; e < 4; ++e) val[e] = o[s][db][4 * i4 + e] * wb;
           if (p.merge) {
-            const f32x4 old = *dst;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) val[e] = __builtin_fmaf(wa, old[e], val[e]);
+            for (int e = 0; e < 4; ++e) val[e] = __builtin_fmaf(wa, old[db][i4][e], val[e]);
           }
-          *dst = val;
+          *reinterpret_cast<f32x4*>(od + 32 * db + 8 * i4) = val;
         }
       if (h == 0) *ld = lse_new;
     }
