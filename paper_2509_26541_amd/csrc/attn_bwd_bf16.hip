@@ -109,7 +109,7 @@ struct ReadAddr {
 // dq kernel
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256, 2) void bwd_dq_kernel(const BwdLaunch p) {
+__global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdLaunch p) {
   using C = BCfg<D, 4>;
   constexpr int KS = D / 16, DB = D / 32, BS = C::BS, NTHREADS = C::NTHREADS;
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE_BYTES];   // stage: K tile, V tile

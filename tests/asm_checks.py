@@ -97,3 +97,26 @@ def spill_report(asm):
     for m in re.finditer(r"\.name:\s+(\S+)\n(?:.*\n)*?\s+\.private_segment_fixed_size:\s+(\d+)\n(?:.*\n)*?\s+\.vgpr_spill_count:\s+(\d+)", asm):
         out.append((m.group(1), int(m.group(3)), int(m.group(2))))
     return out
+
+
+def scratch_in_loops(asm, kernel_substring):
+    """(kernel, block label) of every basic block that the compiler marks as part of a loop and that
+    holds a scratch (spill) instruction, for kernels whose symbol contains `kernel_substring`."""
+    out, name, label, in_loop = [], None, None, False
+    for line in asm.split("\n"):
+        m = re.match(r"^(_Z\w+):", line)
+        if m:
+            name, label, in_loop = (m.group(1) if kernel_substring in m.group(1) else None), None, False
+            continue
+        if name is None:
+            continue
+        if line.startswith(".Lfunc_end"):
+            name = None
+            continue
+        m = re.match(r"^(\.LBB\d+_\d+):(.*)", line)
+        if m:
+            label, in_loop = m.group(1), "Loop" in m.group(2)
+            continue
+        if in_loop and line.strip().startswith("scratch_"):
+            out.append((name, label))
+    return out

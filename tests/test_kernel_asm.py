@@ -30,7 +30,7 @@ def test_checker_flags_a_planted_violation():
 def test_attention_kernels_found(attn_asm):
     ks = asm_checks.kernels(attn_asm)
     names = [k for k in ks if "attn_bf16_kernel" in k]
-    assert len(names) == 2, names                      # d = 128 and d = 64
+    assert len(names) == 3, names                      # d = 128, and d = 64 with 8 and 12 wavefronts
     for k in names:
         ops = [s.split()[0] for _, s in ks[k]]
         assert sum(o.startswith("v_mfma_f32_32x32x16_bf16") for o in ops) >= 32
@@ -48,11 +48,17 @@ def test_no_register_of_a_pending_lds_read_is_touched(attn_asm):
             name, len(bad), bad[:3])
 
 
-def test_no_spills(attn_asm):
+def test_no_spills_in_the_loop(attn_asm):
+    """No spills at all where two wavefronts share a SIMD; the twelve-wavefront variant (168
+    registers) may park a few values of the prologue for the epilogue, but nothing inside a loop."""
     rep = [r for r in asm_checks.spill_report(attn_asm) if "attn_bf16_kernel" in r[0]]
-    assert len(rep) == 2
+    assert len(rep) == 3
     for name, spills, scratch in rep:
-        assert spills == 0 and scratch == 0, (name, spills, scratch)
+        if "ELi12EEE" in name:
+            assert spills <= 6, (name, spills)
+        else:
+            assert spills == 0 and scratch == 0, (name, spills, scratch)
+    assert asm_checks.scratch_in_loops(attn_asm, "attn_bf16_kernel") == []
 
 
 # ---------------------------------------------------------------- backward kernels (compiler-scheduled)
