@@ -36,13 +36,15 @@ __device__ __forceinline__ void static_for(F&& f) {
 // The compiler does not see it as a memory operation: the caller waits (s_waitcnt vmcnt) and
 // publishes the data with a barrier before anybody reads it.  FENCE adds a compiler-level memory
 // clobber for callers whose LDS reads are ordinary loads the compiler could otherwise move across.
+// m0 is written here without being declared: the compiler reserves it (it never keeps a value
+// there, and names it only immediately before an instruction that reads it).
 template <bool FENCE>
 __device__ inline void global_to_lds_16(const unsigned char* base, unsigned off, unsigned char* lds_base) {
   const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)lds_base));
   if constexpr (FENCE)
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "m0", "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory");
   else
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base));
 }
 
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); this maps the hardware
