@@ -56,6 +56,8 @@ SMALL = [
     ("bf16_zz_n8", 1, 8, 3, 4096, 8, 2, 128),
     ("bf16_zz_n8_ragged", 1, 8, 6, 8 * 2 * 200, 4, 2, 128),     # H = 200: ragged query and key tiles
     ("bf16_zz_n8_tiny", 1, 8, 0, 112, 2, 1, 128),               # sub-chunks of 1 token
+    ("bf16_zz_n8_one_row", 1, 8, 5, 16, 2, 2, 128),             # the smallest sequence: one row per half-chunk, most sub-chunks empty
+    ("bf16_full_n4_one_row", 2, 4, 3, 4, 2, 1, 64),             # L = 1
     ("bf16_full_n8", 2, 8, 0, 8 * 331, 4, 4, 128),              # L = 331, pieces of 47/48
     ("bf16_full_n4", 2, 4, 2, 4 * 512, 4, 1, 128),
     ("bf16_zz_n16", 3, 16, 5, 16 * 2 * 96, 8, 1, 128),

@@ -44,6 +44,8 @@ SMALL = [
     ("zz_n8", 8, 3, 4096, 8, 2, 128, wl.ZIGZAG_CAUSAL, 1),
     ("zz_n8_ragged", 8, 6, 8 * 2 * 100, 4, 2, 128, wl.ZIGZAG_CAUSAL, 1),      # H = 100: ragged query and key tiles
     ("zz_n8_tiny", 8, 0, 112, 2, 1, 128, wl.ZIGZAG_CAUSAL, 1),               # sub-chunks of 1 token
+    ("zz_n8_one_row", 8, 5, 16, 2, 2, 128, wl.ZIGZAG_CAUSAL, 1),             # one row per half-chunk, most sub-chunks empty
+    ("full_n4_one_row", 4, 3, 4, 2, 1, 64, wl.FULL, 1),                      # L = 1
     ("full_n8", 8, 0, 8 * 331, 4, 4, 128, wl.FULL, 2),                       # L = 331, k scaled by 2
     ("full_n4_gqa4", 4, 2, 4 * 300, 4, 1, 128, wl.FULL, 2),
     ("zz_n16", 16, 5, 16 * 2 * 96, 8, 1, 128, wl.ZIGZAG_CAUSAL, 3),
