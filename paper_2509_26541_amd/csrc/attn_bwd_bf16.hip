@@ -485,6 +485,24 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
     }
   }
 
+  constexpr int NFB = 2 * KS + 4 * DB, NFT = 2 * NFB, PD = 2;
+  bf16x8 ring[PD];   // A-operand fragments in flight (slot = fragment % PD); used without VLDS only
+  auto issue = [&](auto ff, const unsigned char* qt_, const unsigned char* ot_) __attribute__((always_inline)) {
+    constexpr int F = decltype(ff)::value, qb = F / NFB, f = F % NFB, slot = F % PD;
+    if constexpr (f < KS) {
+      ring[slot] = lds_row8(qt_ + ra.row[f] + qb * 32 * D * 2);
+    } else if constexpr (f < KS + 2 * DB) {
+      constexpr int j = (f - KS) / DB, db = (f - KS) % DB, grp = (2 * qb + j) * 16 * D * 2;
+      ring[slot] = lds_tr8(ot_ + ra.tr[db][0] + grp, ot_ + ra.tr[db][1] + grp);
+    } else if constexpr (f < 2 * KS + 2 * DB) {
+      constexpr int ks = f - KS - 2 * DB;
+      ring[slot] = lds_row8(ot_ + ra.row[ks] + qb * 32 * D * 2);
+    } else {
+      constexpr int j = (f - 2 * KS - 2 * DB) / DB, db = (f - 2 * KS - 2 * DB) % DB, grp = (2 * qb + j) * 16 * D * 2;
+      ring[slot] = lds_tr8(qt_ + ra.tr[db][0] + grp, qt_ + ra.tr[db][1] + grp);
+    }
+  };
+
   It cur = settle(It{0, 0, first_tile(0)});
   if (cur.hh < G) fetch(cur, 0);
   int stage = 0;
@@ -497,83 +515,161 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
     const unsigned char* ot_ = qt_ + C::TILE_BYTES;
     const int pos0 = p.causal ? p.blk[cur.blk].pos0 + cur.qt * BT : 0;
     const bool need_mask = tmax > pos0;
+    if constexpr (VLDS) {
+      // At D = 128 the registers are too few for a fragment ring on top of everything else (the
+      // streamed form below spills inside the loop and measures 2 % slower), so the compiler orders
+      // the reads inside each phase.
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      // Five phases in a fixed order (the compiler may not mix them: that would keep S, dP, p and
-      // ds alive at once, more than the registers hold):  S -> p (in place) -> dv -> dP -> ds (in
-      // place) -> dk.  The other wavefront of the SIMD fills the matrix pipe meanwhile.
-      f32x16 S;
+      for (int qb = 0; qb < 2; ++qb) {
+        // Five phases in a fixed order (the compiler may not mix them: that would keep S, dP, p and
+        // ds alive at once, more than the registers hold):  S -> p (in place) -> dv -> dP -> ds (in
+        // place) -> dk.  The other wavefront of the SIMD fills the matrix pipe meanwhile.
+        f32x16 S;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) S[i] = 0.f;
+        for (int i = 0; i < 16; ++i) S[i] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) S = mfma(lds_row8(qt_ + ra.row[ks] + qb * 32 * D * 2), kf[ks], S);
-      __builtin_amdgcn_sched_barrier(0);
-      // p for the 32 queries of this block (register 4 i4 + e: query 8 i4 + 4 h + e)
+        for (int ks = 0; ks < KS; ++ks) S = mfma(lds_row8(qt_ + ra.row[ks] + qb * 32 * D * 2), kf[ks], S);
+        __builtin_amdgcn_sched_barrier(0);
+        // p for the 32 queries of this block (register 4 i4 + e: query 8 i4 + 4 h + e)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const int r0 = 32 * qb + 8 * i4 + 4 * h;
-        const f32x4 l2 = *reinterpret_cast<const f32x4*>(&s_l2[stage][r0]);
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const int r0 = 32 * qb + 8 * i4 + 4 * h;
+          const f32x4 l2 = *reinterpret_cast<const f32x4*>(&s_l2[stage][r0]);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) S[4 * i4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[4 * i4 + e], c, -l2[e]));
+          for (int e = 0; e < 4; ++e) S[4 * i4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[4 * i4 + e], c, -l2[e]));
+        }
+        if (need_mask) {
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int q_pos = p.causal ? pos0 + 32 * qb + 8 * i4 + 4 * h + e : INT_MAX - 1;
+              if (key_tok > q_pos) S[4 * i4 + e] = 0.f;
+            }
+        }
+        bf16x8 pb[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const u32x4 pf = {pack2(S[8 * j + 0], S[8 * j + 1]), pack2(S[8 * j + 2], S[8 * j + 3]),
+                            pack2(S[8 * j + 4], S[8 * j + 5]), pack2(S[8 * j + 6], S[8 * j + 7])};
+          pb[j] = __builtin_bit_cast(bf16x8, pf);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int grp = (2 * qb + j) * 16 * D * 2;
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+            dv[db] = mfma(lds_tr8(ot_ + ra.tr[db][0] + grp, ot_ + ra.tr[db][1] + grp), pb[j], dv[db]);
+        }
+        f32x16 dP;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dP[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          bf16x8 vb;
+          if constexpr (VLDS) vb = lds_row8(vst + ra.row[ks]);
+          else vb = vf[ks];
+          dP = mfma(lds_row8(ot_ + ra.row[ks] + qb * 32 * D * 2), vb, dP);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const int r0 = 32 * qb + 8 * i4 + 4 * h;
+          const f32x4 dl = *reinterpret_cast<const f32x4*>(&s_dl[stage][r0]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dP[4 * i4 + e] = S[4 * i4 + e] * (dP[4 * i4 + e] - dl[e]);
+        }
+        bf16x8 eb[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const u32x4 ef = {pack2(dP[8 * j + 0], dP[8 * j + 1]), pack2(dP[8 * j + 2], dP[8 * j + 3]),
+                            pack2(dP[8 * j + 4], dP[8 * j + 5]), pack2(dP[8 * j + 6], dP[8 * j + 7])};
+          eb[j] = __builtin_bit_cast(bf16x8, ef);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int grp = (2 * qb + j) * 16 * D * 2;
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+            dk[db] = mfma(lds_tr8(qt_ + ra.tr[db][0] + grp, qt_ + ra.tr[db][1] + grp), eb[j], dk[db]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      if (need_mask) {
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int q_pos = p.causal ? pos0 + 32 * qb + 8 * i4 + 4 * h + e : INT_MAX - 1;
-            if (key_tok > q_pos) S[4 * i4 + e] = 0.f;
-          }
-      }
+    } else {
+      // The matrix instructions of a tile as one stream of A-operand fragments, per 32-query block qb:
+      // KS row fragments of Q (scores), 2 DB transposed fragments of dout (dv), KS row fragments of
+      // dout (dout.v), 2 DB
+      // transposed fragments of Q (dk).  The reads of fragment F + PD are issued right after the
+      // instruction that consumed fragment F; scheduling barriers keep that order and keep S, p, dP
+      // and ds from being alive together more than they must (p is formed in place before the dv
+      // instructions, ds of each 16-query group right before the dk instructions that use it).
+      f32x16 S, dP;
       bf16x8 pb[2];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const u32x4 pf = {pack2(S[8 * j + 0], S[8 * j + 1]), pack2(S[8 * j + 2], S[8 * j + 3]),
-                          pack2(S[8 * j + 4], S[8 * j + 5]), pack2(S[8 * j + 6], S[8 * j + 7])};
-        pb[j] = __builtin_bit_cast(bf16x8, pf);
-      }
+      static_for<PD>([&](auto ff) __attribute__((always_inline)) { issue(ff, qt_, ot_); });
       __builtin_amdgcn_sched_barrier(0);
+      static_for<NFT>([&](auto ff) __attribute__((always_inline)) {
+        constexpr int F = decltype(ff)::value, qb = F / NFB, f = F % NFB, slot = F % PD;
+        if constexpr (f < KS) {
+          if constexpr (f == 0) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int grp = (2 * qb + j) * 16 * D * 2;
+            for (int i = 0; i < 16; ++i) S[i] = 0.f;
+          }
+          S = mfma(ring[slot], kf[f], S);
+        } else if constexpr (f < KS + 2 * DB) {
+          constexpr int j = (f - KS) / DB, db = (f - KS) % DB;
+          if constexpr (f == KS) {
+            // p for the 32 queries of this block (register 4 i4 + e: query 8 i4 + 4 h + e), in place
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-          dv[db] = mfma(lds_tr8(ot_ + ra.tr[db][0] + grp, ot_ + ra.tr[db][1] + grp), pb[j], dv[db]);
-      }
-      f32x16 dP;
+            for (int i4 = 0; i4 < 4; ++i4) {
+              const f32x4 l2 = *reinterpret_cast<const f32x4*>(&s_l2[stage][32 * qb + 8 * i4 + 4 * h]);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) dP[i] = 0.f;
+              for (int e = 0; e < 4; ++e) S[4 * i4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[4 * i4 + e], c, -l2[e]));
+            }
+            if (need_mask) {
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 vb;
-        if constexpr (VLDS) vb = lds_row8(vst + ra.row[ks]);
-        else vb = vf[ks];
-        dP = mfma(lds_row8(ot_ + ra.row[ks] + qb * 32 * D * 2), vb, dP);
-      }
-      __builtin_amdgcn_sched_barrier(0);
+              for (int i4 = 0; i4 < 4; ++i4)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const int r0 = 32 * qb + 8 * i4 + 4 * h;
-        const f32x4 dl = *reinterpret_cast<const f32x4*>(&s_dl[stage][r0]);
+                for (int e = 0; e < 4; ++e) {
+                  const int q_pos = p.causal ? pos0 + 32 * qb + 8 * i4 + 4 * h + e : INT_MAX - 1;
+                  if (key_tok > q_pos) S[4 * i4 + e] = 0.f;
+                }
+            }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) dP[4 * i4 + e] = S[4 * i4 + e] * (dP[4 * i4 + e] - dl[e]);
-      }
-      bf16x8 eb[2];
+            for (int jj = 0; jj < 2; ++jj) {
+              const u32x4 pf = {pack2(S[8 * jj + 0], S[8 * jj + 1]), pack2(S[8 * jj + 2], S[8 * jj + 3]),
+                                pack2(S[8 * jj + 4], S[8 * jj + 5]), pack2(S[8 * jj + 6], S[8 * jj + 7])};
+              pb[jj] = __builtin_bit_cast(bf16x8, pf);
+            }
+          }
+          dv[db] = mfma(ring[slot], pb[j], dv[db]);
+        } else if constexpr (f < 2 * KS + 2 * DB) {
+          constexpr int ks = f - KS - 2 * DB;
+          if constexpr (ks == 0) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const u32x4 ef = {pack2(dP[8 * j + 0], dP[8 * j + 1]), pack2(dP[8 * j + 2], dP[8 * j + 3]),
-                          pack2(dP[8 * j + 4], dP[8 * j + 5]), pack2(dP[8 * j + 6], dP[8 * j + 7])};
-        eb[j] = __builtin_bit_cast(bf16x8, ef);
-      }
-      __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < 16; ++i) dP[i] = 0.f;
+          }
+          dP = mfma(ring[slot], vf[ks], dP);
+        } else {
+          constexpr int j = (f - 2 * KS - 2 * DB) / DB, db = (f - 2 * KS - 2 * DB) % DB;
+          if constexpr (db == 0) {          // ds of the 16 queries of group j, packed to bf16 (reuses pb[j])
+            const f32x4 dla = *reinterpret_cast<const f32x4*>(&s_dl[stage][32 * qb + 16 * j + 4 * h]);
+            const f32x4 dlb = *reinterpret_cast<const f32x4*>(&s_dl[stage][32 * qb + 16 * j + 8 + 4 * h]);
+            float ds[8];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int grp = (2 * qb + j) * 16 * D * 2;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-          dk[db] = mfma(lds_tr8(qt_ + ra.tr[db][0] + grp, qt_ + ra.tr[db][1] + grp), eb[j], dk[db]);
-      }
-      __builtin_amdgcn_sched_barrier(0);
+            for (int e = 0; e < 4; ++e) {
+              ds[e] = S[8 * j + e] * (dP[8 * j + e] - dla[e]);
+              ds[4 + e] = S[8 * j + 4 + e] * (dP[8 * j + 4 + e] - dlb[e]);
+            }
+            const u32x4 ef = {pack2(ds[0], ds[1]), pack2(ds[2], ds[3]), pack2(ds[4], ds[5]), pack2(ds[6], ds[7])};
+            pb[j] = __builtin_bit_cast(bf16x8, ef);
+          }
+          dk[db] = mfma(ring[slot], pb[j], dk[db]);
+        }
+        if constexpr (F + PD < NFT) issue(std::integral_constant<int, F + PD>{}, qt_, ot_);
+        __builtin_amdgcn_sched_barrier(0);
+      });
     }
     cur = nxt;
     stage ^= 1;
