@@ -182,7 +182,8 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   int rem = w - g * per_g;
   const int tsk = rem >= tiles0 * G ? 1 : 0;
   if (tsk) rem -= tiles0 * G;
-  const int tile_q = rem / G;
+  // under the causal mask the later query tiles of a block see more keys: they start first
+  const int tile_q = p.causal ? (tsk ? tiles1 : tiles0) - 1 - rem / G : rem / G;
   const int hq = g * G + rem % G;
   const AttnTask& T = p.task[tsk];
   const int q_tile_row0 = tile_q * BM;                        // relative to the task
