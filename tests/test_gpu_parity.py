@@ -64,6 +64,8 @@ SMALL = [
     ("bf16_zz_n8_outliers", 4, 8, 7, 4096, 4, 2, 128),
     ("bf16_zz_d64", 1, 8, 2, 4096, 4, 2, 64),
     ("bf16_full_d64", 2, 8, 5, 8 * 200, 2, 2, 64),
+    ("bf16_zz_d64_w12", 1, 8, 2, 16 * 768, 2, 1, 64),           # half-chunks of 768 rows: the twelve-wavefront variant (384-row tiles)
+    ("bf16_full_d64_w12", 2, 8, 6, 8 * 1152, 2, 2, 64),         # L = 1152 = 3 x 384
     ("fp32_zz_n8", 0, 8, 4, 8 * 2 * 40, 2, 2, 64),
     ("fp32_full_d128", 0, 4, 1, 4 * 70, 2, 1, 128),
 ]
