@@ -276,3 +276,20 @@ def test_backward_call_recorded_into_a_graph(tb, fuse_steps):
         graph.replay()
         torch.cuda.synchronize()
         assert all(torch.equal(a, b) for a, b in zip((plan.dq, plan.dk, plan.dv), eager)), rep
+
+
+def test_fp32_batched(tb):
+    """The plain fp32 path with a batch of sequences: every element of every sequence at the fp32 bar."""
+    B = 2
+    ws = [wl.Workload("bwd_fp32_b%d" % b, 8, 1, 8 * 2 * 24, 2, 1, 64, "fp32", wl.ZIGZAG_CAUSAL, seed=wl.BASE_SEED + 970 + b)
+          for b in range(B)]
+    data = [wl.make_qkv(w) + (wl.make_dout(w),) for w in ws]
+    q, k, v, do = (torch.stack([x[i] for x in data]).cuda() for i in range(4))
+    s = tb.tasp_schedule(8, 1)
+    out, lse = tb.tasp_chunk_attn(q, k, v, s, wl.ZIGZAG_CAUSAL)
+    grads = tb.tasp_chunk_attn_bwd(q, k, v, out, lse, do, s, wl.ZIGZAG_CAUSAL)
+    torch.cuda.synchronize()
+    for b in range(B):
+        for nm, got, ref in zip(("dq", "dk", "dv"), grads, oracle_grads(ws[b], *data[b])):
+            err = float(np.abs(got[b].cpu().numpy().astype(np.float64) - ref).max())
+            assert err <= 1e-4 * max(1.0, float(np.abs(ref).max())), (b, nm, err)
