@@ -142,7 +142,7 @@ __device__ __forceinline__ void fence_o_written(f32x16& a) {
   else asm volatile("s_nop 1" : "+v"(a));
 }
 
-template <int D, int NS, int NW>
+template <int D, int NS, int NW, bool PERSIST>
 __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLaunch p) {
   using C = Cfg<D, NS, NW>;
   constexpr int BM = C::BM;
@@ -174,8 +174,13 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   const int tiles0 = (p.task[0].n_q + BM - 1) / BM;
   const int tiles1 = p.n_tasks > 1 ? (p.task[1].n_q + BM - 1) / BM : 0;
   const int per_g = (tiles0 + tiles1) * G;
-  const int w_all = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int per_b = per_g * p.Hkv;                            // workgroups of one sequence of the batch
+  const int per_b = per_g * p.Hkv;                            // work items of one sequence of the batch
+  // With PERSIST there is one workgroup per CU and it takes several work items in turn, which
+  // saves the 4 us a CU idles between two workgroups.  The outer loop costs registers, so this pays
+  // only where there are registers to spare and the items are short: d = 64, all steps in one launch.
+  for (int round = 0; PERSIST || round == 0; ++round) {
+  const int w_all = PERSIST ? persistent_item(blockIdx.x, gridDim.x, p.n_items, round) : xcd_contiguous(blockIdx.x, gridDim.x);
+  if (PERSIST && w_all < 0) break;
   const int bi = w_all / per_b;
   const int w = w_all - bi * per_b;
   const int g = w / per_g;
@@ -665,6 +670,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // no fetch may still be writing LDS when the workgroup ends
+  if constexpr (PERSIST) __syncthreads();   //   or when any wavefront starts staging the next item there
   fence_o();
 
   // ---- epilogue: normalise and store.  A lane owns one query row per strip; per (db, i4) it holds
@@ -721,17 +727,34 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
       if (h == 0) *ld = lse_new;
     }
   }
+  }  // next work item (PERSIST)
 }
 
 template <int D, int NS, int NW>
-hipError_t launch_variant(const AttnLaunch& p, hipStream_t stream) {
+hipError_t launch_variant(const AttnLaunch& p0, hipStream_t stream) {
   using C = Cfg<D, NS, NW>;
   int64_t tiles = 0;
-  for (int t = 0; t < p.n_tasks; ++t) tiles += (p.task[t].n_q + C::BM - 1) / C::BM;
-  const int64_t blocks = tiles * p.Hq * p.batch;
-  if (blocks == 0) return hipSuccess;
-  if (blocks > INT_MAX) return hipErrorInvalidValue;
-  return TASP_LAUNCH((attn_bf16_kernel<D, NS, NW>), dim3(static_cast<unsigned>(blocks)), dim3(C::NTHREADS), stream, p);
+  for (int t = 0; t < p0.n_tasks; ++t) tiles += (p0.task[t].n_q + C::BM - 1) / C::BM;
+  const int64_t items = tiles * p0.Hq * p0.batch;
+  if (items == 0) return hipSuccess;
+  if (items > INT_MAX) return hipErrorInvalidValue;
+  if constexpr (D == 64) {
+    if (p0.seg_ext[0] != nullptr) {            // all steps in one launch: persistent workgroups, one per CU
+      int dev = 0, cus = 0;
+      if (note_hip(hipGetDevice(&dev)) != hipSuccess ||
+          note_hip(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess)
+        return hipErrorInvalidValue;
+      cus -= cus % 8;
+      if (cus >= 8 && items > cus) {
+        AttnLaunch p = p0;
+        p.n_items = static_cast<int32_t>(items);
+        return TASP_LAUNCH((attn_bf16_kernel<D, NS, NW, true>), dim3(static_cast<unsigned>(cus)), dim3(C::NTHREADS), stream, p);
+      }
+    }
+  }
+  const AttnLaunch& p = p0;
+  const int64_t blocks = items;
+  return TASP_LAUNCH((attn_bf16_kernel<D, NS, NW, false>), dim3(static_cast<unsigned>(blocks)), dim3(C::NTHREADS), stream, p);
 }
 
 }  // namespace

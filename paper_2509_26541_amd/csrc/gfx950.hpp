@@ -55,4 +55,16 @@ __device__ inline int xcd_contiguous(int block, int nblocks) {
   return xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
 }
 
+// Work item of persistent workgroup `block` (of `nblocks`, a multiple of 8 and fewer than
+// n_items) in its `round`-th turn, or -1 when it has none left.  XCD x owns the same contiguous run
+// of items as in xcd_contiguous, and its nblocks/8 workgroups walk that run in rounds, forwards in
+// even rounds and backwards in odd ones, so that a run sorted by falling work is shared out evenly.
+__device__ inline int persistent_item(int block, int nblocks, int n_items, int round) {
+  const int xcd = block & 7, slot = block >> 3, slots = nblocks >> 3;
+  const int q8 = n_items >> 3, r8 = n_items & 7;
+  const int start = xcd * q8 + (xcd < r8 ? xcd : r8), cnt = q8 + (xcd < r8 ? 1 : 0);
+  const int pos = round * slots + ((round & 1) ? slots - 1 - slot : slot);
+  return pos < cnt ? start + pos : -1;
+}
+
 }  // namespace tasp

@@ -38,6 +38,7 @@ struct AttnLaunch {
   // Single-launch mode: the segment list of task t does not fit the descriptor and lives in device
   // memory as task[t].n_seg (start, end) pairs; task[t].seg_start / seg_end are then unused.
   const int32_t* seg_ext[kMaxTasks];
+  int32_t n_items;    // work items of the launch, for persistent workgroups; filled in by the launcher
 };
 
 // One contiguous run of local query rows (a half-chunk of the zig-zag layout, or all rows).

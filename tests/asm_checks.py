@@ -99,14 +99,15 @@ def spill_report(asm):
     return out
 
 
-def scratch_in_loops(asm, kernel_substring):
-    """(kernel, block label) of every basic block that the compiler marks as part of a loop and that
-    holds a scratch (spill) instruction, for kernels whose symbol contains `kernel_substring`."""
-    out, name, label, in_loop = [], None, None, False
+def scratch_in_loops(asm, kernel_substring, min_depth=1):
+    """(kernel, block label) of every basic block that the compiler marks as part of a loop nested at
+    least `min_depth` deep and that holds a scratch (spill) instruction, for kernels whose symbol
+    contains `kernel_substring`."""
+    out, name, label, deep = [], None, None, False
     for line in asm.split("\n"):
         m = re.match(r"^(_Z\w+):", line)
         if m:
-            name, label, in_loop = (m.group(1) if kernel_substring in m.group(1) else None), None, False
+            name, label, deep = (m.group(1) if kernel_substring in m.group(1) else None), None, False
             continue
         if name is None:
             continue
@@ -115,8 +116,10 @@ def scratch_in_loops(asm, kernel_substring):
             continue
         m = re.match(r"^(\.LBB\d+_\d+):(.*)", line)
         if m:
-            label, in_loop = m.group(1), "Loop" in m.group(2)
+            label = m.group(1)
+            depths = [int(d) for d in re.findall(r"Depth[= ](\d+)", m.group(2))]
+            deep = bool(depths) and max(depths) >= min_depth
             continue
-        if in_loop and line.strip().startswith("scratch_"):
+        if deep and line.strip().startswith("scratch_"):
             out.append((name, label))
     return out

@@ -247,6 +247,26 @@ def test_paper_grid_shape_batched(tb):
             check(ws[b], out[b].float().cpu().numpy(), lse[b].cpu().numpy(), ref_o, ref_l, rows)
 
 
+def test_single_launch_with_persistent_workgroups(tb):
+    """d = 64 and all steps in one launch with more work items (2 tasks x 12 heads x 16 sequences = 384)
+    than CUs: one persistent workgroup per CU takes its items in turn (two rounds, the second
+    incomplete).  Every row of three of the sequences against the oracle, the others against the
+    step-by-step call."""
+    B = 16
+    ws = [wl.paper_grid(12, 3072, seed_offset=1000 * b) for b in range(B)]
+    qkv = [wl.make_qkv(w) for w in ws]
+    q, k, v = (torch.stack([x[i] for x in qkv]).cuda() for i in range(3))
+    s = tb.tasp_schedule(ws[0].n_ranks, ws[0].rank)
+    out, lse = tb.tasp_chunk_attn(q, k, v, s, ws[0].mask_mode, fuse_steps=True)
+    ref_out, ref_lse = tb.tasp_chunk_attn(q, k, v, s, ws[0].mask_mode, fuse_merge=True)
+    torch.cuda.synchronize()
+    rows = list(range(ws[0].L))
+    for b in (0, 7, 15):
+        ref_o, ref_l = oracle_rows(ws[b], *qkv[b], rows)
+        check(ws[b], out[b].float().cpu().numpy(), lse[b].cpu().numpy(), ref_o, ref_l, rows)
+    assert float((lse - ref_lse).abs().max()) <= 1e-4 and float((out.float() - ref_out.float()).abs().max()) <= 2e-2
+
+
 @pytest.mark.parametrize("case", BATCHED, ids=[c[0] for c in BATCHED])
 @pytest.mark.parametrize("fuse", [False, True])
 def test_batched_call(tb, case, fuse):
