@@ -157,10 +157,12 @@ struct Profiler {
   hipStream_t stream = nullptr;
   bool failed = false;
   void begin(int kind) {
-    Span sp{kind, nullptr, nullptr};
-    if (hipEventCreate(&sp.beg) != hipSuccess || hipEventCreate(&sp.end) != hipSuccess) { failed = true; return; }
-    if (hipEventRecord(sp.beg, stream) != hipSuccess) failed = true;
-    spans.push_back(sp);
+    if (failed) return;
+    spans.push_back(Span{kind, nullptr, nullptr});       // pushed first: the destructor owns whatever gets created
+    Span& sp = spans.back();
+    if (hipEventCreate(&sp.beg) != hipSuccess || hipEventCreate(&sp.end) != hipSuccess ||
+        hipEventRecord(sp.beg, stream) != hipSuccess)
+      failed = true;
   }
   void end() {
     if (spans.empty() || failed) return;
@@ -468,40 +470,47 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
       }
       return TASP_OK;
     };
-    std::vector<tasp::QueryBlock> empty;
-    std::vector<tasp::Segment> ranges, step_ranges;
-    if (b->fuse_steps) {
-      AttnLaunch all{};
-      int32_t* dev_table = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes) +
-                                                      align_up(sh.lse_bytes));
-      {
-        Scope sc(prof, BwdSpans::kOther);
-        st = build_all_steps(s, &a, dev_table, stream, &all);
+    // All units; returns at the first failure, and the join below runs either way so that the
+    // caller's second stream is never left forked (which would also break a stream capture).
+    auto walk = [&]() -> int {
+      std::vector<tasp::QueryBlock> empty;
+      std::vector<tasp::Segment> ranges, step_ranges;
+      if (b->fuse_steps) {
+        AttnLaunch all{};
+        int32_t* dev_table = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes) +
+                                                        align_up(sh.lse_bytes));
+        {
+          Scope sc(prof, BwdSpans::kOther);
+          st = build_all_steps(s, &a, dev_table, stream, &all);
+          if (st != TASP_OK) return st;
+        }
+        for (int step = 0; step < s->n; ++step) {
+          st = tasp::step_key_ranges(*s, b->S, b->mask_mode, b->order, step, &step_ranges);
+          if (st != TASP_OK) return st;
+          ranges.insert(ranges.end(), step_ranges.begin(), step_ranges.end());
+        }
+        st = launch_unit(all, ranges);
         if (st != TASP_OK) return st;
       }
-      for (int step = 0; step < s->n; ++step) {
-        st = tasp::step_key_ranges(*s, b->S, b->mask_mode, b->order, step, &step_ranges);
+      for (int step = 0; step < s->n && !b->fuse_steps; ++step) {
+        AttnLaunch lp{};
+        empty.clear();
+        st = build_step(s, &a, step, &lp, &empty);
         if (st != TASP_OK) return st;
-        ranges.insert(ranges.end(), step_ranges.begin(), step_ranges.end());
+        st = tasp::step_key_ranges(*s, b->S, b->mask_mode, b->order, step, &ranges);
+        if (st != TASP_OK) return st;
+        st = launch_unit(lp, ranges);
+        if (st != TASP_OK) return st;
       }
-      st = launch_unit(all, ranges);
-      if (st != TASP_OK) return st;
-    }
-    for (int step = 0; step < s->n && !b->fuse_steps; ++step) {
-      AttnLaunch lp{};
-      empty.clear();
-      st = build_step(s, &a, step, &lp, &empty);
-      if (st != TASP_OK) return st;
-      st = tasp::step_key_ranges(*s, b->S, b->mask_mode, b->order, step, &ranges);
-      if (st != TASP_OK) return st;
-      st = launch_unit(lp, ranges);
-      if (st != TASP_OK) return st;
-    }
+      return TASP_OK;
+    };
+    st = walk();
     if (kv_stream != stream) {
       if (tasp::note_hip(hipEventRecord(join.e, kv_stream)) != hipSuccess ||
           tasp::note_hip(hipStreamWaitEvent(stream, join.e, 0)) != hipSuccess)
-        return TASP_EHIP;
+        return st != TASP_OK ? st : TASP_EHIP;
     }
+    if (st != TASP_OK) return st;
     if (bf16) {
       Scope sc(prof, BwdSpans::kOther);
       if (tasp::launch_cast_bf16(dq_acc, b->dq, n_q_elems, stream) != hipSuccess) return TASP_EHIP;
