@@ -85,7 +85,8 @@ def main():
     ap.add_argument("--no-backward", action="store_true", help="skip the leg that times the backward pass (bf16 workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-mode", action="store_true",
-                    help="skip the leg that runs the other merge mode (profiler runs: one kind of launch only)")
+                    help="skip the legs that run the other merge mode, the single launch and the backward pass on "
+                         "two streams (profiler runs: one kind of launch per kernel)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 256 MiB copy with the library's copy kernel (scales profiler traffic counters)")
     args = ap.parse_args()
@@ -279,14 +280,16 @@ def main():
 
         # one stream, and the dk/dv kernels on a second stream beside the dq kernels
         bplan, one_ms = time_bwd(None)
-        aux_plan, two_ms = time_bwd(torch.cuda.Stream())
-        del aux_plan
-        try:                                       # all steps in one dq and one dk/dv launch
-            fs_plan, fs_ms = time_bwd(None, fuse_steps=True)
-            del fs_plan
-        except tb.TaspError:
-            fs_ms = None
-        b_ms = min(one_ms, two_ms)
+        two_ms = fs_ms = None
+        if not args.no_other_mode:                 # profiler runs: one kind of launch only
+            aux_plan, two_ms = time_bwd(torch.cuda.Stream())
+            del aux_plan
+            try:                                   # all steps in one dq and one dk/dv launch
+                fs_plan, fs_ms = time_bwd(None, fuse_steps=True)
+                del fs_plan
+            except tb.TaspError:
+                fs_ms = None
+        b_ms = one_ms if two_ms is None else min(one_ms, two_ms)
         bp = bplan.profile()
         b_flops = bplan.flops()                  # 2.5 x forward: five products
         backward = {

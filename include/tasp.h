@@ -245,8 +245,12 @@ double tasp_chunk_attn_flops(const tasp_schedule_t* s, const tasp_attn_args* a);
  * instructions, the measured path) or TASP_DTYPE_FP32 (a plain small-shape path, all arithmetic
  * fp32); d is 64 or 128.  Every row of dq, dk and dv is written.
  * workspace: device, 256-byte aligned, at least tasp_chunk_attn_bwd_workspace_bytes() (the delta
- * vector and, for bf16, an fp32 copy of dq); contents are scratch.  Kernels are enqueued on hip_stream; the call
- * returns without synchronising.  Errors as for tasp_chunk_attn.
+ * vector; for bf16 also an fp32 copy of dq and, step by step with Hq > Hkv, fp32 partial dk and dv of
+ * one step's keys per query head of a group, twice the size of that copy: a step's dk/dv launch with
+ * few, unequal key tiles is cut into one workgroup per key tile and query head, and the partial sums
+ * are added in the order of the heads, so results do not depend on timing); contents are scratch.
+ * Kernels are enqueued on hip_stream; the call returns without synchronising.  Errors as for
+ * tasp_chunk_attn.
  * ---------------------------------------------------------------------------------------------- */
 typedef struct tasp_attn_bwd_args {
   const void*  q;
@@ -282,8 +286,9 @@ size_t tasp_chunk_attn_bwd_workspace_bytes(const tasp_schedule_t* s, const tasp_
 int    tasp_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args* a, void* hip_stream);
 
 /* The same call with every launch bracketed by HIP events; synchronises the stream.  dq = the
- * kernels that accumulate dq, dkv = the kernels that write dk and dv, other = delta, clearing the
- * fp32 dq and the final cast. */
+ * kernels that accumulate dq, dkv = the kernels that form dk and dv, other = delta and clearing the
+ * fp32 dq (one bracket), the final cast, the segment table of fuse_steps, and after every dk/dv
+ * launch that was split by query head the launch that adds its partial sums. */
 typedef struct tasp_bwd_profile {
   double  dq_ms, dkv_ms, other_ms;
   int32_t dq_launches, dkv_launches, other_launches;

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <functional>
 #include <vector>
 
 #include "internal.hpp"
@@ -219,6 +220,52 @@ int validate_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args* b, tasp_att
 
 struct BwdSpans { enum Kind { kDq = 0, kDkv = 1, kOther = 2 }; };
 
+// Estimated duration of a dk/dv launch, in 64-row query tiles of one head, with one workgroup per
+// key tile (`per_tile` = 1, each serving all G query heads of its group) or per key tile and query
+// head (`per_tile` = G).  Mirrors what the kernel and the hardware do: the work list is (sequence,
+// KV head, key tile, head) in that order, every XCD gets one contiguous eighth of it, and each of
+// its slots/8 workgroup slots takes the next workgroup when it is free.  A workgroup walks, for
+// each query block, the tiles from the first one that holds a row at or after its first key.
+int64_t dkv_makespan(const tasp::BwdLaunch& bp, int d, int per_tile, int slots) {
+  const int bs = d == 128 ? 256 : 128, bt = 64;
+  const int64_t total = bp.rng_vbeg[bp.n_rng];
+  const int64_t ktiles = (total + bs - 1) / bs;
+  const int G = bp.Hq / bp.Hkv;
+  std::vector<int32_t> work(static_cast<size_t>(ktiles));
+  int j = 0;
+  for (int64_t t = 0; t < ktiles; ++t) {
+    while (j + 1 < bp.n_rng && bp.rng_vbeg[j + 1] <= t * bs) ++j;     // the range that holds the tile's first key
+    // ranges are sorted by position, so the tile's first key is its earliest
+    const int64_t tmin = bp.rng_start[j] + (t * bs - bp.rng_vbeg[j]);
+    int64_t w = 0;
+    for (int qb = 0; qb < bp.n_blk; ++qb) {
+      const int64_t tiles = (bp.blk[qb].n + bt - 1) / bt;
+      const int64_t first = bp.causal ? std::max<int64_t>(0, (tmin - bp.blk[qb].pos0) / bt) : 0;
+      w += std::max<int64_t>(0, tiles - first);
+    }
+    work[static_cast<size_t>(t)] = static_cast<int32_t>(w);
+  }
+  const int64_t n = ktiles * bp.Hkv * bp.batch * per_tile;
+  const int xcd_slots = std::max(1, slots / 8);
+  constexpr int64_t kFixed = 4;      // set-up and epilogue of a workgroup, in the same unit
+  int64_t makespan = 0;
+  std::vector<int64_t> heap;
+  for (int x = 0; x < 8; ++x) {
+    const int64_t q8 = n / 8, r8 = n % 8;
+    const int64_t start = x * q8 + std::min<int64_t>(x, r8), cnt = q8 + (x < r8 ? 1 : 0);
+    heap.assign(static_cast<size_t>(xcd_slots), 0);
+    for (int64_t i = start; i < start + cnt; ++i) {
+      const int64_t tile = (i / per_tile) % ktiles;
+      const int64_t w = kFixed + static_cast<int64_t>(work[static_cast<size_t>(tile)]) * (per_tile == 1 ? G : 1);
+      std::pop_heap(heap.begin(), heap.end(), std::greater<int64_t>());
+      heap.back() += w;
+      std::push_heap(heap.begin(), heap.end(), std::greater<int64_t>());
+    }
+    makespan = std::max(makespan, *std::max_element(heap.begin(), heap.end()));
+  }
+  return makespan;
+}
+
 }  // namespace
 
 namespace tasp {
@@ -374,7 +421,10 @@ size_t tasp_chunk_attn_bwd_workspace_bytes(const tasp_schedule_t* s, const tasp_
   const size_t delta_bytes = align_up(B * L * b->Hq * sizeof(float));
   if (b->dtype == TASP_DTYPE_FP32) return delta_bytes;                   // dq itself is the fp32 accumulator
   const size_t table = b->fuse_steps ? align_up(kFusedTableBytes) : 0;    // segment lists of the single launch
-  return align_up(B * L * b->Hq * b->d * sizeof(float)) + delta_bytes + table;   // fp32 dq, delta
+  const size_t dq_bytes = align_up(B * L * b->Hq * b->d * sizeof(float));
+  // step by step with grouped heads: partial dk and dv per query head of a step's L keys, fp32
+  const size_t parts = (!b->fuse_steps && b->Hkv > 0 && b->Hq > b->Hkv) ? 2 * dq_bytes : 0;
+  return dq_bytes + delta_bytes + table + parts;   // fp32 dq, delta
 }
 
 double tasp_chunk_attn_bwd_flops(const tasp_schedule_t* s, const tasp_attn_bwd_args* b) {
@@ -405,6 +455,11 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
   float* delta = bf16 ? reinterpret_cast<float*>(static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes))
                       : static_cast<float*>(b->workspace);
   const int64_t n_q_elems = static_cast<int64_t>(sh.B) * sh.L * b->Hq * b->d;
+  // partial dk / dv of a dk/dv launch split by query head (see launch_unit): room for L keys a launch
+  float* part = (bf16 && !b->fuse_steps && b->Hq > b->Hkv)
+                    ? reinterpret_cast<float*>(static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes) +
+                                               align_up(sh.lse_bytes))
+                    : nullptr;
 
   try {
     {
@@ -457,6 +512,22 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
         vpos += ranges[i].end - ranges[i].start;
       }
       bp.rng_vbeg[n] = static_cast<int32_t>(vpos);
+      // A step's key tiles are few (S / N keys) and under the causal mask their work differs by
+      // whole multiples (a tile is seen by both local half-chunks, by one, or by none), so the
+      // launch ends with most CUs idle while a few finish a second tile.  Such a launch is cut
+      // finer, one workgroup per key tile and query head; the partial sums are added up afterwards.
+      // The finer launch costs about a tenth more where the coarse one is already even (four streams
+      // of query tiles per L2 instead of one, partial sums written and read back), so it is used
+      // where the estimate says it wins by more than that.
+      bp.split_heads = 0;
+      const int64_t wgs = tasp::bwd_dkv_workgroups(bp, b->d);
+      const int slots = tasp::bwd_dkv_resident_workgroups(b->d);
+      if (part != nullptr && vpos <= sh.L && wgs > 0 && wgs < 8 * static_cast<int64_t>(slots) &&
+          dkv_makespan(bp, b->d, bp.Hq / bp.Hkv, slots) * 112 < dkv_makespan(bp, b->d, 1, slots) * 100) {
+        bp.split_heads = 1;
+        bp.part_dk = part;
+        bp.part_dv = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(part) + align_up(sh.o_bytes));
+      }
       {
         Scope sc(prof, BwdSpans::kDq);
         if ((bf16 ? tasp::launch_bwd_dq_bf16(bp, b->d, stream) : tasp::launch_bwd_dq_fp32(bp, b->d, stream)) != hipSuccess)
@@ -467,6 +538,10 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
         if ((bf16 ? tasp::launch_bwd_dkv_bf16(bp, b->d, kv_stream) : tasp::launch_bwd_dkv_fp32(bp, b->d, kv_stream)) !=
             hipSuccess)
           return TASP_EHIP;
+      }
+      if (bp.split_heads) {
+        Scope sc(prof, BwdSpans::kOther);
+        if (tasp::launch_bwd_dkv_reduce(bp, b->d, kv_stream) != hipSuccess) return TASP_EHIP;
       }
       return TASP_OK;
     };

@@ -351,7 +351,8 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
 // NW wavefronts of 32 keys each.  The K rows of a wavefront's keys stay in registers; with VLDS the
 // V rows stay in LDS instead (read as B operand when needed), which is what lets a wavefront with
 // two 32 x D accumulators fit the 256 registers of two wavefronts per SIMD at D = 128.
-template <int D, int NW, bool VLDS>
+// With SPLIT a workgroup serves one query head of the group only and leaves fp32 partial sums.
+template <int D, int NW, bool VLDS, bool SPLIT>
 __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const BwdLaunch p) {
   using C = BCfg<D, NW>;
   constexpr int KS = D / 16, DB = D / 32, BS = C::BS, NTHREADS = C::NTHREADS;
@@ -368,10 +369,13 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
   const int total_keys = p.rng_vbeg[p.n_rng];
   const int ktiles = (total_keys + BS - 1) / BS;
   const int w_all = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int bi = w_all / (ktiles * p.Hkv);
-  const int w = w_all - bi * (ktiles * p.Hkv);
-  const int g = w / ktiles;
-  const int v0 = (w - g * ktiles) * BS;        // first key of the tile in the virtual concatenation
+  const int per_tile = SPLIT ? G : 1;          // workgroups per key tile
+  const int bi = w_all / (ktiles * p.Hkv * per_tile);
+  const int w = w_all - bi * (ktiles * p.Hkv * per_tile);
+  const int g = w / (ktiles * per_tile);
+  const int wt = w - g * (ktiles * per_tile);
+  const int v0 = (wt / per_tile) * BS;         // first key of the tile in the virtual concatenation
+  const int hh_beg = SPLIT ? wt % per_tile : 0, hh_end = SPLIT ? hh_beg + 1 : G;   // query heads of the group served here
 
   // smallest global position among the keys of the tile: queries before it see none of them
   if (tid == 0) {
@@ -421,9 +425,9 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
   };
   auto tiles_of = [&](int blk) __attribute__((always_inline)) { return (p.blk[blk].n + BT - 1) / BT; };
   struct It { int hh, blk, qt; };
-  // the first state at or after (hh, blk, qt) that has work; hh == G means done
+  // the first state at or after (hh, blk, qt) that has work; hh == hh_end means done
   auto settle = [&](It it) __attribute__((always_inline)) {
-    while (it.hh < G) {
+    while (it.hh < hh_end) {
       if (it.blk < p.n_blk && it.qt < tiles_of(it.blk)) return it;
       ++it.blk;
       if (it.blk >= p.n_blk) { it.blk = 0; ++it.hh; }
@@ -504,14 +508,14 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
     }
   };
 
-  It cur = settle(It{0, 0, first_tile(0)});
-  if (cur.hh < G) fetch(cur, 0);
+  It cur = settle(It{hh_beg, 0, first_tile(0)});
+  if (cur.hh < hh_end) fetch(cur, 0);
   int stage = 0;
-  while (cur.hh < G) {
+  while (cur.hh < hh_end) {
     const It nxt = settle(It{cur.hh, cur.blk, cur.qt + 1});
     wait_all_loads();
     __syncthreads();                 // the current tile is complete; nobody reads the other stage any more
-    if (nxt.hh < G) fetch(nxt, stage ^ 1);
+    if (nxt.hh < hh_end) fetch(nxt, stage ^ 1);
     const unsigned char* qt_ = smem + stage * C::STAGE_BYTES;
     const unsigned char* ot_ = qt_ + C::TILE_BYTES;
     const int pos0 = p.causal ? p.blk[cur.blk].pos0 + cur.qt * BT : 0;
@@ -678,6 +682,22 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
   wait_all_loads();
 
   // ---- epilogue: a lane owns one key row; per (db, i4) it holds 4 consecutive columns
+  if constexpr (SPLIT) {
+    if (key_valid) {
+      const int64_t vi = v0 + wave * 32 + lq;
+      const int64_t poff = (((static_cast<int64_t>(bi) * G + hh_beg) * total_keys + vi) * p.Hkv + g) * D + 4 * h;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const f32x4 a = {dk[db][4 * i4], dk[db][4 * i4 + 1], dk[db][4 * i4 + 2], dk[db][4 * i4 + 3]};
+          const f32x4 b = {dv[db][4 * i4], dv[db][4 * i4 + 1], dv[db][4 * i4 + 2], dv[db][4 * i4 + 3]};
+          *reinterpret_cast<f32x4*>(p.part_dk + poff + 32 * db + 8 * i4) = a;
+          *reinterpret_cast<f32x4*>(p.part_dv + poff + 32 * db + 8 * i4) = b;
+        }
+    }
+    return;
+  }
   if (key_valid) {
     __bf16* dkp = static_cast<__bf16*>(p.dk) + koff + 4 * h;
     __bf16* dvp = static_cast<__bf16*>(p.dv) + koff + 4 * h;
@@ -719,6 +739,43 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
   if (row < n_rows && part == 0) delta[row] = s;
 }
 
+// dk, dv of a launch split by query head: one thread per (sequence, key, KV head, 4 columns) adds the
+// G partial sums in the order of the heads, so the result does not depend on how the launch ran.
+template <int D>
+__global__ __launch_bounds__(256) void bwd_dkv_reduce_kernel(const BwdLaunch p) {
+  constexpr int C4 = D / 4;
+  const int total_keys = p.rng_vbeg[p.n_rng];
+  const int G = p.Hq / p.Hkv;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const int64_t per_b = static_cast<int64_t>(total_keys) * p.Hkv * C4;
+  if (idx >= per_b * p.batch) return;
+  const int64_t bi = idx / per_b;
+  const int64_t r = idx - bi * per_b;
+  const int c4 = static_cast<int>(r % C4);
+  const int g = static_cast<int>((r / C4) % p.Hkv);
+  const int vi = static_cast<int>(r / (static_cast<int64_t>(C4) * p.Hkv));
+  int tok = 0;
+  for (int j = 0; j < p.n_rng; ++j)
+    if (vi >= p.rng_vbeg[j] && vi < p.rng_vbeg[j + 1]) tok = p.rng_start[j] + (vi - p.rng_vbeg[j]);
+  f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+  for (int hh = 0; hh < G; ++hh) {
+    const int64_t poff = ((((bi * G + hh) * total_keys + vi) * p.Hkv + g) * C4 + c4) * 4;
+    const f32x4 x = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p.part_dk + poff));
+    const f32x4 y = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p.part_dv + poff));
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { a[e] += x[e]; b[e] += y[e]; }
+  }
+  bf16x4 ka, vb;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    ka[e] = static_cast<__bf16>(a[e] * p.scale);
+    vb[e] = static_cast<__bf16>(b[e]);
+  }
+  const int64_t koff = bi * p.kv_bstride + (static_cast<int64_t>(tok) * p.Hkv + g) * D + 4 * c4;
+  *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.dk) + koff) = ka;
+  *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.dv) + koff) = vb;
+}
+
 __global__ __launch_bounds__(256) void bwd_zero_kernel(f32x4* __restrict__ dst, int64_t n4) {
   const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   if (i < n4) dst[i] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -742,15 +799,39 @@ template <int D, int NW, bool VLDS>
 hipError_t launch_dkv_variant(const BwdLaunch& p, hipStream_t stream) {
   constexpr int BS = 32 * NW;
   const int64_t total = p.rng_vbeg[p.n_rng];
-  const int64_t blocks = (total + BS - 1) / BS * p.Hkv * p.batch;
+  const int64_t blocks = (total + BS - 1) / BS * p.Hkv * p.batch * (p.split_heads ? p.Hq / p.Hkv : 1);
   if (blocks == 0) return hipSuccess;
   if (blocks > INT_MAX) return hipErrorInvalidValue;
-  return TASP_LAUNCH((bwd_dkv_kernel<D, NW, VLDS>), dim3(static_cast<unsigned>(blocks)), dim3(64 * NW), stream, p);
+  const dim3 grid(static_cast<unsigned>(blocks)), block(64 * NW);
+  if (p.split_heads) return TASP_LAUNCH((bwd_dkv_kernel<D, NW, VLDS, true>), grid, block, stream, p);
+  return TASP_LAUNCH((bwd_dkv_kernel<D, NW, VLDS, false>), grid, block, stream, p);
 }
 
 hipError_t launch_bwd_dkv_bf16(const BwdLaunch& p, int d, hipStream_t stream) {
   if (d == 128) return launch_dkv_variant<128, 8, true>(p, stream);
   if (d == 64) return launch_dkv_variant<64, 4, false>(p, stream);
+  return hipErrorInvalidValue;
+}
+
+int64_t bwd_dkv_workgroups(const BwdLaunch& p, int d) {
+  const int bs = d == 128 ? 256 : 128;
+  return (static_cast<int64_t>(p.rng_vbeg[p.n_rng]) + bs - 1) / bs * p.Hkv * p.batch;
+}
+
+int bwd_dkv_resident_workgroups(int d) {
+  int dev = 0, cus = 256;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+    cus = 256;
+  return cus * (d == 128 ? 1 : 2);
+}
+
+hipError_t launch_bwd_dkv_reduce(const BwdLaunch& p, int d, hipStream_t stream) {
+  const int64_t threads = static_cast<int64_t>(p.rng_vbeg[p.n_rng]) * p.Hkv * (d / 4) * p.batch;
+  const int64_t blocks = (threads + 255) / 256;
+  if (blocks == 0) return hipSuccess;
+  if (blocks > INT_MAX) return hipErrorInvalidValue;
+  if (d == 128) return TASP_LAUNCH((bwd_dkv_reduce_kernel<128>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, p);
+  if (d == 64) return TASP_LAUNCH((bwd_dkv_reduce_kernel<64>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, p);
   return hipErrorInvalidValue;
 }
 

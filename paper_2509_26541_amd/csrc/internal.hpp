@@ -72,6 +72,13 @@ struct BwdLaunch {
   int32_t n_rng;
   int32_t rng_start[kMaxSeg];
   int32_t rng_vbeg[kMaxSeg + 1];
+  // dk/dv launch split by query head (a workgroup per key tile AND query head of the group, for
+  // launches whose key tiles alone are too few and too unequal to fill the chip): the workgroups
+  // write fp32 partial sums [B, Hq / Hkv, keys of the launch, Hkv, d] (unscaled, keys in the order of
+  // the concatenated ranges) and launch_bwd_dkv_reduce adds them up in a fixed order.
+  int32_t split_heads;
+  float* part_dk;
+  float* part_dv;
 };
 
 // Last HIP error this thread saw inside the library (hipSuccess if none); see tasp_last_hip_error().
@@ -106,6 +113,11 @@ hipError_t launch_write_i32(int32_t* dst, const int32_t* host_vals, int64_t n, h
 // Implemented in attn_bwd_bf16.hip.
 hipError_t launch_bwd_dq_bf16(const BwdLaunch& p, int d, hipStream_t stream);
 hipError_t launch_bwd_dkv_bf16(const BwdLaunch& p, int d, hipStream_t stream);
+// after a launch with split_heads: dk, dv = sum over the query heads of the partial sums, as bf16
+hipError_t launch_bwd_dkv_reduce(const BwdLaunch& p, int d, hipStream_t stream);
+// workgroups of the dk/dv launch without the split, and how many of them the chip holds at once
+int64_t bwd_dkv_workgroups(const BwdLaunch& p, int d);
+int bwd_dkv_resident_workgroups(int d);
 hipError_t launch_bwd_delta_bf16(const void* out, const void* dout, float* delta, int64_t n_rows, int d,
                                  hipStream_t stream);
 hipError_t launch_zero_f32(float* dst, int64_t n, hipStream_t stream);   // n a multiple of 4, dst 16-byte aligned

@@ -167,6 +167,47 @@ def test_second_stream_gives_the_same_bits(tb):
         assert all(torch.equal(a, b) for a, b in zip(one, two))
 
 
+def bwd_plan(tb, w, q, k, v, do, **kw):
+    s = tb.tasp_schedule(w.n_ranks, w.rank)
+    qd, kd, vd, dod = q.cuda(), k.cuda(), v.cuda(), do.cuda()
+    out, lse = tb.tasp_chunk_attn(qd, kd, vd, s, w.mask_mode, fuse_merge=True)
+    return tb.ChunkAttnBwdPlan(s, qd, kd, vd, out, lse, dod, w.mask_mode, **kw)
+
+
+def test_which_dkv_launches_are_split_by_query_head(tb):
+    """A step's dk/dv launch with few, unequal key tiles runs one workgroup per key tile and query
+    head and is followed by the launch that adds the partial sums up; seen from outside as one more
+    launch per step among the profile's `other` launches (delta + clearing dq, and the cast of dq)."""
+    w = small_workload(SMALL[0])                      # causal, 4 query heads per KV head
+    q, k, v = wl.make_qkv(w)
+    do = wl.make_dout(w)
+    assert 2 < bwd_plan(tb, w, q, k, v, do).profile().other_launches <= 2 + w.n_ranks      # not where nobody sees a key
+    assert bwd_plan(tb, w, q, k, v, do, fuse_steps=True).profile().other_launches == 3     # + the segment table
+    w1 = small_workload(SMALL[5])                     # one query head per KV head: nothing to split by
+    assert w1.Hq == w1.Hkv
+    assert bwd_plan(tb, w1, *wl.make_qkv(w1), wl.make_dout(w1)).profile().other_launches == 2
+
+
+def test_grouped_heads_step_by_step_with_equal_key_tiles(tb):
+    """Without the mask every key tile costs the same, and 64 tiles x 8 KV heads fill the chip's 512
+    workgroup slots (d = 64) exactly: this launch is NOT split, so the dk/dv kernel itself adds up the
+    query heads of a group.  Every element, upstream gradient on sampled rows."""
+    w = wl.Workload("bwd_full_n4_s32k_gqa2", 4, 1, 32768, 16, 8, 64, "bf16", wl.FULL, seed=wl.BASE_SEED + 733)
+    q, k, v = wl.make_qkv(w)
+    do = wl.make_dout(w)
+    keep = wl.sample_rows(w, 16)
+    sparse = torch.zeros_like(do)
+    sparse[keep] = do[keep]
+    plan = bwd_plan(tb, w, q, k, v, sparse)
+    if torch.cuda.get_device_properties(0).multi_processor_count == 256:
+        assert plan.profile().other_launches == 2
+    dq, dk, dv = plan.run()
+    torch.cuda.synchronize()
+    rq, rk, rv = oracle_grads(w, q, k, v, do, rows=keep)
+    close("dq kept rows", dq[keep], rq)
+    close("dk", dk, rk); close("dv", dv, rv)
+
+
 def test_rows_without_upstream_gradient_get_none(tb):
     """dout = 0 on a row: its dq is exactly zero and it adds nothing to dk, dv (linearity in dout)."""
     w = small_workload(SMALL[0])

@@ -74,13 +74,13 @@ def bwd_asm(tmp_path_factory):
 
 
 def test_backward_kernels_shape_and_register_budget(bwd_asm):
-    """Four instantiations; each reads its LDS tiles with LDS instructions (no flat loads: the address
+    """Six instantiations (the dk/dv kernel also split by query head); each reads its LDS tiles with LDS instructions (no flat loads: the address
     space was inferred), fills them with direct global->LDS loads, fits the 256 registers that let two
     wavefronts share a SIMD, and keeps register spills out of the loop that holds the matrix
     instructions."""
     import re
     ks = {k: v for k, v in asm_checks.kernels(bwd_asm).items() if "bwd_dq_kernel" in k or "bwd_dkv_kernel" in k}
-    assert len(ks) == 4, list(ks)
+    assert len(ks) == 6, list(ks)
     budget = dict((m.group(1), int(m.group(2))) for m in re.finditer(
         r"\.name:\s+(\S+)\n(?:.*\n)*?\s+\.vgpr_count:\s+(\d+)", bwd_asm))
     for name, ins in ks.items():
