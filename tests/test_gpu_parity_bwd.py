@@ -334,3 +334,68 @@ def test_fp32_batched(tb):
         for nm, got, ref in zip(("dq", "dk", "dv"), grads, oracle_grads(ws[b], *data[b])):
             err = float(np.abs(got[b].cpu().numpy().astype(np.float64) - ref).max())
             assert err <= 1e-4 * max(1.0, float(np.abs(ref).max())), (b, nm, err)
+
+
+# ------------------------------------------------------------------ the documented maxima
+def test_thirty_two_ranks(tb):
+    """N = 32, the most ranks one call takes (31 rings, 62 key segments per query block and step).
+    The single-launch form is refused there: the later half-chunk of rank 17 meets
+    31 x (17 + 2 x 14) = 1395 segments over all steps, more than TASP_MAX_FUSED_SEGMENTS."""
+    w = wl.Workload("bwd_zz_n32", 32, 17, 64 * 36, 4, 2, 128, "bf16", wl.ZIGZAG_CAUSAL, seed=wl.BASE_SEED + 761)
+    q, k, v = wl.make_qkv(w)
+    do = wl.make_dout(w)
+    s = tb.tasp_schedule(w.n_ranks, w.rank)
+    out, lse = tb.tasp_chunk_attn(q.cuda(), k.cuda(), v.cuda(), s, w.mask_mode, fuse_merge=True)
+    dq, dk, dv = tb.tasp_chunk_attn_bwd(q.cuda(), k.cuda(), v.cuda(), out, lse, do.cuda(), s, w.mask_mode)
+    torch.cuda.synchronize()
+    ro, rl = oracle_rows(w, q, k, v, range(w.L))
+    assert np.abs(out.float().cpu().numpy() - ro).max() <= 2e-2 and np.abs(lse.cpu().numpy() - rl).max() <= 1e-3
+    rq, rk, rv = oracle_grads(w, q, k, v, do, out=out.cpu())
+    close("dq", dq, rq); close("dk", dk, rk); close("dv", dv, rv)
+    for call in (lambda: tb.tasp_chunk_attn(q.cuda(), k.cuda(), v.cuda(), s, w.mask_mode, fuse_steps=True),
+                 lambda: tb.tasp_chunk_attn_bwd(q.cuda(), k.cuda(), v.cuda(), out, lse, do.cuda(), s, w.mask_mode, fuse_steps=True)):
+        with pytest.raises(tb.TaspError) as e:
+            call()
+        assert e.value.status == tb.EUNSUPPORTED_SHAPE
+
+
+def test_kv_tensors_of_exactly_2_to_32_bytes(tb):
+    """The largest K and V the bf16 kernels address (32-bit byte offsets): 2^21 tokens x 8 KV heads x
+    128 x 2 bytes = 2^32 bytes each.  Rank 0 holds the first and the LAST half-chunk, so its later
+    rows read every key up to the last byte.  Inputs are drawn on the GPU (seeded); the oracle gets the
+    last head (the highest addresses) of sampled rows, the upstream gradient is non-zero on those rows."""
+    S, H, d, n, rank = 1 << 21, 8, 128, 8, 0
+    w1 = wl.Workload("max_kv_head7", n, rank, S, 1, 1, d, "bf16", wl.ZIGZAG_CAUSAL, seed=wl.BASE_SEED + 787)
+    L = S // n
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w1.seed)
+    def draw(rows):
+        t = torch.empty((rows, H, d), dtype=torch.bfloat16, device="cuda")
+        for a in range(0, rows, 1 << 18):
+            b = min(rows, a + (1 << 18))
+            t[a:b] = torch.randn((b - a, H, d), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        return t
+    q, k, v = draw(L), draw(S), draw(S)
+    assert k.numel() * k.element_size() == 1 << 32
+    keep = wl.sample_rows(w1, 8)
+    assert L - 1 in keep
+    do = torch.zeros_like(q)
+    do[keep] = torch.randn((len(keep), H, d), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    s = tb.tasp_schedule(n, rank)
+    h = H - 1
+    q1, k1, v1, do1 = (t[:, h:h + 1].cpu() for t in (q, k, v, do))
+    ro, rl = oracle_rows(w1, q1, k1, v1, keep)
+    rq = rk = rv = None
+    for fuse_steps in (False, True):
+        out, lse = tb.tasp_chunk_attn(q, k, v, s, wl.ZIGZAG_CAUSAL, fuse_merge=True, fuse_steps=fuse_steps)
+        torch.cuda.synchronize()
+        eo = np.abs(out[keep, h:h + 1].float().cpu().numpy() - ro).max()
+        el = np.abs(lse[keep, h:h + 1].cpu().numpy() - rl).max()
+        assert eo <= 2e-2 and el <= 1e-3, (fuse_steps, eo, el)
+        dq, dk, dv = tb.tasp_chunk_attn_bwd(q, k, v, out, lse, do, s, wl.ZIGZAG_CAUSAL, fuse_steps=fuse_steps)
+        torch.cuda.synchronize()
+        if rq is None:
+            rq, rk, rv = oracle_grads(w1, q1, k1, v1, do1, rows=keep, out=out[:, h:h + 1].cpu())
+        close("dq kept rows", dq[keep, h:h + 1], rq)
+        close("dk last head", dk[:, h:h + 1], rk); close("dv last head", dv[:, h:h + 1], rv)
+        del out, lse, dq, dk, dv

@@ -302,3 +302,27 @@ def test_backward_argument_checks_and_sizes():
     assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EINVAL
     b.fuse_steps = 0
     assert tb.lib.tasp_chunk_attn_bwd_flops(s.handle, C.byref(b)) == 4 * 2.5 * fwd
+
+
+def test_documented_size_limits_of_the_attention_call():
+    """The limits tasp.h states, from both sides, before any HIP call: 32 ranks (62 segments a step)
+    pass the shape checks and 36 do not; K/V of exactly 2^32 bytes per tensor pass and one more row of
+    tokens does not; S must stay below 2^24 for bf16."""
+    a = tb.AttnArgs()
+    a.q = a.k = a.v = a.out = a.lse = 4096
+    a.Hq, a.Hkv, a.d, a.dtype, a.mask_mode = 8, 8, 128, tb.DTYPE_BF16, tb.MASK_ZIGZAG_CAUSAL
+    a.S = 64 * 36
+    assert tb.lib.tasp_chunk_attn(tb.tasp_schedule(32, 5).handle, C.byref(a), None) == tb.EWORKSPACE
+    a.S = 72 * 36
+    assert tb.lib.tasp_chunk_attn(tb.tasp_schedule(36, 5).handle, C.byref(a), None) == tb.EUNSUPPORTED_SHAPE
+    s8 = tb.tasp_schedule(8, 0)
+    a.S = 1 << 21                                     # x 8 heads x 128 x 2 bytes = 2^32
+    assert tb.lib.tasp_chunk_attn(s8.handle, C.byref(a), None) == tb.EWORKSPACE
+    a.S = (1 << 21) + 16
+    assert tb.lib.tasp_chunk_attn(s8.handle, C.byref(a), None) == tb.EUNSUPPORTED_SHAPE
+    a.Hq = a.Hkv = 1
+    a.d = 64
+    a.S = (1 << 24) - 16
+    assert tb.lib.tasp_chunk_attn(s8.handle, C.byref(a), None) == tb.EWORKSPACE
+    a.S = 1 << 24
+    assert tb.lib.tasp_chunk_attn(s8.handle, C.byref(a), None) == tb.EUNSUPPORTED_SHAPE
