@@ -399,3 +399,36 @@ def test_kv_tensors_of_exactly_2_to_32_bytes(tb):
         close("dq kept rows", dq[keep, h:h + 1], rq)
         close("dk last head", dk[:, h:h + 1], rk); close("dv last head", dv[:, h:h + 1], rv)
         del out, lse, dq, dk, dv
+
+
+def test_sequence_just_below_2_to_24_tokens(tb):
+    """The longest sequence the bf16 kernels take (token index times row bytes by a 24-bit multiply):
+    S = 2^24 - 64 tokens, one head of 64 columns, 32 ranks; rank 0 reads up to the last token.  Forward
+    and backward step by step (the single-launch form is refused at this rank count), sampled rows."""
+    S, d, n, rank = (1 << 24) - 64, 64, 32, 0
+    w1 = wl.Workload("max_tokens", n, rank, S, 1, 1, d, "bf16", wl.ZIGZAG_CAUSAL, seed=wl.BASE_SEED + 797)
+    L, Hh = S // n, S // (2 * n)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w1.seed)
+    def draw(rows):
+        t = torch.empty((rows, 1, d), dtype=torch.bfloat16, device="cuda")
+        for a in range(0, rows, 1 << 21):
+            b = min(rows, a + (1 << 21))
+            t[a:b] = torch.randn((b - a, 1, d), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        return t
+    q, k, v = draw(L), draw(S), draw(S)
+    keep = sorted({0, Hh - 1, Hh, L - 1} | {int(x) for x in torch.randint(0, L, (2,), generator=torch.Generator().manual_seed(5))})
+    do = torch.zeros_like(q)
+    do[keep] = torch.randn((len(keep), 1, d), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    s = tb.tasp_schedule(n, rank)
+    out, lse = tb.tasp_chunk_attn(q, k, v, s, wl.ZIGZAG_CAUSAL, fuse_merge=True)
+    dq, dk, dv = tb.tasp_chunk_attn_bwd(q, k, v, out, lse, do, s, wl.ZIGZAG_CAUSAL)
+    torch.cuda.synchronize()
+    qc, kc, vc, doc = q.cpu(), k.cpu(), v.cpu(), do.cpu()
+    ro, rl = oracle_rows(w1, qc, kc, vc, keep)
+    eo = np.abs(out[keep].float().cpu().numpy() - ro).max()
+    el = np.abs(lse[keep].cpu().numpy() - rl).max()
+    assert eo <= 2e-2 and el <= 1e-3, (eo, el)
+    rq, rk, rv = oracle_grads(w1, qc, kc, vc, doc, rows=keep, out=out.cpu())
+    close("dq kept rows", dq[keep], rq)
+    close("dk", dk, rk); close("dv", dv, rv)
