@@ -432,3 +432,30 @@ def test_sequence_just_below_2_to_24_tokens(tb):
     rq, rk, rv = oracle_grads(w1, qc, kc, vc, doc, rows=keep, out=out.cpu())
     close("dq kept rows", dq[keep], rq)
     close("dk", dk, rk); close("dv", dv, rv)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_largest_batch(tb, dtype):
+    """65535 sequences in one call, the most it takes; tiny ones (N = 4, 8 tokens, two rows a rank).
+    The first, a middle and the last sequence against the oracle, forward and backward."""
+    B, n, rank, S, Hq, Hkv, d = 65535, 4, 2, 8, 2, 1, 64
+    w = wl.Workload("max_batch_" + dtype, n, rank, S, Hq, Hkv, d, dtype, wl.ZIGZAG_CAUSAL, seed=wl.BASE_SEED + 811)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed)
+    draw = lambda *shape: torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(w.torch_dtype)
+    q, k, v, do = draw(B, w.L, Hq, d), draw(B, S, Hkv, d), draw(B, S, Hkv, d), draw(B, w.L, Hq, d)
+    s = tb.tasp_schedule(n, rank)
+    out, lse = tb.tasp_chunk_attn(q, k, v, s, w.mask_mode, fuse_merge=True)
+    dq, dk, dv = tb.tasp_chunk_attn_bwd(q, k, v, out, lse, do, s, w.mask_mode)
+    torch.cuda.synchronize()
+    tol_o, tol_l = (2e-2, 1e-3) if dtype == "bf16" else (1e-4, 1e-4)
+    for b in (0, 31000, B - 1):
+        qb, kb, vb, dob = q[b].cpu(), k[b].cpu(), v[b].cpu(), do[b].cpu()
+        ro, rl = oracle_rows(w, qb, kb, vb, range(w.L))
+        assert np.abs(out[b].float().cpu().numpy() - ro).max() <= tol_o and np.abs(lse[b].cpu().numpy() - rl).max() <= tol_l
+        rq, rk, rv = oracle_grads(w, qb, kb, vb, dob, out=out[b].cpu())
+        if dtype == "bf16":
+            close("dq", dq[b], rq); close("dk", dk[b], rk); close("dv", dv[b], rv)
+        else:
+            for got, ref in ((dq[b], rq), (dk[b], rk), (dv[b], rv)):
+                assert np.abs(got.cpu().numpy() - ref).max() <= 1e-4 * max(1.0, np.abs(ref).max())

@@ -326,3 +326,7 @@ def test_documented_size_limits_of_the_attention_call():
     assert tb.lib.tasp_chunk_attn(s8.handle, C.byref(a), None) == tb.EWORKSPACE
     a.S = 1 << 24
     assert tb.lib.tasp_chunk_attn(s8.handle, C.byref(a), None) == tb.EUNSUPPORTED_SHAPE
+    a.S, a.batch = 1024, 65535                       # the most sequences one call takes
+    assert tb.lib.tasp_chunk_attn(s8.handle, C.byref(a), None) == tb.EWORKSPACE
+    a.batch = 65536
+    assert tb.lib.tasp_chunk_attn(s8.handle, C.byref(a), None) == tb.EINVAL
