@@ -155,9 +155,10 @@ def main():
     flops_per_launch = flops / w.n_ranks                     # a launch = one step of Algorithm 3
     achieved = flops_per_launch / (attn_avg_ms * 1e-3) / 1e12
     # HBM bytes per attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
-    # the copy-kernel calibration); the figures live in profiles/traffic.json next to their summaries
+    # the copy-kernel calibration); the figures live in paper_2509_26541_amd/hbm_traffic.json, the
+    # summaries they come from in profiles/
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    tpath = os.path.join(ROOT, "paper_2509_26541_amd", "hbm_traffic.json")
     if os.path.exists(tpath) and args.batch == 1 and args.nodes <= 1 and args.order == "tasp":   # what was profiled
         with open(tpath) as f:
             traffic = json.load(f).get(w.name, {}).get("attn_bytes_per_launch")

@@ -18,7 +18,7 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_profiles_name_the_workload_the_bench_times():
     import json
     from paper_2509_26541_amd import workloads as wl
-    with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+    with open(os.path.join(ROOT, "paper_2509_26541_amd", "hbm_traffic.json")) as f:
         traffic = json.load(f)
     name = wl.CONFIGS[1].name                      # the default workload of bench.py
     assert name in traffic and traffic[name]["attn_bytes_per_launch"] > 0
