@@ -223,7 +223,7 @@ struct BwdSpans { enum Kind { kDq = 0, kDkv = 1, kOther = 2 }; };
 // Estimated duration of a dk/dv launch, in 64-row query tiles of one head, with one workgroup per
 // key tile (`per_tile` = 1, each serving all G query heads of its group) or per key tile and query
 // head (`per_tile` = G).  Mirrors what the kernel and the hardware do: the work list is (sequence,
-// KV head, key tile, head) in that order, every XCD gets one contiguous eighth of it, and each of
+// KV head, head, key tile) in that order, every XCD gets one contiguous eighth of it, and each of
 // its slots/8 workgroup slots takes the next workgroup when it is free.  A workgroup walks, for
 // each query block, the tiles from the first one that holds a row at or after its first key.
 int64_t dkv_makespan(const tasp::BwdLaunch& bp, int d, int per_tile, int slots) {
@@ -255,7 +255,7 @@ int64_t dkv_makespan(const tasp::BwdLaunch& bp, int d, int per_tile, int slots) 
     const int64_t start = x * q8 + std::min<int64_t>(x, r8), cnt = q8 + (x < r8 ? 1 : 0);
     heap.assign(static_cast<size_t>(xcd_slots), 0);
     for (int64_t i = start; i < start + cnt; ++i) {
-      const int64_t tile = (i / per_tile) % ktiles;
+      const int64_t tile = i % ktiles;
       const int64_t w = kFixed + static_cast<int64_t>(work[static_cast<size_t>(tile)]) * (per_tile == 1 ? G : 1);
       std::pop_heap(heap.begin(), heap.end(), std::greater<int64_t>());
       heap.back() += w;
@@ -516,14 +516,14 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
       // whole multiples (a tile is seen by both local half-chunks, by one, or by none), so the
       // launch ends with most CUs idle while a few finish a second tile.  Such a launch is cut
       // finer, one workgroup per key tile and query head; the partial sums are added up afterwards.
-      // The finer launch costs about a tenth more where the coarse one is already even (four streams
-      // of query tiles per L2 instead of one, partial sums written and read back), so it is used
-      // where the estimate says it wins by more than that.
+      // The finer launch costs a little where the coarse one is already even (partial sums written
+      // and read back, more workgroup set-ups), so it is used where the estimate says it wins by more
+      // than 4 %.
       bp.split_heads = 0;
       const int64_t wgs = tasp::bwd_dkv_workgroups(bp, b->d);
       const int slots = tasp::bwd_dkv_resident_workgroups(b->d);
       if (part != nullptr && vpos <= sh.L && wgs > 0 && wgs < 8 * static_cast<int64_t>(slots) &&
-          dkv_makespan(bp, b->d, bp.Hq / bp.Hkv, slots) * 112 < dkv_makespan(bp, b->d, 1, slots) * 100) {
+          dkv_makespan(bp, b->d, bp.Hq / bp.Hkv, slots) * 104 < dkv_makespan(bp, b->d, 1, slots) * 100) {
         bp.split_heads = 1;
         bp.part_dk = part;
         bp.part_dv = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(part) + align_up(sh.o_bytes));
