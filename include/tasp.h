@@ -174,6 +174,25 @@ typedef struct tasp_attn_args {
 size_t tasp_chunk_attn_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_args* a);
 int    tasp_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it): tasp_chunk_attn with the workspace taken from a fixed array of
+ * TASP_STATIC_SCRATCH_BYTES bytes inside the library's code object instead of from the caller
+ * (a->workspace and a->workspace_bytes are ignored).  Each GPU the library runs on holds that array
+ * from the time the library is loaded until the process ends.  The call allocates nothing on the
+ * device and frees nothing; inputs and outputs are the caller's as before.
+ *   - A call whose tasp_chunk_attn_workspace_bytes() exceeds TASP_STATIC_SCRATCH_BYTES returns
+ *     TASP_EWORKSPACE and enqueues nothing (bf16: B*L*Hq*d <= 16 Mi elements with fuse_merge, half of
+ *     that without; fp32 with fuse_merge needs no workspace at all).
+ *   - The device that is current when the call is made must be the device of hip_stream.  The first
+ *     call on a device asks the HIP runtime for the array's address on that device (a symbol query;
+ *     make that first call outside a stream capture).
+ *   - All calls on one GPU share the one array, and it keeps the last call's contents: nothing in it
+ *     has to start at zero (step 0 of every call overwrites what it uses), but two calls that overlap
+ *     on one GPU (different streams, or different threads) race.  Serialise them.
+ * Results are those of tasp_chunk_attn (the same kernels run). */
+#define TASP_STATIC_SCRATCH_BYTES (64u << 20)
+int tasp_chunk_attn_static(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream);
+
 /* The same call with every kernel launch bracketed by HIP events on `hip_stream`, for measurement.
  * Synchronises the stream before returning.  Times are sums over launches, in milliseconds:
  * attn = step-attention kernels, merge = update_out_lse kernels, other = the final bf16 cast. */

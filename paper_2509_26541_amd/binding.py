@@ -27,8 +27,9 @@ EXPORTS = [
     "tasp_lse_merge", "tasp_chunk_attn_flops", "tasp_chunk_attn_profile", "tasp_last_hip_error", "tasp_calibration_copy",
     "tasp_lse_merge_many", "tasp_calibration_mfma", "tasp_schedule_create_multinode",
     "tasp_chunk_attn_bwd_workspace_bytes", "tasp_chunk_attn_bwd", "tasp_chunk_attn_bwd_profile",
-    "tasp_chunk_attn_bwd_flops",
+    "tasp_chunk_attn_bwd_flops", "tasp_chunk_attn_static",
 ]
+STATIC_SCRATCH_BYTES = 64 << 20
 
 
 class TaspError(RuntimeError):
@@ -102,6 +103,7 @@ def _load():
     lib.tasp_chunk_attn_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(AttnArgs)]
     lib.tasp_chunk_attn_workspace_bytes.restype = C.c_size_t
     lib.tasp_chunk_attn.argtypes = [C.c_void_p, C.POINTER(AttnArgs), C.c_void_p]
+    lib.tasp_chunk_attn_static.argtypes = [C.c_void_p, C.POINTER(AttnArgs), C.c_void_p]
     lib.tasp_chunk_attn_profile.argtypes = [C.c_void_p, C.POINTER(AttnArgs), C.c_void_p, C.POINTER(Profile)]
     lib.tasp_step_attn.argtypes = [C.c_void_p, C.POINTER(AttnArgs), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.tasp_lse_merge.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
@@ -304,6 +306,22 @@ class ChunkAttnBwdPlan:
 
     def flops(self):
         return lib.tasp_chunk_attn_bwd_flops(self.schedule.handle, C.byref(self.args))
+
+
+def tasp_chunk_attn_static(q, k, v, out, lse, schedule, mask_mode, order=ORDER_TASP, fuse_merge=False,
+                           softmax_scale=0.0, fuse_steps=False):
+    """tasp_chunk_attn into the caller's out / lse with the library's own fixed scratch as workspace:
+    nothing is allocated, here or in the library.  Raises TaspError(EWORKSPACE) beyond STATIC_SCRATCH_BYTES."""
+    torch = _torch()
+    a = _args(q, k, v, mask_mode, order, fuse_merge, softmax_scale, fuse_steps)
+    if not (out.is_cuda and out.is_contiguous() and out.dtype == q.dtype and out.shape == q.shape):
+        raise ValueError("out must be a contiguous device tensor shaped and typed like q")
+    if not (lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and lse.shape == q.shape[:-1]):
+        raise ValueError("lse must be a contiguous fp32 device tensor [.., L, Hq]")
+    a.out, a.lse = out.data_ptr(), lse.data_ptr()
+    s = torch.cuda.current_stream().cuda_stream
+    _check(lib.tasp_chunk_attn_static(schedule.handle, C.byref(a), C.c_void_p(s)), "tasp_chunk_attn_static")
+    return out, lse
 
 
 def tasp_chunk_attn_bwd(q, k, v, out, lse, dout, schedule, mask_mode, order=ORDER_TASP, softmax_scale=0.0,

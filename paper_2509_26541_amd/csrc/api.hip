@@ -6,11 +6,17 @@
 #include <algorithm>
 #include <cmath>
 #include <functional>
+#include <mutex>
 #include <vector>
 
 #include "internal.hpp"
 #include "schedule.hpp"
 #include "tasp.h"
+
+// Scratch of tasp_chunk_attn_static: the workspace of a forward call, held in the code object instead
+// of being brought in by the caller.  In host code this name is only a handle for the HIP symbol
+// query below; the address the kernels get is the one that query returns, per device.
+static __device__ __align__(256) unsigned char scratch[TASP_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -412,6 +418,41 @@ static int run_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, voi
 
 int tasp_chunk_attn(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream) {
   return run_chunk_attn(s, a, hip_stream, nullptr);
+}
+
+// Device address of `scratch` on the current device.  Every GPU holds its own copy of the array at
+// its own address, so the address is asked for once per device, with that device current, and kept.
+static int static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = -1;
+  if (tasp::note_hip(hipGetDevice(&dev)) != hipSuccess) return TASP_EHIP;
+  if (dev < 0 || dev >= kMaxDevices) return TASP_EUNSUPPORTED_SHAPE;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (tasp::note_hip(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) != hipSuccess || p == nullptr) return TASP_EHIP;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return TASP_OK;
+}
+
+int tasp_chunk_attn_static(const tasp_schedule_t* s, const tasp_attn_args* a, void* hip_stream) {
+  if (s == nullptr || a == nullptr) return TASP_EINVAL;
+  Shape sh;
+  const int st = validate(s, a, &sh);
+  if (st != TASP_OK) return st;
+  // workspace_bytes() trusts its arguments; they have been validated above
+  if (tasp_chunk_attn_workspace_bytes(s, a) > static_cast<size_t>(TASP_STATIC_SCRATCH_BYTES)) return TASP_EWORKSPACE;
+  void* ws = nullptr;
+  const int sp = static_scratch(&ws);
+  if (sp != TASP_OK) return sp;
+  tasp_attn_args b = *a;
+  b.workspace = ws;
+  b.workspace_bytes = TASP_STATIC_SCRATCH_BYTES;
+  return run_chunk_attn(s, &b, hip_stream, nullptr);
 }
 
 size_t tasp_chunk_attn_bwd_workspace_bytes(const tasp_schedule_t* s, const tasp_attn_bwd_args* b) {
