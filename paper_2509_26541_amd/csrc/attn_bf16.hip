@@ -104,20 +104,29 @@ __device__ __forceinline__ void lds_wait(u32x2& a, u32x2& b) {
 // ACC: O^T and the Q fragments live in AGPRs (needed when a wave owns two strips; with one strip
 // everything fits the 256 VGPRs of a wave that shares its SIMD, and using any AGPR would make the
 // compiler split that budget in half).
-template <bool ACC>
+// W >= 0: the instruction's fragment `a` comes from LDS reads in flight, and the wait for it (at most
+// W younger LDS instructions outstanding) sits in the same asm statement: a wait in a statement of
+// its own that names the fragment makes the compiler put a wait state between the two (it has to
+// assume that any asm statement forwards its result like a sub-dword write).  W < 0: no wait.
+#define TASP_MFMA_ASM(W, ...)                                                                   \
+  do {                                                                                          \
+    if constexpr ((W) >= 0) asm volatile("s_waitcnt lgkmcnt(%3)\n\t" __VA_ARGS__, "n"((W) < 0 ? 0 : (W))); \
+    else asm volatile(__VA_ARGS__, "n"(0));                                                     \
+  } while (0)
+template <bool ACC, int W = -1>
 __device__ __forceinline__ void mfma_s_first(f32x16& d, const u32x4& a, const u32x4& b) {
-  if constexpr (ACC) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
-  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
+  if constexpr (ACC) TASP_MFMA_ASM(W, "v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+  else TASP_MFMA_ASM(W, "v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
 }
-template <bool ACC>
+template <bool ACC, int W = -1>
 __device__ __forceinline__ void mfma_s(f32x16& d, const u32x4& a, const u32x4& b) {
-  if constexpr (ACC) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
-  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
+  if constexpr (ACC) TASP_MFMA_ASM(W, "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+  else TASP_MFMA_ASM(W, "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
 }
-template <bool ACC>
+template <bool ACC, int W = -1>
 __device__ __forceinline__ void mfma_o(f32x16& d, const u32x4& a, const u32x4& b) {
-  if constexpr (ACC) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
-  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
+  if constexpr (ACC) TASP_MFMA_ASM(W, "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
+  else TASP_MFMA_ASM(W, "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
 }
 // score tile: readable by the vector ALU after this point (placed at least one matrix instruction after the last one that wrote it)
 __device__ __forceinline__ void fence_s(f32x16& a, f32x16& b) { asm volatile("s_nop 15" : "+v"(a), "+v"(b)); }
@@ -588,8 +597,19 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   //   vector stream:  P(t) = exp2(S(t) c - m), most of it     the rest, mask and row maxima of S(t+1)
   // Two score tiles alternate, so the loop is unrolled twice; an odd last body runs on a tile past
   // the end, whose scores are all masked (its exponentials are 0, its maxima -inf).
+  //
+  // Two wavefronts share a SIMD, and when both have an instruction ready the arbiter always takes
+  // the one of the wavefront that was launched first: left alone, the first four wavefronts finish
+  // a body in 2 700 cycles and wait 700 at the barrier while the other four, which got what issue
+  // slots were left, take 3 300.  So the later four run at priority 1 throughout, and the first
+  // four at priority 1 (where the tie goes to them) for the first half of a body and at 0 for the
+  // rest; both groups then reach the barrier within about a hundred cycles of each other.
+  constexpr bool kBalance = NW == 8;
+  const bool first_on_simd = wave_u < 4;
+  if (kBalance && !first_on_simd) __builtin_amdgcn_s_setprio(1);
   constexpr std::integral_constant<int, 1> one_in_flight{};
   auto body = [&](int t, f32x16 (&S_cur)[NS][2], f32x16 (&S_next)[NS][2]) __attribute__((always_inline)) {
+    if (kBalance && first_on_simd) __builtin_amdgcn_s_setprio(1);
     const unsigned base_v = (t & 3) * STAGE_BYTES, base_k = ((t + 1) & 3) * STAGE_BYTES;
     static_for<PD>([&](auto f) __attribute__((always_inline)) { issue(f, base_k, base_v); });
     raise_max();                                  // of S_cur; also fills the time the first fragments take to arrive
@@ -598,13 +618,15 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
     __builtin_amdgcn_sched_barrier(0);
     static_for<NF>([&](auto ff) __attribute__((always_inline)) {
       constexpr int F = decltype(ff)::value, slot = F % PD, W = younger(F);
+      if constexpr (kBalance && F == NF / 2) {
+        if (first_on_simd) __builtin_amdgcn_s_setprio(0);
+      }
       if constexpr (F < NKF) {
         constexpr int ks = F / 2, kb = F % 2;
-        lds_wait<W>(fk[slot]);
         static_for<NS>([&](auto ss) __attribute__((always_inline)) {
-          constexpr int s = decltype(ss)::value;
-          if constexpr (ks == 0) mfma_s_first<ACC>(S_next[s][kb], fk[slot], qf[s][0]);
-          else mfma_s<ACC>(S_next[s][kb], fk[slot], qf[s][ks]);
+          constexpr int s = decltype(ss)::value, WW = s == 0 ? W : -1;     // the first strip's instruction waits for the fragment
+          if constexpr (ks == 0) mfma_s_first<ACC, WW>(S_next[s][kb], fk[slot], qf[s][0]);
+          else mfma_s<ACC, WW>(S_next[s][kb], fk[slot], qf[s][ks]);
           vector_slot(std::integral_constant<int, NS * F + s>{}, S_cur, S_next);
           __builtin_amdgcn_sched_barrier(0);
         });
@@ -619,11 +641,10 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
           fence_scores(S_next);
           mask(t + 1, S_next);
         }
-        lds_wait<W>(fl[slot], fh[slot]);
         const u32x4 av = {fl[slot][0], fl[slot][1], fh[slot][0], fh[slot][1]};
         static_for<NS>([&](auto ss) __attribute__((always_inline)) {
-          constexpr int s = decltype(ss)::value;
-          mfma_o<ACC>(o[s][db], av, pf[s][gg]);
+          constexpr int s = decltype(ss)::value, WW = s == 0 ? W : -1;
+          mfma_o<ACC, WW>(o[s][db], av, pf[s][gg]);
           vector_slot(std::integral_constant<int, NS * F + s>{}, S_cur, S_next);
           __builtin_amdgcn_sched_barrier(0);
         });
