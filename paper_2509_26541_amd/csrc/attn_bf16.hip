@@ -14,18 +14,28 @@
 // tiles with the transposing LDS read (ds_read_b64_tr_b16); both tiles are XOR-swizzled in 16-byte
 // units so that neither the fills nor the reads conflict on banks.
 //
-// The loop is software-pipelined by hand inside each wavefront: the scores of tile t+1 and the
-// second product of tile t form one stream of matrix instructions, the softmax arithmetic of tile t
-// and the row maxima of tile t+1 are dealt out between them, operand fragments are read four
-// ahead (two would do: the depth from 2 to 8 makes no measurable difference).  Matrix instructions
-// and LDS reads are volatile assembly, so their order is the schedule.
+// The loop is software-pipelined by hand inside each wavefront: the second product of tile t and
+// the scores of tile t+2 form one stream of matrix instructions that never drains (not at the
+// barrier of a tile either), the softmax arithmetic of tiles t and t+1 is dealt out between them,
+// operand fragments are read four ahead (two would do: the depth from 2 to 8 makes no measurable
+// difference).  Matrix instructions and LDS reads are volatile assembly, so their order is the
+// schedule.
+//
+// What bounds it (measured with issue microbenchmarks on this chip): the vector issue port of a
+// SIMD.  A matrix instruction occupies it for 12 cycles (and its own pipe for 32), a plain vector
+// instruction for 4, an exponential for 8, and every KiB of LDS data returned to registers for
+// about 4 more; per 64-key tile and wavefront that is 32 x 12 + ~115 x 4 + 32 x 8 + 32 x 4 cycles,
+// for two wavefronts more than the 2 048 cycles the matrix pipe needs.  So every vector instruction
+// in the loop counts (the scalar bookkeeping of the loader, the waits folded into the matrix
+// instructions, the few branches), and beyond that the chip's power limit: with operands of
+// ordinary statistics the clock falls as the pipes fill (1.55 - 1.7 GHz in this kernel against
+// 2.4 GHz nominal), so cycles saved come back only in part.
 //
 // A wavefront owns NS strips.  NS = 1 (eight wavefronts, two per SIMD) is what the library
-// launches.  With 32 rows per wavefront every matrix instruction needs 1 KiB of operand from LDS,
-// i.e. the LDS has to deliver its full 128 B/clk for the matrix pipe to run at its peak.  NS = 2
-// (each fragment feeds two matrix instructions, O^T and Q in AGPRs, one wavefront per SIMD) halves
-// that traffic, but then one wavefront has to issue every instruction of its SIMD and is bound by
-// that: measured slower, kept as a template parameter.
+// launches.  NS = 2 (each LDS fragment feeds two matrix instructions, O^T and Q in AGPRs, one
+// wavefront per SIMD) halves the LDS traffic and runs at a higher clock, but one wavefront issues a
+// vector instruction only every five cycles and has to issue everything itself: 4 050 cycles per
+// tile against 3 100, slower in time as well; kept as a template parameter.
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -75,9 +85,10 @@ __device__ inline void dma16(const unsigned char* base, unsigned off, unsigned c
 }
 
 // LDS operand reads whose wait is placed by hand.  A read is volatile assembly (issued in program
-// order), and the fragment reaches its matrix instruction only through lds_wait, which waits until
-// at most N younger LDS instructions are outstanding (LDS instructions of a wavefront complete in
-// order, so extra ones the compiler adds only make a wait stricter).
+// order), and the fragment reaches its matrix instruction only behind a wait until at most N
+// younger LDS instructions are outstanding (LDS instructions of a wavefront complete in order, so
+// extra ones the compiler adds only make a wait stricter).  In the loop that wait is part of the
+// matrix instruction's own asm statement (TASP_MFMA_ASM); lds_wait is the stand-alone form.
 template <int IMM>
 __device__ __forceinline__ void lds_read_b128(u32x4& d, unsigned addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(IMM));
@@ -304,77 +315,98 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   // into K and V fit 32 bits (checked on the host).
   const int fr = tid / C::UNITS, fu = tid % C::UNITS;
   const unsigned row_bytes = static_cast<unsigned>(p.Hkv) * D * 2;
-  // Row bookkeeping of the loader.  Each thread follows its PASSES rows through the virtual
-  // concatenation: from one tile to the next a row moves 64 keys on and normally stays inside its
-  // effective segment (token += 64); only when it runs off the end of the segment is the segment
-  // list searched again.  tokk = global position (INT_MAX: past the last key), lefti = keys from
-  // the row to the end of its segment.
-  int tokk[C::PASSES], segi[C::PASSES], lefti[C::PASSES];
-  auto relocate = [&](int i, int v) __attribute__((always_inline)) {
-    int j = segi[i];
-    while (j < n_eff && v >= e_vbeg[j + 1]) ++j;              // rows only move forward
-    segi[i] = j;
-    if (j < n_eff) { tokk[i] = v + e_goff[j]; lefti[i] = e_vbeg[j + 1] - v; }
-    else { tokk[i] = INT_MAX; lefti[i] = 1 << 30; }
+  // Row bookkeeping of the loader.  One wavefront-load covers RW consecutive rows of a tile, and as
+  // long as these are RW consecutive keys of one effective segment, the lane offsets are a
+  // wavefront-uniform base plus a per-lane constant.  So the bookkeeping is scalar: per pass the
+  // wavefront follows the first of its RW rows through the virtual concatenation (w_tok = its global
+  // position, INT_MAX past the last key; w_left = keys from it to the end of its segment; w_seg = its
+  // segment), from one tile to the next it moves 64 keys on, and only when fewer than RW keys are
+  // left in the segment (one tile in about twenty with sub-chunks of a thousand keys) every lane
+  // searches the segment list for its own row.  A vector instruction costs the SIMD's issue port as
+  // much as a third of a matrix instruction, and the port is what bounds this kernel.
+  constexpr int RW = 64 / C::UNITS;
+  const int r_lane = lane / C::UNITS;
+  int w_tok[C::PASSES], w_left[C::PASSES], w_seg[C::PASSES];
+#pragma unroll
+  for (int i = 0; i < C::PASSES; ++i) { w_tok[i] = 0; w_left[i] = 0; w_seg[i] = 0; }
+  int tokk[C::PASSES];           // global position of this lane's row of the tile being fetched
+  // every lane finds its own row of tile t (pass i); the wavefront's state is taken from its first lane
+  auto locate_slow = [&](int i, int t) __attribute__((always_inline)) {
+    const int v = t * BN + fr + C::RPP * i;
+    int j = w_seg[i], left;                                   // rows only move forward
+    while (j < n_eff && v >= e_vbeg[j + 1]) ++j;
+    if (j < n_eff) { tokk[i] = v + e_goff[j]; left = e_vbeg[j + 1] - v; }
+    else { tokk[i] = INT_MAX; left = 1 << 30; }
+    w_tok[i] = __builtin_amdgcn_readfirstlane(tokk[i]);
+    w_left[i] = __builtin_amdgcn_readfirstlane(left);
+    w_seg[i] = __builtin_amdgcn_readfirstlane(j);
   };
   // rows of tile t; must be called for t = 0, 1, 2, ... in this order
   auto locate = [&](int t) __attribute__((always_inline)) {
-    if (t == 0) {
-#pragma unroll
-      for (int i = 0; i < C::PASSES; ++i) { segi[i] = 0; relocate(i, fr + C::RPP * i); }
-      return;
-    }
-    bool off_end = false;
+    int least = 1 << 30;
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
-      lefti[i] -= BN;
-      tokk[i] = tokk[i] == INT_MAX ? INT_MAX : tokk[i] + BN;
-      off_end |= lefti[i] <= 0;
+      w_left[i] -= BN;                                        // tile 0: from 0, i.e. search
+      w_tok[i] = w_tok[i] == INT_MAX ? INT_MAX : w_tok[i] + BN;
+      least = min(least, w_left[i]);
     }
-    if (__builtin_amdgcn_ballot_w64(off_end) != 0) {
+#pragma unroll
+    for (int i = 0; i < C::PASSES; ++i) tokk[i] = w_tok[i] + (r_lane & (w_tok[i] == INT_MAX ? 0 : -1));
+    if (__builtin_expect(least < RW, 0)) {
 #pragma unroll
       for (int i = 0; i < C::PASSES; ++i)
-        if (lefti[i] <= 0) relocate(i, t * BN + fr + C::RPP * i);
+        if (w_left[i] < RW) locate_slow(i, t);
     }
   };
-  // Fetch tile t straight into ring stage `stage` (global_load_lds: no registers, no LDS write
-  // instructions).  A wavefront's 64 lanes fill 1 KiB of consecutive LDS; the XOR swizzle of the
-  // tile layout is applied on the source side: the lane that owns LDS slot (row, unit) reads the
-  // 16 bytes of column swz(row, unit) of that row.  Rows past the end fetch token 0 and are masked.
+  // Tiles go straight into the ring (global_load_lds: no registers, no LDS write instructions).
+  // A wavefront's 64 lanes fill 1 KiB of consecutive LDS; the XOR swizzle of the tile layout is
+  // applied on the source side: the lane that owns LDS slot (row, unit) reads the 16 bytes of column
+  // swz(row, unit) of that row.  Rows past the end fetch token 0 and are masked.
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  const bool is_loader = wave_u < C::LOADERS / 64;     // wavefront-uniform
+  // wavefront-uniform, and known at compile time when every wavefront fetches (a branch costs a
+  // wavefront 20-40 cycles even when it is not taken)
+  const bool is_loader = C::LOADERS == C::NTHREADS || wave_u < C::LOADERS / 64;
   const unsigned char* Kg = static_cast<const unsigned char*>(p.k) + (bi * p.kv_bstride + static_cast<int64_t>(g) * D) * 2;   // this sequence and KV head, uniform
   const unsigned char* Vg = static_cast<const unsigned char*>(p.v) + (bi * p.kv_bstride + static_cast<int64_t>(g) * D) * 2;
   const unsigned k_col = C::swz_k(fr, fu) * 16, v_col = C::swz_v(fr, fu) * 16;    // byte column this lane reads
   static_assert(C::RPP % 16 == 0, "the swizzle of a thread's rows must not depend on the pass");
-  // A tile fetch is 2*PASSES loads per thread.  The path from L2 into LDS takes roughly 25 cycles per
-  // wavefront-load and the issuing wave stalls once its queue is full, so the loads are not issued
-  // in one burst: fetch_begin does the bookkeeping, fetch_piece(j) issues load j, and the loop
-  // drops the pieces between its matrix instructions.
+  // Round u of the fetch brings K(u) into the K half of stage u % 4 and V(u-1) into the V half of
+  // stage (u-1) % 4 (the main loop says why the two halves of a tile travel a round apart); 2*PASSES
+  // loads per thread.  The path from L2 into LDS takes roughly 25 cycles per wavefront-load and the
+  // issuing wave stalls once its queue is full, so the loads are not issued in one burst:
+  // fetch_begin(u) does the bookkeeping of tile u, fetch_piece(j) issues load j (even: K(u), pass
+  // j/2; odd: V(u-1)), and the loop drops the pieces between its matrix instructions.  The V offsets
+  // of a tile are its K offsets moved to the V swizzle column, taken over once the V load of the
+  // tile before has gone out.
   unsigned fetch_k[C::PASSES], fetch_v[C::PASSES];   // byte offsets from Kg / Vg
-  unsigned char* fetch_dst = smem;
-  auto fetch_begin = [&](int t, int stage) __attribute__((always_inline)) {
+  unsigned char* fetch_dst_k = smem;
+  unsigned char* fetch_dst_v = smem;
+  auto fetch_begin = [&](int u) __attribute__((always_inline)) {
     if (!is_loader) return;
-    locate(t);
-    fetch_dst = smem + stage * 2 * C::TILE_BYTES + wave_u * 1024;
+    locate(u);
+    fetch_dst_k = smem + (u & 3) * 2 * C::TILE_BYTES + wave_u * 1024;
+    fetch_dst_v = smem + ((u - 1) & 3) * 2 * C::TILE_BYTES + C::TILE_BYTES + wave_u * 1024;
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
       const unsigned row_off = __umul24(tokk[i] == INT_MAX ? 0u : static_cast<unsigned>(tokk[i]), row_bytes);   // both below 2^24 (host check)
       fetch_k[i] = row_off + k_col;
-      fetch_v[i] = row_off + v_col;
-      s_tok[stage][fr + C::RPP * i] = tokk[i];    // the UNITS lanes of a row write the same value
+      s_tok[u & 3][fr + C::RPP * i] = tokk[i];    // the UNITS lanes of a row write the same value
     }
   };
-  auto fetch_piece = [&](int j) __attribute__((always_inline)) {
+  auto fetch_piece = [&](int j, bool with_v = true) __attribute__((always_inline)) {
     const int i = j >> 1;
     if (!is_loader) return;
-    if (j & 1) dma16(Vg, fetch_v[i], fetch_dst + C::TILE_BYTES + i * C::LOADERS * 16);
-    else dma16(Kg, fetch_k[i], fetch_dst + i * C::LOADERS * 16);
+    if (j & 1) {
+      if (with_v) dma16(Vg, fetch_v[i], fetch_dst_v + i * C::LOADERS * 16);
+      fetch_v[i] = fetch_k[i] + (v_col - k_col);       // tile u, for the next round (unsigned wrap-around is exact)
+    } else {
+      dma16(Kg, fetch_k[i], fetch_dst_k + i * C::LOADERS * 16);
+    }
   };
-  auto fetch = [&](int t, int stage) __attribute__((always_inline)) {
-    fetch_begin(t, stage);
+  auto fetch_round = [&](int u, bool with_v) __attribute__((always_inline)) {
+    fetch_begin(u);
 #pragma unroll
-    for (int j = 0; j < 2 * C::PASSES; ++j) fetch_piece(j);
+    for (int j = 0; j < 2 * C::PASSES; ++j) fetch_piece(j, with_v);
   };
   // wait until at most `newest` of this wave's tile fetches (each 2*PASSES loads) are still in flight
   auto wait_fetches = [&](auto newest) __attribute__((always_inline)) {
@@ -436,6 +468,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   int m_idx = 0;
   int m_cur_lo = __builtin_amdgcn_readfirstlane(m_lo[0]), m_cur_hi = __builtin_amdgcn_readfirstlane(m_hi[0]);
   auto mask = [&](int t, f32x16 (&S)[NS][2]) __attribute__((always_inline)) {
+    if (__builtin_expect(t < m_cur_lo, 1)) return;     // one compare on the common path (m_cur_lo <= m_cur_hi)
     while (t > m_cur_hi) {     // t only grows; the last run never ends
       ++m_idx;
       m_cur_lo = __builtin_amdgcn_readfirstlane(m_lo[m_idx]);
@@ -543,10 +576,13 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
       lds_read_tr_b64<gg * 16 * D * 2 + 8 * D * 2>(fh[slot], vadr[db] + base_v);
     }
   };
-  // LDS read instructions issued after those of fragment f and before its wait (the counter holds 15)
+  // The fragment stream never drains: after the last K fragment of a tile come the V^T fragments of
+  // the next second product, after those the K fragments of the next score tile.  LDS read
+  // instructions issued after those of a fragment and before its wait = those of the PD - 1 fragments
+  // behind it in that cyclic order (one per K fragment, two per V^T fragment).
   auto younger = [](int f) constexpr {
     int n = 0;
-    for (int r = f + 1; r < f + PD && r < NF; ++r) n += r < NKF ? 1 : 2;
+    for (int r = f + 1; r < f + PD; ++r) n += (r % NF) < NKF ? 1 : 2;
     return n < 15 ? n : 15;
   };
   // ---- vector work dealt out to the matrix instructions of a body.  A matrix instruction keeps
@@ -585,82 +621,107 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
     }
   };
 
-  // ---- main loop over 64-key tiles.  Ring of four LDS stages filled by direct global->LDS loads:
-  // at the barrier that opens body t, tiles t and t+1 are complete, tile t+2 is in flight and the
-  // fetch of tile t+3 starts into the stage tile t-1 has left; before the closing barrier every
-  // wave waits for its part of tile t+2.
+  // ---- main loop over 64-key tiles.
   //
-  // Body t, entered with the masked scores S(t) and their row maxima (mx):
-  //   first the reads of the first fragments are issued and, while they are on their way, the
-  //   running max is raised if it has to be and the bookkeeping of the next tile fetch is done;
-  //   matrix stream:  S(t+1) = K(t+1) Q^T              then   O^T += V(t)^T P(t)^T
-  //   vector stream:  P(t) = exp2(S(t) c - m), most of it     the rest, mask and row maxima of S(t+1)
-  // Two score tiles alternate, so the loop is unrolled twice; an odd last body runs on a tile past
-  // the end, whose scores are all masked (its exponentials are 0, its maxima -inf).
+  // Body t, entered with the scores S(t+1) (complete but not yet masked), the first part of P(t)
+  // and the first V^T fragments of tile t on their way from LDS:
+  //   matrix stream:  O^T += V(t)^T P(t)^T                       then   S(t+2) = K(t+2) Q^T
+  //   vector stream:  rest of P(t), mask and row maxima of S(t+1);      running max, first part of P(t+1)
+  // and it ends at the one barrier of the tile.  Two score tiles alternate, so the loop is unrolled
+  // twice; bodies past the last tile work on scores that are all masked (exponentials 0, maxima
+  // -inf).  The loop boundary sits in the middle of the dependency chain on purpose: the barrier
+  // then falls where the fragments of the next matrix instructions are already in registers or on
+  // their way (they belong to tiles that were complete a barrier ago), so the matrix stream runs
+  // across it, instead of restarting from an empty pipeline after every barrier.
   //
-  // Two wavefronts share a SIMD, and when both have an instruction ready the arbiter always takes
-  // the one of the wavefront that was launched first: left alone, the first four wavefronts finish
-  // a body in 2 700 cycles and wait 700 at the barrier while the other four, which got what issue
-  // slots were left, take 3 300.  So the later four run at priority 1 throughout, and the first
-  // four at priority 1 (where the tie goes to them) for the first half of a body and at 0 for the
-  // rest; both groups then reach the barrier within about a hundred cycles of each other.
-  constexpr bool kBalance = NW == 8;
-  const bool first_on_simd = wave_u < 4;
-  if (kBalance && !first_on_simd) __builtin_amdgcn_s_setprio(1);
+  // Tile ring (four stages, K half and V half used independently).  K(u) is read in the second half
+  // of body u-2, V(u) in the first half of body u (its first fragments at the end of body u-1).
+  // Body t, after the barrier that opens it, starts fetch round t+4: K(t+4) - into the stage K(t)
+  // left in body t-2 - and V(t+3) - into the stage V(t-1) left in body t-1, which every wavefront
+  // has finished, having passed the barrier.  Before a barrier every wavefront waits for its loads
+  // of all rounds but the newest, so at the barrier that opens body t the rounds up to t+2 are
+  // complete: K up to t+2 and V up to t+1, which is what body t reads.
+  //
+  // The wavefronts of a SIMD share its issue slots, and when several have an instruction ready the
+  // arbiter always takes the one that was launched first: left alone, the first four wavefronts
+  // of the workgroup finish a body in 2 700 cycles and wait 700 at the barrier while the other four,
+  // which got what slots were left, take 3 300.  So every wavefront lowers its own priority as it
+  // moves through a body (3, 2, 1, 0 by quarters): whoever is behind outranks whoever is ahead, and
+  // all reach the barrier within about a hundred cycles of each other.  No branch is involved.
   constexpr std::integral_constant<int, 1> one_in_flight{};
-  auto body = [&](int t, f32x16 (&S_cur)[NS][2], f32x16 (&S_next)[NS][2]) __attribute__((always_inline)) {
-    if (kBalance && first_on_simd) __builtin_amdgcn_s_setprio(1);
-    const unsigned base_v = (t & 3) * STAGE_BYTES, base_k = ((t + 1) & 3) * STAGE_BYTES;
-    static_for<PD>([&](auto f) __attribute__((always_inline)) { issue(f, base_k, base_v); });
-    raise_max();                                  // of S_cur; also fills the time the first fragments take to arrive
-    fetch_begin(t + 3, (t + 3) & 3);
+  // fragment g of the cyclic stream that starts with the V^T fragments of tile tv and goes on with the K fragments of tile tk
+  auto issue_cyc = [&](auto gg_, unsigned base_k, unsigned base_v) __attribute__((always_inline)) {
+    constexpr int G = decltype(gg_)::value;
+    if constexpr (G < NVF) issue(std::integral_constant<int, NKF + G>{}, base_k, base_v);
+    else issue(std::integral_constant<int, G - NVF>{}, base_k, base_v);
+  };
+  // Second product of tile t: S_cur = S(t), S_next = S(t+1).  Its trailing reads are the first K fragments of tile t+2.
+  auto pv_half = [&](int t, f32x16 (&S_cur)[NS][2], f32x16 (&S_next)[NS][2]) __attribute__((always_inline)) {
+    const unsigned base_k = ((t + 2) & 3) * STAGE_BYTES, base_v = (t & 3) * STAGE_BYTES;
+    static_for<NVF>([&](auto gg_) __attribute__((always_inline)) {
+      constexpr int G = decltype(gg_)::value, F = NKF + G, slot = F % PD, W = younger(F);
+      constexpr int gg = G / DB, db = G % DB;
+      if constexpr (2 * G == NVF) __builtin_amdgcn_s_setprio(2);
+      if constexpr (G == 1) fetch_begin(t + 4);
+      if constexpr (db == 0) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) fence_p(pf[s][gg]);
+      }
+      if constexpr (NS * G == VS) {
+        // the scores of tile t+1 are complete (several matrix instructions of the second product lie between)
+        fence_scores(S_next);
+        mask(t + 1, S_next);
+      }
+      const u32x4 av = {fl[slot][0], fl[slot][1], fh[slot][0], fh[slot][1]};
+      static_for<NS>([&](auto ss) __attribute__((always_inline)) {
+        constexpr int s = decltype(ss)::value, WW = s == 0 ? W : -1;     // the first strip's instruction waits for the fragment
+        mfma_o<ACC, WW>(o[s][db], av, pf[s][gg]);
+        vector_slot(std::integral_constant<int, NS * F + s>{}, S_cur, S_next);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      issue_cyc(std::integral_constant<int, (G + PD) % NF>{}, base_k, base_v);
+      if constexpr ((G + 1) % FRAGS_PER_PIECE == 0) fetch_piece((G + 1) / FRAGS_PER_PIECE - 1);
+    });
+  };
+  // Scores of tile t2 into S_next while S_cur = S(t2-1) turns into P(t2-1).  PRIME: nothing is in
+  // flight yet (the first call).  Its trailing reads are the first V^T fragments of tile t2-1.
+  auto qk_half = [&](auto prime, int t2, f32x16 (&S_cur)[NS][2], f32x16 (&S_next)[NS][2]) __attribute__((always_inline)) {
+    constexpr bool PRIME = decltype(prime)::value;
+    const unsigned base_k = (t2 & 3) * STAGE_BYTES, base_v = ((t2 - 1) & 3) * STAGE_BYTES;
+    if constexpr (PRIME) static_for<PD>([&](auto f) __attribute__((always_inline)) { issue(f, base_k, base_v); });
+    else __builtin_amdgcn_s_setprio(1);
+    raise_max();                                  // of S_cur
     static_for<PRE>([&](auto i) __attribute__((always_inline)) { exp_one(i, S_cur); });
     __builtin_amdgcn_sched_barrier(0);
-    static_for<NF>([&](auto ff) __attribute__((always_inline)) {
-      constexpr int F = decltype(ff)::value, slot = F % PD, W = younger(F);
-      if constexpr (kBalance && F == NF / 2) {
-        if (first_on_simd) __builtin_amdgcn_s_setprio(0);
-      }
-      if constexpr (F < NKF) {
-        constexpr int ks = F / 2, kb = F % 2;
-        static_for<NS>([&](auto ss) __attribute__((always_inline)) {
-          constexpr int s = decltype(ss)::value, WW = s == 0 ? W : -1;     // the first strip's instruction waits for the fragment
-          if constexpr (ks == 0) mfma_s_first<ACC, WW>(S_next[s][kb], fk[slot], qf[s][0]);
-          else mfma_s<ACC, WW>(S_next[s][kb], fk[slot], qf[s][ks]);
-          vector_slot(std::integral_constant<int, NS * F + s>{}, S_cur, S_next);
-          __builtin_amdgcn_sched_barrier(0);
-        });
-      } else {
-        constexpr int gg = (F - NKF) / DB, db = (F - NKF) % DB;
-        if constexpr (db == 0) {
-#pragma unroll
-          for (int s = 0; s < NS; ++s) fence_p(pf[s][gg]);
-        }
-        if constexpr (NS * (F - NKF) == VS) {
-          // the scores of tile t+1 are complete (several matrix instructions of the second product lie between)
-          fence_scores(S_next);
-          mask(t + 1, S_next);
-        }
-        const u32x4 av = {fl[slot][0], fl[slot][1], fh[slot][0], fh[slot][1]};
-        static_for<NS>([&](auto ss) __attribute__((always_inline)) {
-          constexpr int s = decltype(ss)::value, WW = s == 0 ? W : -1;
-          mfma_o<ACC, WW>(o[s][db], av, pf[s][gg]);
-          vector_slot(std::integral_constant<int, NS * F + s>{}, S_cur, S_next);
-          __builtin_amdgcn_sched_barrier(0);
-        });
-      }
-      if constexpr (F + PD < NF) issue(std::integral_constant<int, F + PD>{}, base_k, base_v);
-      if constexpr ((F + 1) % FRAGS_PER_PIECE == 0) fetch_piece((F + 1) / FRAGS_PER_PIECE - 1);
+    static_for<NKF>([&](auto ff) __attribute__((always_inline)) {
+      constexpr int F = decltype(ff)::value, slot = F % PD, W = younger(F), G = NVF + F;
+      constexpr int ks = F / 2, kb = F % 2;
+      if constexpr (!PRIME && 2 * F == NKF) __builtin_amdgcn_s_setprio(0);
+      static_for<NS>([&](auto ss) __attribute__((always_inline)) {
+        constexpr int s = decltype(ss)::value, WW = s == 0 ? W : -1;
+        if constexpr (ks == 0) mfma_s_first<ACC, WW>(S_next[s][kb], fk[slot], qf[s][0]);
+        else mfma_s<ACC, WW>(S_next[s][kb], fk[slot], qf[s][ks]);
+        vector_slot(std::integral_constant<int, NS * F + s>{}, S_cur, S_next);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      issue_cyc(std::integral_constant<int, (G + PD) % NF>{}, base_k, base_v);
+      if constexpr (!PRIME && (G + 1) % FRAGS_PER_PIECE == 0) fetch_piece((G + 1) / FRAGS_PER_PIECE - 1);
     });
+  };
+  auto body = [&](int t, f32x16 (&S_a)[NS][2], f32x16 (&S_b)[NS][2]) __attribute__((always_inline)) {
+    __builtin_amdgcn_s_setprio(3);
+    pv_half(t, S_a, S_b);
+    qk_half(std::false_type{}, t + 2, S_b, S_a);
     wait_fetches(one_in_flight);
     __syncthreads();
   };
 
   if (n_tiles > 0) {
-    fetch(0, 0);
-    fetch(1, 1);
-    fetch(2, 2);
-    wait_fetches(one_in_flight);
+    fetch_round(0, false);                   // rounds 0 .. 3: K(0 .. 3) and V(0 .. 2)
+    fetch_round(1, true);
+    fetch_round(2, true);
+    fetch_round(3, true);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
   }
   __syncthreads();
 
@@ -681,6 +742,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
     fence_scores(Sa);
     mask(0, Sa);
     static_for<16 * NS>([&](auto i) __attribute__((always_inline)) { max_step(i, Sa); });
+    qk_half(std::true_type{}, 1, Sa, Sb);
     for (int t = 0; t < n_tiles; t += 2) {
       body(t, Sa, Sb);
       body(t + 1, Sb, Sa);
@@ -689,6 +751,8 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
         for (int s = 0; s < NS; ++s) { l_run[s] += l_lo[s]; l_lo[s] = 0.f; }
       }
     }
+    // the first V^T fragments of a tile nobody will use are still on their way into registers
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fl[0]), "+v"(fl[1]), "+v"(fl[2]), "+v"(fl[3]), "+v"(fh[0]), "+v"(fh[1]), "+v"(fh[2]), "+v"(fh[3]));
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // no fetch may still be writing LDS when the workgroup ends
   if constexpr (PERSIST) __syncthreads();   //   or when any wavefront starts staging the next item there
@@ -759,7 +823,7 @@ hipError_t launch_variant(const AttnLaunch& p0, hipStream_t stream) {
   const int64_t items = tiles * p0.Hq * p0.batch;
   if (items == 0) return hipSuccess;
   if (items > INT_MAX) return hipErrorInvalidValue;
-  if constexpr (D == 64) {
+  if constexpr (D == 64 && NW == 8) {          // (twelve wavefronts leave no registers for the outer loop)
     if (p0.seg_ext[0] != nullptr) {            // all steps in one launch: persistent workgroups, one per CU
       int dev = 0, cus = 0;
       if (note_hip(hipGetDevice(&dev)) != hipSuccess ||
@@ -787,13 +851,16 @@ hipError_t launch_attn_bf16(const AttnLaunch& p, int d, hipStream_t stream) {
   if (d == 64) {
     // At d = 64 the kernel needs 160 registers, so three wavefronts fit a SIMD (twelve per
     // workgroup, 384 query rows): measured 5-15 % faster than eight when the query blocks fill
-    // 384-row tiles as well as 256-row tiles; 3 % more padding already eats the gain.
+    // 384-row tiles as well as 256-row tiles; 3 % more padding already eats the gain.  With all
+    // steps in one launch the eight-wavefront form runs as persistent workgroups, which is worth
+    // more than the third wavefront as long as a work item is short (up to 256 key tiles).
     int64_t rows8 = 0, rows12 = 0;
     for (int t = 0; t < p.n_tasks; ++t) {
       rows8 += (p.task[t].n_q + 255) / 256 * 256;
       rows12 += (p.task[t].n_q + 383) / 384 * 384;
     }
-    return rows12 * 100 <= rows8 * 101 ? launch_variant<64, 1, 12>(p, stream) : launch_variant<64, 1, 8>(p, stream);
+    const bool short_items = p.seg_ext[0] != nullptr && p.max_keys <= 256 * BN;
+    return rows12 * 100 <= rows8 * 101 && !short_items ? launch_variant<64, 1, 12>(p, stream) : launch_variant<64, 1, 8>(p, stream);
   }
   return hipErrorInvalidValue;
 }

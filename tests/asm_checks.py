@@ -4,10 +4,11 @@ The kernel issues its LDS operand reads as inline assembly and waits for them by
 lgkmcnt(N) placed in front of the matrix instruction that consumes the fragment).  The compiler does
 not know that the destination registers of such a read are still "in flight" after the read has been
 issued; the source keeps them live up to the wait, so a correct build never touches them in between.
-This module re-derives that property from the generated code: it walks the instruction stream, keeps
-the list of LDS instructions that may still be outstanding (LDS instructions of a wavefront complete
-in order, a wait for "at most N outstanding" retires all but the youngest N) and reports every
-instruction that reads or writes a register of an outstanding read.  It also reports register spills.
+This module re-derives that property from the generated code: it follows every path through the
+basic blocks, keeps the list of LDS instructions that may still be outstanding (LDS instructions of
+a wavefront complete in order, a wait for "at most N outstanding" retires all but the youngest N;
+the fragment stream of the loop runs across its back edge) and reports every instruction that reads
+or writes a register of an outstanding read.  It also reports register spills.
 """
 import os
 import re
@@ -39,7 +40,8 @@ def _regs(text):
 
 
 def kernels(asm):
-    """{kernel symbol: list of (line number, instruction text)} for every kernel of the module."""
+    """{kernel symbol: list of (line number, text)} for every kernel of the module: its instructions
+    and, as entries that end with a colon, the labels of its basic blocks."""
     out, name = {}, None
     for i, line in enumerate(asm.split("\n")):
         m = re.match(r"^(_Z\w+):", line)
@@ -53,28 +55,61 @@ def kernels(asm):
             name = None
             continue
         s = line.split(";")[0].strip()
-        if not s or s.startswith(".") or s.endswith(":"):
+        if not s or (s.startswith(".") and not s.endswith(":")):
             continue
         out[name].append((i + 1, s))
     return out
 
 
-def in_flight_violations(instructions):
-    """Instructions that touch a register of an LDS read that may not have landed yet."""
-    pending = []          # (destination registers, line) of possibly outstanding LDS instructions, oldest first
-    bad = []
+def _blocks(instructions):
+    """Basic blocks of an instruction list (labels are entries that end with a colon) with successors."""
+    blocks, cur = [], {"label": None, "ins": []}
     for line, s in instructions:
+        if s.endswith(":"):
+            blocks.append(cur)
+            cur = {"label": s[:-1], "ins": []}
+            continue
+        cur["ins"].append((line, s))
+        op = s.split()[0]
+        if op.startswith("s_cbranch") or op in ("s_branch", "s_endpgm", "s_setpc_b64"):
+            blocks.append(cur)
+            cur = {"label": None, "ins": []}
+    blocks.append(cur)
+    by_label = {b["label"]: k for k, b in enumerate(blocks) if b["label"] is not None}
+    for k, b in enumerate(blocks):
+        succ = []
+        last = b["ins"][-1][1] if b["ins"] else ""
+        op = last.split()[0] if last else ""
+        target = last.split()[-1] if last else ""
+        if op == "s_branch":
+            succ = [by_label[target]] if target in by_label else []
+        elif op in ("s_endpgm", "s_setpc_b64"):
+            succ = []
+        else:
+            if op.startswith("s_cbranch") and target in by_label:
+                succ.append(by_label[target])
+            if k + 1 < len(blocks):
+                succ.append(k + 1)
+        b["succ"] = succ
+    return blocks
+
+
+def _walk(ins, pending, bad):
+    """One basic block: `pending` = LDS instructions that may be outstanding at its entry, oldest
+    first, each (destination registers, line of issue).  Returns the list at its exit."""
+    pending = list(pending)
+    for line, s in ins:
         op = s.split()[0]
         operands = s[len(op):].split(",")
         if op.startswith("ds_read") or op.startswith("ds_bpermute") or op.startswith("ds_permute"):
             src = set().union(*[_regs(x) for x in operands[1:]]) if len(operands) > 1 else set()
             for regs, issued in pending:
                 if regs & src:
-                    bad.append((line, s, issued))
-            pending.append((_regs(operands[0]), line))
+                    bad.add((line, s, issued))
+            pending.append((frozenset(_regs(operands[0])), line))
             continue
         if op.startswith("ds_") or op.startswith("s_load") or op.startswith("s_buffer_load") or op == "s_memtime":
-            pending.append((set(), line))      # counts towards lgkmcnt, returns no vector register
+            pending.append((frozenset(), line))      # counts towards lgkmcnt, returns no vector register
             continue
         if op == "s_waitcnt":
             m = re.search(r"lgkmcnt\((\d+)\)", s)
@@ -87,8 +122,41 @@ def in_flight_violations(instructions):
         touched = _regs(s[len(op):])
         for regs, issued in pending:
             if regs & touched:
-                bad.append((line, s, issued))
-    return bad
+                bad.add((line, s, issued))
+    return pending[-64:]
+
+
+def in_flight_violations(instructions):
+    """Instructions that touch a register of an LDS read that may not have landed yet, along every
+    path through the code: the list of possibly outstanding reads at the entry of a basic block is
+    the merge over its predecessors, aligned at the youngest end (a wait for "at most N
+    outstanding" retires all but the youngest N), iterated until nothing changes."""
+    blocks = _blocks(instructions)
+    entry = [None] * len(blocks)
+    entry[0] = []
+    work = [0]
+    while work:
+        k = work.pop()
+        out = _walk(blocks[k]["ins"], entry[k], set())
+        for t in blocks[k]["succ"]:
+            if entry[t] is None:
+                merged = list(out)
+            else:
+                old, n = entry[t], max(len(entry[t]), len(out))
+                merged = []
+                for pos in range(n):              # position counted from the youngest end
+                    a = old[len(old) - 1 - pos] if pos < len(old) else (frozenset(), 1 << 30)
+                    b = out[len(out) - 1 - pos] if pos < len(out) else (frozenset(), 1 << 30)
+                    merged.append((a[0] | b[0], min(a[1], b[1])))
+                merged.reverse()
+            if entry[t] is None or merged != entry[t]:
+                entry[t] = merged
+                work.append(t)
+    bad = set()
+    for k, b in enumerate(blocks):
+        if entry[k] is not None:
+            _walk(b["ins"], entry[k], bad)
+    return sorted(bad)
 
 
 def spill_report(asm):
