@@ -56,34 +56,69 @@ def get_path(m):
     return [[(i + zt) % m for zt in z] for i in range(m)]
 
 
-def gen_cycles(paths, new_vertex):
-    """GenCycles of Algorithm 1 (reading R1): close every path through one extra vertex."""
-    return [[new_vertex] + list(p) for p in paths]
+def hub_cycles(m):
+    """GenCycles of Algorithm 1 (reading R1): the m paths of GetPath(m), each closed through one extra
+    vertex m ("hub").  Returned as successor maps {vertex: next vertex}; together they use every arc
+    of the complete directed graph on the m+1 vertices once."""
+    cycles = []
+    for path in get_path(m):
+        nxt = {a: b for a, b in zip(path, path[1:])}
+        nxt[m] = path[0]
+        nxt[path[-1]] = m
+        cycles.append(nxt)
+    return cycles
+
+
+def diverted_arc_head(n, i):
+    """Which arc of hub cycle i is taken out and led through rank n-1 instead: the head of that arc,
+    given as the number of hops from the hub along the cycle.  The four special cycles and the common
+    distance are the shift table of Algorithm 1 (k = n/4 - 1); they are the paper's data."""
+    k = n // 4 - 1
+    special = {0: 1, k + 1: 4 * k + 2, 2 * k + 2: 3, 3 * k + 2: 4 * k}
+    return special.get(i, 2 * k)
+
+
+def _listed_from(nxt, start):
+    ring, v = [], start
+    while True:
+        ring.append(v)
+        v = nxt[v]
+        if v == start:
+            return ring
 
 
 def hamilton_rings(n):
-    """K_n-decomposition: n-1 rings, each a list of the n ranks; ring[j] sends to ring[(j+1)%n]."""
+    """K_n-decomposition: n-1 rings, each a list of the n ranks; ring[j] sends to ring[(j+1)%n].
+
+    Built on successor maps.  The n-2 hub cycles on ranks 0..n-2 (hub = rank n-2) are each opened at
+    one arc a -> b, which becomes a -> n-1 -> b.  The arcs taken out are chosen (by the shift table)
+    so that they chain into a single path from the hub through all ranks 0..n-2; that path, closed
+    through rank n-1, is the last ring.  Every ring is listed starting at the rank that follows rank
+    n-1, so rank n-1 stands last.
+    """
     if n == 4:
         return _least_overlap_rings_k4()
     if n < 8 or n % 4 != 0:
         raise ValueError("Algorithm 1 is defined for n >= 8 with n % 4 == 0 (and the n = 4 stand-in)")
-    init_paths = get_path(n - 2)
-    init_cycles = gen_cycles(init_paths, n - 2)          # cycles on the n-1 vertices 0..n-2
-    k = n // 4 - 1
-    shifts = {0: 1, k + 1: 4 * k + 2, 2 * k + 2: 3, 3 * k + 2: 4 * k}
-    rotated = []
-    appender = {}
-    for i in range(n - 2):
-        shift = shifts.get(i, 2 * k)
-        row = [init_cycles[i][(j + shift) % (n - 1)] for j in range(n - 1)]
-        rotated.append(row)
-        # the arc that closes the rotated list is the one taken out of cycle i
-        appender[row[-1]] = row[0]
-    appender_list = [n - 2]
-    for _ in range(n - 2):
-        appender_list.append(appender[appender_list[-1]])
-    # the removed arcs form one more Hamiltonian path; every path is closed through vertex n-1
-    return [row + [n - 1] for row in rotated] + [appender_list + [n - 1]]
+    hub, new = n - 2, n - 1
+    rings, taken_out = [], {}
+    for i, nxt in enumerate(hub_cycles(n - 2)):
+        head = hub
+        for _ in range(diverted_arc_head(n, i)):
+            head = nxt[head]
+        tail = next(a for a, b in nxt.items() if b == head)
+        assert tail not in taken_out
+        taken_out[tail] = head
+        nxt = dict(nxt)
+        nxt[tail], nxt[new] = new, head
+        rings.append(_listed_from(nxt, head))
+    # the arcs taken out leave exactly one rank of 0..n-2 without a successor: it sends to rank n-1
+    loose = [v for v in range(n - 1) if v not in taken_out]
+    assert len(loose) == 1 and hub not in taken_out.values()
+    last = dict(taken_out)
+    last[loose[0]], last[new] = new, hub
+    rings.append(_listed_from(last, hub))
+    return rings
 
 
 def _least_overlap_rings_k4():
@@ -119,20 +154,24 @@ def multinode_rings(m, u):
 # ----------------------------------------------------------------------------------------------
 # Algorithm 2
 # ----------------------------------------------------------------------------------------------
-def routing_table(looping, d):
-    """mapping[u][v] = i when v follows (d=+1) or precedes (d=-1) u on ring i; -1 elsewhere.
+def ring_of_arc(rings):
+    """{(sender, receiver): ring id} over every arc of every ring.  When an arc lies on two rings
+    (possible only for the n=4 stand-in, reading R7) the lower ring id is kept."""
+    owner = {}
+    for i, ring in enumerate(rings):
+        for a, b in zip(ring, ring[1:] + ring[:1]):
+            owner.setdefault((a, b), i)
+    return owner
 
-    When an arc lies on two rings (possible only for the n=4 stand-in, reading R7) the lower ring id
-    is kept, which is why the rings are written from the highest id down.
-    """
-    n = len(looping[0])
-    mapping = [[-1] * n for _ in range(n)]
-    for i in reversed(range(len(looping))):
-        for j in range(n):
-            u = looping[i][j]
-            v = looping[i][(j + d) % n]
-            mapping[u][v] = i
-    return mapping
+
+def routing_table(rings, d):
+    """Algorithm 2 as a lookup: table[u][v] = the ring on which v follows u (d=+1: u sends to v) or
+    precedes u (d=-1: u receives from v); -1 where the two are not neighbours on any ring."""
+    n = len(rings[0])
+    owner = ring_of_arc(rings)
+    if d == +1:
+        return [[owner.get((u, v), -1) for v in range(n)] for u in range(n)]
+    return [[owner.get((v, u), -1) for v in range(n)] for u in range(n)]
 
 
 def out_mapping(looping):

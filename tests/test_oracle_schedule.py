@@ -89,9 +89,12 @@ def test_wrong_shift_breaks_the_decomposition(monkeypatch):
     """The shift table of Algorithm 1 matters: any other rotation of cycle 0 is caught."""
     good = sch.hamilton_rings(8)
     n = 8
-    cyc = sch.gen_cycles(sch.get_path(n - 2), n - 2)
+    nxt = sch.hub_cycles(n - 2)[0]
+    cyc0 = [n - 2]
+    while nxt[cyc0[-1]] != n - 2:
+        cyc0.append(nxt[cyc0[-1]])
     for wrong in (0, 2, 3):
-        row0 = [cyc[0][(j + wrong) % (n - 1)] for j in range(n - 1)] + [n - 1]
+        row0 = [cyc0[(j + wrong) % (n - 1)] for j in range(n - 1)] + [n - 1]
         assert not sch.is_decomposition([row0] + good[1:])
 
 
