@@ -444,9 +444,17 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   // swallows the many small ones that follow (each below half an ulp of it): with a million keys
   // and outlier scores that alone costs up to 1e-3 in lse.  The sum of 64 tiles is large enough to
   // register, and a large term sits in l_lo for 64 tiles at most.
-  float m_run[NS], l_run[NS], l_lo[NS];
+  // The second product sees P rounded to bf16 while l adds up the fp32 values, so a row that a few
+  // keys dominate would come out scaled by the rounding error of their probabilities: up to 2^-9 of
+  // its value, 0.01 where |v| reaches 5, on top of the final rounding of the output.  r_fix collects,
+  // per 64-key tile, what the rounding added to the largest probability each lane holds; the output
+  // is divided by l + r_fix, which cancels the error of every dominant key to first order (keys that
+  // dominate from the same 32 scores of a lane share one correction).  Summing all rounded
+  // probabilities would be exact, but v_dot2c_f32_bf16 is a half-rate instruction: 10 % of the
+  // vector port.  lse comes from l alone.
+  float m_run[NS], l_run[NS], l_lo[NS], r_fix[NS];
 #pragma unroll
-  for (int s = 0; s < NS; ++s) { m_run[s] = kNegBig; l_run[s] = 0.f; l_lo[s] = 0.f; }
+  for (int s = 0; s < NS; ++s) { m_run[s] = kNegBig; l_run[s] = 0.f; l_lo[s] = 0.f; r_fix[s] = 0.f; }
   const float c = p.scale * kLog2e;
   auto fence_o = [&]() __attribute__((always_inline)) {
     fence_o_first<ACC>(o[0][0]);
@@ -518,6 +526,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
         m_run[s] = m_cand[s];
         l_run[s] *= alpha;
         l_lo[s] *= alpha;
+        r_fix[s] *= alpha;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
 #pragma unroll
@@ -691,6 +700,11 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
     if constexpr (PRIME) static_for<PD>([&](auto f) __attribute__((always_inline)) { issue(f, base_k, base_v); });
     else __builtin_amdgcn_s_setprio(1);
     raise_max();                                  // of S_cur
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {                // what rounding adds to this lane's largest probability of the tile
+      const float p_top = fast_exp2(__builtin_fmaf(mx[s], c, -m_run[s]));
+      r_fix[s] += static_cast<float>(static_cast<__bf16>(p_top)) - p_top;
+    }
     static_for<PRE>([&](auto i) __attribute__((always_inline)) { exp_one(i, S_cur); });
     __builtin_amdgcn_sched_barrier(0);
     static_for<NKF>([&](auto ff) __attribute__((always_inline)) {
@@ -764,9 +778,9 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
     const float l_mine = l_run[s] + l_lo[s];
-    const float l_tot = l_mine + __shfl_xor(l_mine, 32);
+    const float l_tot = l_mine + __shfl_xor(l_mine, 32), r_tot = l_tot + (r_fix[s] + __shfl_xor(r_fix[s], 32));
     const bool seen = l_tot > 0.f;
-    const float inv = seen ? 1.f / l_tot : 0.f;
+    const float inv = seen && r_tot > 0.f ? 1.f / r_tot : 0.f;
     float lse_new = seen ? (m_run[s] + __builtin_amdgcn_logf(l_tot)) * kLn2 : -__builtin_inff();
     if (q_valid[s]) {
       const int64_t grow = T.q_row0 + my_q[s];

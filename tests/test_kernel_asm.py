@@ -1,6 +1,7 @@
 """The generated code of the bf16 attention kernel keeps the hand-placed LDS waits valid (CPU only:
 hipcc cross-compiles to assembly without a GPU)."""
 import os
+import re
 import shutil
 
 import pytest
@@ -15,6 +16,12 @@ pytestmark = pytest.mark.skipif(shutil.which(os.environ.get("HIPCC", "/opt/rocm/
 def attn_asm(tmp_path_factory):
     out = tmp_path_factory.mktemp("asm") / "attn_bf16.s"
     return asm_checks.compile_to_asm("attn_bf16.hip", str(out))
+
+
+@pytest.fixture(scope="module")
+def bwd_asm(tmp_path_factory):
+    out = tmp_path_factory.mktemp("asm") / "attn_bwd_bf16.s"
+    return asm_checks.compile_to_asm("attn_bwd_bf16.hip", str(out))
 
 
 def test_checker_flags_a_planted_violation():
@@ -63,13 +70,41 @@ def test_no_spills_in_the_loop(attn_asm):
     assert asm_checks.scratch_in_loops(attn_asm, "ELb1EEEvNS_10AttnLaunch", min_depth=2) == []
 
 
+def _m0_misuse(instructions):
+    """Instructions that name m0 outside the one pattern the direct global->LDS load uses (its asm
+    statement: s_mov_b32 m0, <sgpr> / s_nop 0 / global_load_lds_dwordx4), and loads without it."""
+    ins = [(line, s) for line, s in instructions if not s.endswith(":")]
+    bad = []
+    for k, (line, s) in enumerate(ins):
+        op = s.split()[0]
+        if re.search(r"\bm0\b", s):
+            ok = (op == "s_mov_b32" and s.split()[1].rstrip(",") == "m0" and k + 2 < len(ins)
+                  and ins[k + 1][1] == "s_nop 0" and ins[k + 2][1].startswith("global_load_lds_dwordx4"))
+            if not ok:
+                bad.append((line, s))
+        if op.startswith("global_load_lds") and not (k >= 2 and ins[k - 2][1].startswith("s_mov_b32 m0,") and ins[k - 1][1] == "s_nop 0"):
+            bad.append((line, s))
+    return bad
+
+
+def test_m0_checker_flags_planted_uses():
+    good = [(1, "s_mov_b32 m0, s4"), (2, "s_nop 0"), (3, "global_load_lds_dwordx4 v1, s[2:3]")]
+    assert _m0_misuse(good) == []
+    assert [b[0] for b in _m0_misuse(good + [(4, "v_readlane_b32 s5, v2, m0")])] == [4]
+    assert [b[0] for b in _m0_misuse([(1, "s_mov_b32 m0, s4"), (2, "v_mov_b32_e32 v0, v1"), (3, "global_load_lds_dwordx4 v1, s[2:3]")])] == [1, 3]
+
+
+def test_m0_belongs_to_the_direct_loads_only(attn_asm, bwd_asm):
+    """The asm statement of the direct global->LDS load writes m0 without declaring it.  That is
+    sound as long as the compiler itself never keeps a value in m0: in the generated code of every
+    kernel that uses these loads, m0 appears in that statement's three instructions and nowhere else."""
+    for asm in (attn_asm, bwd_asm):
+        for name, ins in asm_checks.kernels(asm).items():
+            if any(s.startswith("global_load_lds") for _, s in ins):
+                assert _m0_misuse(ins) == [], (name, _m0_misuse(ins)[:3])
+
+
 # ---------------------------------------------------------------- backward kernels (compiler-scheduled)
-@pytest.fixture(scope="module")
-def bwd_asm(tmp_path_factory):
-    out = tmp_path_factory.mktemp("asm") / "attn_bwd_bf16.s"
-    return asm_checks.compile_to_asm("attn_bwd_bf16.hip", str(out))
-
-
 def test_backward_kernels_shape_and_register_budget(bwd_asm):
     """Six instantiations (the dk/dv kernel also split by query head); each reads its LDS tiles with LDS instructions (no flat loads: the address
     space was inferred), fills them with direct global->LDS loads, fits the 256 registers that let two
