@@ -11,8 +11,10 @@
  *
  * Conventions
  *   - Every function returns TASP_OK (0) or a negative tasp_status.  Nothing throws, aborts or prints.
- *   - "host" / "device" is stated for every pointer.  The library never allocates device memory and
- *     keeps no global state; device work is enqueued on the caller's HIP stream and is asynchronous.
+ *   - "host" / "device" is stated for every pointer.  The library never allocates device memory;
+ *     device work is enqueued on the caller's HIP stream and is asynchronous.  Its only state
+ *     outside the objects it hands out: per thread, the last HIP error it met (tasp_last_hip_error),
+ *     and per GPU the fixed scratch array of tasp_chunk_attn_static.
  *   - Tensors are dense, row-major, with the last index fastest.
  *   - Token positions are global positions in [0, S).
  */
@@ -139,15 +141,17 @@ int tasp_step_segments(const tasp_schedule_t* s, int64_t S, int32_t mask_mode, i
  *                 running max / sum / output across them, so no partial pair is ever written or
  *                 merged (the log-sum-exp rescale happens in registers).  For callers whose K and V
  *                 are resident when the call is made; it removes the per-step launch, set-up and
- *                 merge costs, which dominate for short sequences.  bf16 only, at most
+ *                 merge costs, which dominate for short sequences.  At most
  *                 TASP_MAX_FUSED_SEGMENTS visible segments per query block over all steps
  *                 (otherwise TASP_EUNSUPPORTED_SHAPE); fuse_merge is ignored.
  *   batch    B independent sequences handled in one call (0 counts as 1, at most 65535): every
  *            tensor gets a leading dimension, q/out [B, L, Hq, d], k/v [B, S, Hkv, d], lse
  *            [B, L, Hq]; all sequences share S, the schedule and the mask (the shape grid of the
  *            paper's evaluation, Sec. 5.1, has batches of up to 128 sequences).
- * Supported: d in {64, 128}; N <= 32; S < 2^31; for bf16 also S < 2^24 and S*Hkv*d*2 <= 2^32 bytes
- * (K and V are addressed with 32-bit offsets).  All device pointers 16-byte aligned.
+ * Supported: d in {64, 128}; schedules of at most 32 rings (N <= 33 ranks with tasp_schedule_create;
+ * with tasp_schedule_create_multinode up to 32 ranks per node and any N it accepts - a call
+ * enqueues N steps); S < 2^31; for bf16 also S < 2^24 and S*Hkv*d*2 <= 2^32 bytes (K and V are
+ * addressed with 32-bit offsets).  All device pointers 16-byte aligned.
  * The call only enqueues work on `hip_stream` (a hipStream_t, NULL = default stream); results are
  * valid once the stream has been synchronised.
  * ---------------------------------------------------------------------------------------------- */

@@ -56,7 +56,6 @@ int validate(const tasp_schedule_t* s, const tasp_attn_args* a, Shape* sh) {
   if (2 * s->n_rings > tasp::kMaxSeg) return TASP_EUNSUPPORTED_SHAPE;
   if (a->batch < 0 || a->batch > 65535) return TASP_EINVAL;
   if (a->fuse_steps != 0 && a->fuse_steps != 1) return TASP_EINVAL;
-  if (a->fuse_steps && a->dtype != TASP_DTYPE_BF16) return TASP_EUNSUPPORTED_SHAPE;
   if ((reinterpret_cast<uintptr_t>(a->q) | reinterpret_cast<uintptr_t>(a->k) | reinterpret_cast<uintptr_t>(a->v)) & 15)
     return TASP_EALIGN;
   sh->L = a->S / s->n;
@@ -213,6 +212,7 @@ int validate_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args* b, tasp_att
   *a = as_forward(b);
   int st = validate(s, a, sh);
   if (st != TASP_OK) return st;
+  if (b->fuse_steps && b->dtype != TASP_DTYPE_BF16) return TASP_EUNSUPPORTED_SHAPE;   // the plain fp32 backward path walks step by step
   if (b->out == nullptr || b->lse == nullptr || b->dout == nullptr || b->dq == nullptr || b->dk == nullptr ||
       b->dv == nullptr)
     return TASP_EINVAL;

@@ -54,9 +54,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_fp32_kernel(const AttnLaunch 
 #pragma unroll
   for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
 
+  // with all steps in one launch the list comes from device memory; the running max / sum / output
+  // simply carry on across the steps
+  const int32_t* ext = p.seg_ext[tsk];
   for (int s = 0; s < T.n_seg; ++s) {
-    const int a = T.seg_start[s];
-    int b = T.seg_end[s];
+    const int a = ext != nullptr ? ext[2 * s] : T.seg_start[s];
+    int b = ext != nullptr ? ext[2 * s + 1] : T.seg_end[s];
     if (p.causal) b = min(b, q_pos + 1);             // key t is visible iff t <= q_pos
     for (int t0 = a; t0 < b; t0 += 64) {
       const int t = t0 + lane;

@@ -14,11 +14,15 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int MERGE_THREADS = 256;
 
-// One thread per 4 output columns of one (row, head).  n4 = rows*heads*d/4, pieces = d/4.
+// One thread per 4 output columns of one (row, head).  n4 = rows*heads*d/4, pieces = d/4.  The
+// second grid dimension walks the sequences of a batch (the same row range of each): bstride_rh =
+// (row, head) pairs from one sequence to the next.
 __global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(float* __restrict__ o_acc, float* __restrict__ lse_acc,
                                                              const float* __restrict__ o_part,
                                                              const float* __restrict__ lse_part, int64_t n4,
-                                                             int32_t pieces) {
+                                                             int32_t pieces, int64_t bstride_rh) {
+  const int64_t boff = static_cast<int64_t>(blockIdx.y) * bstride_rh;
+  o_acc += boff * pieces * 4; o_part += boff * pieces * 4; lse_acc += boff; lse_part += boff;
   const int64_t stride = static_cast<int64_t>(gridDim.x) * MERGE_THREADS;
   for (int64_t i = static_cast<int64_t>(blockIdx.x) * MERGE_THREADS + threadIdx.x; i < n4; i += stride) {
     const int64_t rh = i / pieces;
@@ -63,12 +67,23 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_many_kernel(float* __rest
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     float den = 0.f;
     if (mx != -__builtin_inff()) {
-      for (int p = 0; p < n_parts; ++p) {
-        const float w = __expf(parts.lse[p][rh] - mx);        // the second read of lse hits the cache
-        const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(parts.o[p]) + i);
-        den += w;
+      // eight partials at a time: all their 16-byte loads are requested before the first one is used,
+      // so a thread keeps eight loads in flight instead of one behind a dependent chain
+      for (int p0 = 0; p0 < n_parts; p0 += 8) {
+        f32x4 b[8];
+        float w[8];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(w, b[e], acc[e]);
+        for (int k = 0; k < 8; ++k) {
+          const int p = p0 + k < n_parts ? p0 + k : n_parts - 1;        // a repeat of the last one, weight 0
+          b[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(parts.o[p]) + i);
+          w[k] = p0 + k < n_parts ? __expf(parts.lse[p][rh] - mx) : 0.f;  // the second read of lse hits the cache
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          den += w[k];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[e] = __builtin_fmaf(w[k], b[k][e], acc[e]);
+        }
       }
       const float rden = 1.f / den;
 #pragma unroll
@@ -82,7 +97,9 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_many_kernel(float* __rest
 }
 
 __global__ __launch_bounds__(MERGE_THREADS) void fill_empty_kernel(float* __restrict__ o, float* __restrict__ lse,
-                                                                  int64_t n4, int32_t pieces) {
+                                                                  int64_t n4, int32_t pieces, int64_t bstride_rh) {
+  o += static_cast<int64_t>(blockIdx.y) * bstride_rh * pieces * 4;
+  lse += static_cast<int64_t>(blockIdx.y) * bstride_rh;
   const int64_t stride = static_cast<int64_t>(gridDim.x) * MERGE_THREADS;
   for (int64_t i = static_cast<int64_t>(blockIdx.x) * MERGE_THREADS + threadIdx.x; i < n4; i += stride) {
     reinterpret_cast<f32x4*>(o)[i] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -123,28 +140,21 @@ hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const
                         hipStream_t stream) {
   if (rows <= 0) return hipSuccess;
   if (rows == L) { rows *= batch; batch = 1; }       // whole sequences: one contiguous range
-  const int64_t n4 = rows * heads * (d / 4);
-  for (int32_t b = 0; b < batch; ++b) {
-    const int64_t off = (b * L + row0) * heads;
-    const hipError_t e = TASP_LAUNCH(merge_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), stream, o_acc + off * d,
-                                     lse_acc + off, o_part + off * d, lse_part + off, n4, d / 4);
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
+  if (batch < 1 || batch > 65535) return hipErrorInvalidValue;
+  const int64_t n4 = rows * heads * (d / 4), off = row0 * heads;
+  // one launch for the whole batch: the second grid dimension walks the sequences
+  return TASP_LAUNCH(merge_kernel, dim3(grid_for(n4), static_cast<unsigned>(batch)), dim3(MERGE_THREADS), stream,
+                     o_acc + off * d, lse_acc + off, o_part + off * d, lse_part + off, n4, d / 4, L * heads);
 }
 
 hipError_t launch_fill_empty(float* o, float* lse, int64_t row0, int64_t rows, int32_t heads, int32_t d,
                              int32_t batch, int64_t L, hipStream_t stream) {
   if (rows <= 0) return hipSuccess;
   if (rows == L) { rows *= batch; batch = 1; }
-  const int64_t n4 = rows * heads * (d / 4);
-  for (int32_t b = 0; b < batch; ++b) {
-    const int64_t off = (b * L + row0) * heads;
-    const hipError_t e = TASP_LAUNCH(fill_empty_kernel, dim3(grid_for(n4)), dim3(MERGE_THREADS), stream, o + off * d,
-                                     lse + off, n4, d / 4);
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
+  if (batch < 1 || batch > 65535) return hipErrorInvalidValue;
+  const int64_t n4 = rows * heads * (d / 4), off = row0 * heads;
+  return TASP_LAUNCH(fill_empty_kernel, dim3(grid_for(n4), static_cast<unsigned>(batch)), dim3(MERGE_THREADS), stream,
+                     o + off * d, lse + off, n4, d / 4, L * heads);
 }
 
 hipError_t launch_cast_bf16(const float* src, void* dst, int64_t n, hipStream_t stream) {

@@ -27,7 +27,7 @@ def oracle_rows(w, q, k, v, rows, heads=None):
     return out, lse
 
 
-def oracle_grads(w, q, k, v, dout, rows=None, out=None):
+def oracle_grads(w, q, k, v, dout, rows=None, out=None, progress=None):
     """Dense fp64 gradients (oracle) of sum(dout * out) for workload w, all heads; `rows` restricts the
     local query rows that take part (the gradient is linear in dout, so this equals zeroing dout
     elsewhere); `out` [L, Hq, d] is the stored forward output delta is taken from (None: the exact
@@ -47,6 +47,8 @@ def oracle_grads(w, q, k, v, dout, rows=None, out=None):
         dq[:, h] = a
         dk[:, g] += b
         dv[:, g] += c
+        if progress is not None and (h + 1) % 8 == 0:
+            progress("oracle: %d of %d heads" % (h + 1, w.Hq))
     return dq, dk, dv
 
 

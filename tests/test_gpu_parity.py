@@ -104,11 +104,33 @@ def test_small_all_rows_single_launch(tb, case):
         check(w, out, lse, ref_o, ref_l, rows)
 
 
-def test_single_launch_refuses_what_it_cannot_do(tb):
-    w = wl.CONFIGS[0]                                    # fp32
+SMALL_FP32 = [c for c in SMALL if c[0].startswith("fp32")]
+
+
+@pytest.mark.parametrize("case", [("cfg1",)] + SMALL_FP32, ids=["cfg1"] + [c[0] for c in SMALL_FP32])
+def test_fp32_single_launch_all_rows(tb, case):
+    """fuse_steps with fp32 inputs: workload 1 (four launches become one) and the small fp32 cases."""
+    if case[0] == "cfg1":
+        w = wl.CONFIGS[0]
+    else:
+        name, base, n, rank, S, Hq, Hkv, d = case
+        w = wl.Workload(name, n, rank, S, Hq, Hkv, d, "fp32", wl.ZIGZAG_CAUSAL if "_zz_" in name else wl.FULL,
+                        seed=wl.CONFIGS[base].seed + 100)
+    q, k, v = wl.make_qkv(w)
+    rows = list(range(w.L))
+    ref_o, ref_l = oracle_rows(w, q, k, v, rows)
+    for kw in ({}, {"order": tb.ORDER_RING}):
+        out, lse = run_gpu(tb, w, q, k, v, fuse_steps=True, **kw)
+        check(w, out, lse, ref_o, ref_l, rows)
+
+
+def test_backward_single_launch_refuses_fp32(tb):
+    w = wl.CONFIGS[0]                                    # fp32: the plain backward path walks step by step
     q, k, v = (x.cuda() for x in wl.make_qkv(w))
+    s = tb.tasp_schedule(w.n_ranks, w.rank)
+    out, lse = tb.tasp_chunk_attn(q, k, v, s, w.mask_mode)
     with pytest.raises(tb.TaspError) as e:
-        tb.tasp_chunk_attn(q, k, v, tb.tasp_schedule(w.n_ranks, w.rank), w.mask_mode, fuse_steps=True)
+        tb.tasp_chunk_attn_bwd(q, k, v, out, lse, torch.ones_like(q), s, w.mask_mode, fuse_steps=True)
     assert e.value.status == tb.EUNSUPPORTED_SHAPE
 
 
@@ -362,17 +384,38 @@ def test_full_size_multinode_8x2_sampled_rows(tb):
     assert np.all(np.isfinite(lse)) and np.all(np.isfinite(out))
 
 
-FULL_SIZE = [(1, 24, 96), (2, 16, 48), (3, 12, 32), (4, 8, 24)]
+# (workload index, random rows checked on every head, random rows checked on one head per KV group);
+# on top of these come the tile-edge rows of sample_rows and the rows next to sub-chunk bounds
+FULL_SIZE = [(1, 64, 1024), (2, 64, 1024), (3, 32, 512), (4, 48, 768)]
+
+
+def subchunk_edge_rows(w):
+    """Local rows whose own position sits at a bound of a sub-chunk of the rank's own chunk (the last
+    row of a piece and the first of the next, eq. (3), (5), (6)): there the causal diagonal and a
+    segment bound of step 0 coincide."""
+    pos = np.asarray(sch.local_positions(w.n_ranks, w.rank, w.S, w.mask_mode), dtype=np.int64)
+    local_of = {int(p): i for i, p in enumerate(pos)}
+    rows = set()
+    for ring in range(w.n_ranks - 1):
+        for a, b in sch.subchunk_ranges(w.n_ranks, w.S, w.mask_mode, ring, w.rank):
+            for p in (a - 1, a, b - 1, b):
+                if p in local_of:
+                    rows.add(local_of[p])
+    return sorted(rows)
 
 
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("idx,n_all_heads,n_one_head", FULL_SIZE, ids=[wl.CONFIGS[i[0]].name for i in FULL_SIZE])
-def test_full_size_sampled_rows(tb, idx, n_all_heads, n_one_head):
+def test_full_size_sampled_rows(tb, capsys, idx, n_all_heads, n_one_head):
     """The launch configuration the benchmark times, checked on sampled rows the oracle computes one
-    by one: tile-edge and half-chunk-edge rows plus seeded random rows; every head on the first set,
-    one head per KV group on a larger set."""
+    by one: tile-edge and half-chunk-edge rows plus seeded random rows on every head; those, the rows
+    at the bounds of the rank's own sub-chunks and a larger random set on one head per KV group.
+    Random rows: 64 + 1024 for the 128K and 256K workloads, 32 + 512 at 512K (64 query heads),
+    48 + 768 at 1M (the oracle is dense fp64 over all keys of every sampled row)."""
     w = wl.CONFIGS[idx]
-    say = lambda msg: print("[%s] %s" % (w.name, msg), flush=True)
+    def say(msg):            # progress past pytest's capture: a silent minute reads as a hang on the GPU box
+        with capsys.disabled():
+            print("[%s] %s" % (w.name, msg), flush=True)
     say("generating inputs")
     q, k, v = wl.make_qkv(w)
     s = tb.tasp_schedule(w.n_ranks, w.rank)
@@ -385,14 +428,19 @@ def test_full_size_sampled_rows(tb, idx, n_all_heads, n_one_head):
         results[fuse] = (out.float().cpu().numpy(), lse.cpu().numpy())
     del qd, kd, vd
     torch.cuda.empty_cache()
-    rows_a = wl.sample_rows(w, n_all_heads)[: n_all_heads + 8]
-    rows_b = wl.sample_rows(w, n_one_head, seed_offset=1)
+    rows_a = wl.sample_rows(w, n_all_heads)                     # tile-edge rows + n_all_heads random ones
+    edge = subchunk_edge_rows(w)
+    rows_b = sorted(set(wl.sample_rows(w, n_one_head, seed_offset=1)) | set(edge))
     G = w.Hq // w.Hkv
     heads_b = [g * G + (g % G) for g in range(w.Hkv)]
     say("oracle: %d rows x all heads" % len(rows_a))
     ref_a = oracle_rows(w, q, k, v, rows_a)
     say("oracle: %d rows x %d heads" % (len(rows_b), len(heads_b)))
-    ref_b = oracle_rows(w, q, k, v, rows_b, heads_b)
+    parts = []
+    for c0 in range(0, len(rows_b), 256):       # in pieces, with a progress line each
+        parts.append(oracle_rows(w, q, k, v, rows_b[c0:c0 + 256], heads_b))
+        say("  ... %d rows done" % min(len(rows_b), c0 + 256))
+    ref_b = (np.concatenate([x[0] for x in parts]), np.concatenate([x[1] for x in parts]))
     say("comparing")
     for fuse, (out, lse) in results.items():
         check(w, out, lse, ref_a[0], ref_a[1], rows_a)
