@@ -8,7 +8,11 @@ already resident in HBM.  Prints ONE JSON line.
 
 The timed call folds update_out_lse into the attention epilogue (fuse_merge, the faster of the two
 modes of the library); the same call with the separate HBM-bound merge kernel is timed next to it
-("other_merge_mode") and provides the merge kernel's GB/s ("merge").
+("other_merge_mode") and provides the merge kernel's GB/s ("merge").  `value` comes from the wall
+clock around the K timed calls (synchronised on both sides); "ms_per_step_median_events" is the
+median of the K calls timed one by one with HIP events on the launch stream.  With the default
+workload the line also carries "other_workloads": the same call on the 256K, 512K and 1M workloads
+(device-generated inputs of the same shapes and distributions, at most three timed calls each).
 """
 import argparse
 import json
@@ -23,6 +27,23 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3        # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0
+N_SIMD, CLOCK_HZ = 256 * 4, 2.4e9
+
+# The second bound of the bf16 attention kernel: the vector issue port of a SIMD.  Measured on this
+# chip with issue microbenchmarks: a matrix instruction occupies the port for 12 cycles, a plain
+# vector instruction for 4, an exponential for 8, and a KiB of LDS data returned to registers for 4.
+# Per 64-key tile and wavefront (32 queries) the kernel issues, on its common path, the counts below
+# (from the generated code); flops of that unit of work divided by its port cycles, times the chip's
+# SIMDs and the nominal clock, is the rate at which the port alone would let the kernel run.
+PORT_CYCLES = {"mfma": 12, "valu": 4, "exp": 8, "lds_kib": 4}
+TILE_MIX = {128: {"mfma": 32, "valu": 147, "exp": 32, "lds_kib": 32},
+            64: {"mfma": 16, "valu": 131, "exp": 32, "lds_kib": 16}}
+
+
+def valu_peak_tflops(d):
+    mix = TILE_MIX[d]
+    cycles = sum(PORT_CYCLES[k] * n for k, n in mix.items())
+    return 4.0 * d * 32 * 64 / cycles * N_SIMD * CLOCK_HZ / 1e12
 
 
 def cpu_baseline(w, q, k, v, budget_s=12.0):
@@ -67,7 +88,52 @@ def cpu_baseline(w, q, k, v, budget_s=12.0):
     }
 
 
+def other_workloads(tb, wl, torch, dev, order, args, t_start, cap_s=150.0):
+    """The forward call on the three larger workloads (256K, 512K, 1M): value and the attention
+    launch's fraction of the bf16 peak.  Inputs are drawn on the device (same shapes, dtypes and value
+    recipes as workloads.make_qkv: N(0,1), K x 2 for the 256K workload, 1 % of the key rows x 8 for
+    the 1M one; a seeded device generator instead of the CPU one, which would take minutes at 1M).
+    At most three timed calls each, and none is started once the bench has run for cap_s seconds."""
+    out = []
+    for idx in (2, 3, 4):
+        w = wl.CONFIGS[idx]
+        if time.perf_counter() - t_start > cap_s:
+            out.append({"workload": w.name, "skipped": "wall-clock cap of the bench reached"})
+            continue
+        g = torch.Generator(device=dev)
+        g.manual_seed(w.seed)
+        draw = lambda shape: torch.randn(shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        qd, kd, vd = draw((w.L, w.Hq, w.d)), draw((w.S, w.Hkv, w.d)), draw((w.S, w.Hkv, w.d))
+        if w.k_scale != 1.0:
+            kd *= w.k_scale
+        if w.outlier_frac > 0.0:
+            rows = torch.randperm(w.S, generator=g, device=dev)[: int(w.outlier_frac * w.S)]
+            kd[rows] *= w.outlier_scale
+        sched = tb.tasp_schedule_multinode(w.n_ranks // args.nodes, args.nodes, w.rank) if args.nodes > 1 else tb.tasp_schedule(w.n_ranks, w.rank)
+        plan = tb.ChunkAttnPlan(sched, qd, kd, vd, w.mask_mode, order=order, fuse_merge=True)
+        flops = plan.flops()
+        plan.run()
+        torch.cuda.synchronize()
+        steps = min(3, args.steps)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            plan.run()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        pr = plan.profile()
+        launch = flops / (pr.attn_ms * 1e-3) / 1e12
+        out.append({"workload": w.name, "S": w.S, "L": w.L, "Hq": w.Hq, "Hkv": w.Hkv, "d": w.d, "steps": steps,
+                    "ms_per_step": ms, "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s",
+                    "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": launch, "peak": PEAK_BF16_TFLOPS,
+                                 "frac": launch / PEAK_BF16_TFLOPS, "avg_launch_ms": pr.attn_ms / max(pr.attn_launches, 1),
+                                 "launches_per_call": pr.attn_launches}})
+        del plan, qd, kd, vd
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
+    t_start = time.perf_counter()
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
@@ -137,6 +203,15 @@ def main():
         plan.run()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    # the same K calls once more, each bracketed by HIP events on the launch stream: the median
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in ev:
+        e0.record()
+        plan.run()
+        e1.record()
+    torch.cuda.synchronize()
+    per_call = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    ms_median = per_call[len(per_call) // 2] if len(per_call) % 2 else 0.5 * (per_call[len(per_call) // 2 - 1] + per_call[len(per_call) // 2])
 
     # per-kernel durations, HIP events around every launch on the launch stream (same work again)
     n_prof = max(1, min(args.steps, 5))
@@ -152,21 +227,35 @@ def main():
     is_bf16 = w.dtype == "bf16"
     peak = PEAK_BF16_TFLOPS if is_bf16 else PEAK_FP32_TFLOPS
     attn_avg_ms = attn_ms / max(attn_n, 1)
-    flops_per_launch = flops / w.n_ranks                     # a launch = one step of Algorithm 3
+    # a launch = one step of Algorithm 3; the average launch does 1/launches of the call's flops
+    # whatever the order or the schedule (totals over totals)
+    flops_per_launch = flops / max(attn_n // n_prof, 1)
     achieved = flops_per_launch / (attn_avg_ms * 1e-3) / 1e12
     # HBM bytes per attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
     # the copy-kernel calibration); the figures live in paper_2509_26541_amd/hbm_traffic.json, the
     # summaries they come from in profiles/
+    # (null when the kernel source has changed since they were taken: the file records its hash)
     traffic = None
     tpath = os.path.join(ROOT, "paper_2509_26541_amd", "hbm_traffic.json")
-    if os.path.exists(tpath) and args.batch == 1 and args.nodes <= 1 and args.order == "tasp":   # what was profiled
+    if os.path.exists(tpath) and args.batch == 1 and args.nodes <= 1 and args.order == "tasp" and args.fuse_merge:   # what was profiled
+        import hashlib
+        with open(os.path.join(ROOT, "paper_2509_26541_amd", "csrc", "attn_bf16.hip"), "rb") as f:
+            sha = hashlib.sha256(f.read()).hexdigest()[:16]
         with open(tpath) as f:
-            traffic = json.load(f).get(w.name, {}).get("attn_bytes_per_launch")
+            rec = json.load(f).get(w.name, {})
+        if rec.get("attn_bf16_hip_sha16") == sha:
+            traffic = rec.get("attn_bytes_per_launch")
     roofline = {
         "bound": "mfma" if is_bf16 else "alu", "kernel": "attn_bf16_kernel" if is_bf16 else "attn_fp32_kernel",
         "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
         "avg_launch_ms": attn_avg_ms, "launches_per_call": attn_n // n_prof,
     }
+    # the vector issue port, the pipe that actually bounds the bf16 kernel (above all at d = 64)
+    roofline_valu = None
+    if is_bf16:
+        vp = valu_peak_tflops(w.d)
+        roofline_valu = {"bound": "valu", "kernel": "attn_bf16_kernel", "achieved": achieved, "peak": vp, "unit": "TFLOP/s",
+                         "frac": achieved / vp, "port_cycles": PORT_CYCLES, "per_tile_and_wavefront": TILE_MIX[w.d]}
     def merge_stats(ms_total, launches, calls):
         # update_out_lse: per (row, head) read 2(4d+4) and write 4d+4 bytes; rows merged per call =
         # all rows of every task of steps 1..N-1
@@ -321,6 +410,8 @@ def main():
                    "Hkv": w.Hkv, "d": w.d, "mask": "zigzag_causal" if w.mask_mode else "full",
                    "order": args.order, "rings": sched.n_rings, "batch": args.batch, "fuse_merge": int(args.fuse_merge), "flops_per_call": flops},
         "roofline": roofline,
+        "roofline_valu": roofline_valu,
+        "ms_per_step_median_events": ms_median,
         "merge": merge,
         "ms_breakdown": {"attn": attn_ms / n_prof, "merge": merge_ms / n_prof, "cast": other_ms / n_prof},
         "other_merge_mode": other,
@@ -328,9 +419,11 @@ def main():
         "merge_many": merge_many,
         "backward": backward,
     }
+    del plan, qd, kd, vd
+    torch.cuda.empty_cache()
+    if not args.grid and args.config == 2 and args.batch == 1 and not args.no_other_mode:
+        line["other_workloads"] = other_workloads(tb, wl, torch, dev, order, args, t_start)
     if not args.no_cpu_baseline:
-        del plan, qd, kd, vd
-        torch.cuda.empty_cache()
         line["cpu_baseline"] = cpu_baseline(w, q, k, v)
     print(json.dumps(line), flush=True)
 
