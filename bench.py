@@ -88,27 +88,33 @@ def cpu_baseline(w, q, k, v, budget_s=12.0):
     }
 
 
+def device_qkv(w, torch, dev):
+    """Inputs of workload w drawn on the device: same shapes, dtypes and value recipe as
+    workloads.make_qkv (N(0,1); K scaled; a seeded 1 % of the key rows scaled for the outlier workload),
+    from a seeded device generator instead of the CPU one, which takes minutes at a million tokens."""
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed)
+    draw = lambda shape: torch.randn(shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16 if w.dtype == "bf16" else torch.float32)
+    qd, kd, vd = draw((w.L, w.Hq, w.d)), draw((w.S, w.Hkv, w.d)), draw((w.S, w.Hkv, w.d))
+    if w.k_scale != 1.0:
+        kd *= w.k_scale
+    if w.outlier_frac > 0.0:
+        rows = torch.randperm(w.S, generator=g, device=dev)[: int(w.outlier_frac * w.S)]
+        kd[rows] *= w.outlier_scale
+    return qd, kd, vd
+
+
 def other_workloads(tb, wl, torch, dev, order, args, t_start, cap_s=150.0):
     """The forward call on the three larger workloads (256K, 512K, 1M): value and the attention
-    launch's fraction of the bf16 peak.  Inputs are drawn on the device (same shapes, dtypes and value
-    recipes as workloads.make_qkv: N(0,1), K x 2 for the 256K workload, 1 % of the key rows x 8 for
-    the 1M one; a seeded device generator instead of the CPU one, which would take minutes at 1M).
-    At most three timed calls each, and none is started once the bench has run for cap_s seconds."""
+    launch's fraction of the bf16 peak.  Inputs are drawn on the device (device_qkv).  At most three
+    timed calls each, and none is started once the bench has run for cap_s seconds."""
     out = []
     for idx in (2, 3, 4):
         w = wl.CONFIGS[idx]
         if time.perf_counter() - t_start > cap_s:
             out.append({"workload": w.name, "skipped": "wall-clock cap of the bench reached"})
             continue
-        g = torch.Generator(device=dev)
-        g.manual_seed(w.seed)
-        draw = lambda shape: torch.randn(shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
-        qd, kd, vd = draw((w.L, w.Hq, w.d)), draw((w.S, w.Hkv, w.d)), draw((w.S, w.Hkv, w.d))
-        if w.k_scale != 1.0:
-            kd *= w.k_scale
-        if w.outlier_frac > 0.0:
-            rows = torch.randperm(w.S, generator=g, device=dev)[: int(w.outlier_frac * w.S)]
-            kd[rows] *= w.outlier_scale
+        qd, kd, vd = device_qkv(w, torch, dev)
         sched = tb.tasp_schedule_multinode(w.n_ranks // args.nodes, args.nodes, w.rank) if args.nodes > 1 else tb.tasp_schedule(w.n_ranks, w.rank)
         plan = tb.ChunkAttnPlan(sched, qd, kd, vd, w.mask_mode, order=order, fuse_merge=True)
         flops = plan.flops()
@@ -140,6 +146,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="1..5, the workload list of BASELINE.json")
     ap.add_argument("--fuse-merge", type=int, default=1)
+    ap.add_argument("--fuse-steps", type=int, default=0,
+                    help="1: time the form with all steps in one launch as the main leg (bf16; the default line "
+                         "reports it as `single_launch` beside the step-by-step `value`)")
     ap.add_argument("--order", choices=["tasp", "ring"], default="tasp")
     ap.add_argument("--nodes", type=int, default=0,
                     help="U > 1: the (m-K_m-m)^U ring scheme for U nodes of N/U ranks (m rings) instead of the N-1 rings of K_N")
@@ -153,6 +162,8 @@ def main():
     ap.add_argument("--no-other-mode", action="store_true",
                     help="skip the legs that run the other merge mode, the single launch and the backward pass on "
                          "two streams (profiler runs: one kind of launch per kernel)")
+    ap.add_argument("--device-inputs", action="store_true",
+                    help="draw the inputs on the device (same recipe, another generator): the 1M workload in seconds")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 256 MiB copy with the library's copy kernel (scales profiler traffic counters)")
     args = ap.parse_args()
@@ -171,10 +182,14 @@ def main():
         w = wl.paper_grid(heads, seq)
     else:
         w = wl.CONFIGS[args.config - 1]
-    q, k, v = wl.make_qkv(w)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    if args.device_inputs:
+        qd, kd, vd = device_qkv(w, torch, dev)
+        q, k, v = (None, None, None) if args.no_cpu_baseline else (qd.cpu(), kd.cpu(), vd.cpu())
+    else:
+        q, k, v = wl.make_qkv(w)
+        qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
     if args.batch > 1:
         import dataclasses
         more = [wl.make_qkv(dataclasses.replace(w, seed=w.seed + 1000 * b)) for b in range(1, args.batch)]
@@ -185,7 +200,8 @@ def main():
     else:
         sched = tb.tasp_schedule(w.n_ranks, w.rank)
     order = tb.ORDER_TASP if args.order == "tasp" else tb.ORDER_RING
-    plan = tb.ChunkAttnPlan(sched, qd, kd, vd, w.mask_mode, order=order, fuse_merge=bool(args.fuse_merge))
+    plan = tb.ChunkAttnPlan(sched, qd, kd, vd, w.mask_mode, order=order, fuse_merge=bool(args.fuse_merge),
+                            fuse_steps=bool(args.fuse_steps))
     flops = plan.flops()
 
     if args.calib_copy:
@@ -237,7 +253,7 @@ def main():
     # (null when the kernel source has changed since they were taken: the file records its hash)
     traffic = None
     tpath = os.path.join(ROOT, "paper_2509_26541_amd", "hbm_traffic.json")
-    if os.path.exists(tpath) and args.batch == 1 and args.nodes <= 1 and args.order == "tasp" and args.fuse_merge:   # what was profiled
+    if os.path.exists(tpath) and args.batch == 1 and args.nodes <= 1 and args.order == "tasp" and args.fuse_merge and not args.fuse_steps:   # what was profiled
         import hashlib
         with open(os.path.join(ROOT, "paper_2509_26541_amd", "csrc", "attn_bf16.hip"), "rb") as f:
             sha = hashlib.sha256(f.read()).hexdigest()[:16]
@@ -408,7 +424,7 @@ def main():
                                "what": "tasp_calibration_mfma: only v_mfma_f32_32x32x16_bf16, operands in registers"},
         "config": {"workload": w.name, "n_ranks": w.n_ranks, "rank": w.rank, "S": w.S, "L": w.L, "Hq": w.Hq,
                    "Hkv": w.Hkv, "d": w.d, "mask": "zigzag_causal" if w.mask_mode else "full",
-                   "order": args.order, "rings": sched.n_rings, "batch": args.batch, "fuse_merge": int(args.fuse_merge), "flops_per_call": flops},
+                   "order": args.order, "rings": sched.n_rings, "batch": args.batch, "fuse_merge": int(args.fuse_merge), "fuse_steps": int(args.fuse_steps), "flops_per_call": flops},
         "roofline": roofline,
         "roofline_valu": roofline_valu,
         "ms_per_step_median_events": ms_median,

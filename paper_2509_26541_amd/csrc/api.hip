@@ -231,8 +231,9 @@ struct BwdSpans { enum Kind { kDq = 0, kDkv = 1, kOther = 2 }; };
 // Estimated duration of a dk/dv launch, in 64-row query tiles of one head, with one workgroup per
 // key tile (`per_tile` = 1, each serving all G query heads of its group) or per key tile and query
 // head (`per_tile` = G).  Mirrors what the kernel and the hardware do: the work list is (sequence,
-// KV head, head, key tile) in that order, every XCD gets one contiguous eighth of it, and each of
-// its slots/8 workgroup slots takes the next workgroup when it is free.  A workgroup walks, for
+// KV head, head, key tile) in that order, every XCD gets one contiguous eighth of it (exactly so when
+// the KV heads of the call are a multiple of 8; otherwise XCDs share heads, which this estimate
+// ignores), and each of its slots/8 workgroup slots takes the next workgroup when it is free.  A workgroup walks, for
 // each query block, the tiles from the first one that holds a row at or after its first key.
 int64_t dkv_makespan(const tasp::BwdLaunch& bp, int d, int per_tile, int slots) {
   const int bs = d == 128 ? 256 : 128, bt = 64;

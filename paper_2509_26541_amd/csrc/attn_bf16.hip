@@ -189,7 +189,8 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
 
   // ---- which (KV head, task, query tile, query head) this workgroup owns.  Workgroups are dealt
   // round-robin to the 8 XCDs; the index is remapped so that each XCD gets a contiguous run of work
-  // ordered KV-head-major: the workgroups of one XCD then stream the same K/V through its L2.
+  // ordered KV-head-major: the workgroups of one XCD then stream the same K/V through its L2 (and
+  // XCDs that have to share KV heads deal the items of those heads among them: xcd_balanced).
   const int G = p.Hq / p.Hkv;
   const int tiles0 = (p.task[0].n_q + BM - 1) / BM;
   const int tiles1 = p.n_tasks > 1 ? (p.task[1].n_q + BM - 1) / BM : 0;
@@ -199,8 +200,8 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   // saves the 4 us a CU idles between two workgroups.  The outer loop costs registers, so this pays
   // only where there are registers to spare and the items are short: d = 64, all steps in one launch.
   for (int round = 0; PERSIST || round == 0; ++round) {
-  const int w_all = PERSIST ? persistent_item(blockIdx.x, gridDim.x, p.n_items, round) : xcd_contiguous(blockIdx.x, gridDim.x);
-  if (PERSIST && w_all < 0) break;
+  const int w_all = PERSIST ? persistent_item(blockIdx.x, gridDim.x, p.n_items, round) : xcd_balanced(blockIdx.x, p.batch * p.Hkv, per_g);
+  if (w_all < 0) break;
   const int bi = w_all / per_b;
   const int w = w_all - bi * per_b;
   const int g = w / per_g;
@@ -852,7 +853,9 @@ hipError_t launch_variant(const AttnLaunch& p0, hipStream_t stream) {
     }
   }
   const AttnLaunch& p = p0;
-  const int64_t blocks = items;
+  const int64_t units = static_cast<int64_t>(p0.batch) * p0.Hkv;
+  const int64_t blocks = xcd_balanced_blocks(units, items / units);
+  if (blocks > INT_MAX) return hipErrorInvalidValue;
   return TASP_LAUNCH((attn_bf16_kernel<D, NS, NW, false>), dim3(static_cast<unsigned>(blocks)), dim3(C::NTHREADS), stream, p);
 }
 

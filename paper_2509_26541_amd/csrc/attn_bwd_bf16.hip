@@ -126,7 +126,8 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
   const int tiles0 = (p.task[0].n_q + BS - 1) / BS;
   const int tiles1 = p.n_tasks > 1 ? (p.task[1].n_q + BS - 1) / BS : 0;
   const int per_g = (tiles0 + tiles1) * G, per_b = per_g * p.Hkv;
-  const int w_all = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int w_all = xcd_balanced(blockIdx.x, p.batch * p.Hkv, per_g);
+  if (w_all < 0) return;
   const int bi = w_all / per_b;
   const int w = w_all - bi * per_b;
   const int g = w / per_g;
@@ -368,7 +369,8 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
   const int G = p.Hq / p.Hkv;
   const int total_keys = p.rng_vbeg[p.n_rng];
   const int ktiles = (total_keys + BS - 1) / BS;
-  const int w_all = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int w_all = xcd_balanced(blockIdx.x, p.batch * p.Hkv, ktiles * (SPLIT ? G : 1));
+  if (w_all < 0) return;
   // Split by head, the work list of a KV head is head-major: the workgroups an XCD runs at one time
   // then stream the query tiles of the same head through its L2, as they do without the split
   // (tile-major measured 9 % slower), and each head's tiles still come by falling work.
@@ -795,8 +797,11 @@ hipError_t launch_bwd_dq_bf16(const BwdLaunch& p, int d, hipStream_t stream) {
   int64_t tiles = 0;
   constexpr int BS = 128;
   for (int t = 0; t < p.n_tasks; ++t) tiles += (p.task[t].n_q + BS - 1) / BS;
-  const int64_t blocks = tiles * p.Hq * p.batch;
-  if (blocks == 0) return hipSuccess;
+  const int64_t items = tiles * p.Hq * p.batch;
+  if (items == 0) return hipSuccess;
+  if (items > INT_MAX) return hipErrorInvalidValue;
+  const int64_t units = static_cast<int64_t>(p.batch) * p.Hkv;
+  const int64_t blocks = xcd_balanced_blocks(units, items / units);
   if (blocks > INT_MAX) return hipErrorInvalidValue;
   if (d == 128) return TASP_LAUNCH((bwd_dq_kernel<128>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, p);
   if (d == 64) return TASP_LAUNCH((bwd_dq_kernel<64>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, p);
@@ -807,8 +812,11 @@ template <int D, int NW, bool VLDS>
 hipError_t launch_dkv_variant(const BwdLaunch& p, hipStream_t stream) {
   constexpr int BS = 32 * NW;
   const int64_t total = p.rng_vbeg[p.n_rng];
-  const int64_t blocks = (total + BS - 1) / BS * p.Hkv * p.batch * (p.split_heads ? p.Hq / p.Hkv : 1);
-  if (blocks == 0) return hipSuccess;
+  const int64_t items = (total + BS - 1) / BS * p.Hkv * p.batch * (p.split_heads ? p.Hq / p.Hkv : 1);
+  if (items == 0) return hipSuccess;
+  if (items > INT_MAX) return hipErrorInvalidValue;
+  const int64_t units = static_cast<int64_t>(p.batch) * p.Hkv;
+  const int64_t blocks = xcd_balanced_blocks(units, items / units);
   if (blocks > INT_MAX) return hipErrorInvalidValue;
   const dim3 grid(static_cast<unsigned>(blocks)), block(64 * NW);
   if (p.split_heads) return TASP_LAUNCH((bwd_dkv_kernel<D, NW, VLDS, true>), grid, block, stream, p);

@@ -55,6 +55,27 @@ __device__ inline int xcd_contiguous(int block, int nblocks) {
   return xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
 }
 
+// The same for a work list that is `units` runs of `per_unit` items, a unit being what reads the
+// same K and V (one KV head of one sequence), each run sorted by falling work.  When the units do
+// not divide among the 8 XCDs, equal counts per XCD are not equal work (half a run is its longer
+// or its shorter items) and an XCD whose run ends with the long items of a part-unit finishes late.
+// So 8/g XCDs (g = gcd(units, 8)) share units/g units and deal their items round-robin: every one of
+// them gets the same mix and still meets each unit's items by falling work.  With units a multiple
+// of 8 this is xcd_contiguous.  The grid has xcd_balanced_blocks workgroups; -1 = none for this one.
+__host__ __device__ inline int xcd_balanced_share(int units) { const int g = units & -units; return g >= 8 ? 1 : 8 / g; }
+__device__ inline int xcd_balanced(int block, int units, int per_unit) {
+  const int k = xcd_balanced_share(units);
+  const int xcd = block & 7, slot = block >> 3;
+  const int len = units / (8 / k) * per_unit;          // items of a group of k XCDs
+  const int j = slot * k + xcd % k;
+  return j < len ? xcd / k * len + j : -1;
+}
+__host__ inline long long xcd_balanced_blocks(long long units, long long per_unit) {
+  const long long k = xcd_balanced_share(static_cast<int>(units));
+  const long long len = units / (8 / k) * per_unit;
+  return 8 * ((len + k - 1) / k);
+}
+
 // Work item of persistent workgroup `block` (of `nblocks`, a multiple of 8 and fewer than
 // n_items) in its `round`-th turn, or -1 when it has none left.  XCD x owns the same contiguous run
 // of items as in xcd_contiguous, and its nblocks/8 workgroups walk that run in rounds, forwards in
