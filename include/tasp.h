@@ -151,7 +151,7 @@ int tasp_step_segments(const tasp_schedule_t* s, int64_t S, int32_t mask_mode, i
  * Supported: d in {64, 128}; schedules of at most 32 rings (N <= 33 ranks with tasp_schedule_create;
  * with tasp_schedule_create_multinode up to 32 ranks per node and any N it accepts - a call
  * enqueues N steps); S < 2^31; for bf16 also S < 2^24 and S*Hkv*d*2 <= 2^32 bytes (K and V are
- * addressed with 32-bit offsets).  All device pointers 16-byte aligned.
+ * addressed with 32-bit offsets; with Hkv = 1, less than 2^32).  All device pointers 16-byte aligned.
  * The call only enqueues work on `hip_stream` (a hipStream_t, NULL = default stream); results are
  * valid once the stream has been synchronised.
  * ---------------------------------------------------------------------------------------------- */

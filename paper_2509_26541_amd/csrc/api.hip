@@ -52,6 +52,9 @@ int validate(const tasp_schedule_t* s, const tasp_attn_args* a, Shape* sh) {
     const int64_t row_bytes = static_cast<int64_t>(a->Hkv) * a->d * 2;
     if (a->S >= (1 << 24) || row_bytes >= (1 << 24) || a->S * row_bytes > (int64_t{1} << 32))
       return TASP_EUNSUPPORTED_SHAPE;
+    // the forward kernel reads them through buffer descriptors of 2^32 - 1 bytes that start at the
+    // KV head's first row: only with a single KV head can the last row end at 2^32 exactly
+    if (a->Hkv == 1 && a->S * row_bytes == (int64_t{1} << 32)) return TASP_EUNSUPPORTED_SHAPE;
   }
   if (2 * s->n_rings > tasp::kMaxSeg) return TASP_EUNSUPPORTED_SHAPE;
   if (a->batch < 0 || a->batch > 65535) return TASP_EINVAL;

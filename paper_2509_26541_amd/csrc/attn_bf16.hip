@@ -65,7 +65,9 @@ struct Cfg {
   static constexpr int ROWS_PER_LINE = 16 / UNITS;    // rows per 256-byte bank line (1 or 2)
   static constexpr int TILE_BYTES = BN * D * 2;
   static constexpr int STAGES = 4;
-  static constexpr int SMEM = STAGES * 2 * TILE_BYTES;   // ring of (K tile, V tile)
+  static constexpr int SMEM = STAGES * 2 * TILE_BYTES;   // ring of K tiles, then ring of V tiles
+  static constexpr int V_RING = STAGES * TILE_BYTES;     // where the V ring starts
+  static_assert(V_RING <= 65536, "stage and fragment offsets of an LDS read go into its 16-bit offset field");
   __device__ static int swz_k(int row, int unit) { return unit ^ ((row / ROWS_PER_LINE) % UNITS); }
   __device__ static int swz_v(int row, int unit) { return unit ^ (4 * ((row / ROWS_PER_LINE) % (UNITS / 4))); }
 };
@@ -80,8 +82,8 @@ __device__ __forceinline__ float max3(float a, float b, float c) { float r; asm(
 // placed by hand (s_waitcnt vmcnt before the barrier that publishes the tile), no other vector
 // memory instruction is in flight while these are, the stage it fills is not read before the next
 // barrier, and barriers and waits are ordered against volatile assembly.
-__device__ inline void dma16(const unsigned char* base, unsigned off, unsigned char* lds_base) {
-  global_to_lds_16<false>(base, off, lds_base);
+__device__ inline void dma16(const u32x4& rsrc, unsigned soff, unsigned off, unsigned char* lds_base) {
+  buffer_to_lds_16(rsrc, soff, off, lds_base);
 }
 
 // LDS operand reads whose wait is placed by hand.  A read is volatile assembly (issued in program
@@ -170,7 +172,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   constexpr int DB = D / 32;     // 32-row blocks of O^T
   constexpr bool ACC = NS > 1;
 
-  __shared__ __attribute__((aligned(16))) unsigned char smem[C::SMEM];   // ring of stages, each a K tile then a V tile
+  __shared__ __attribute__((aligned(16))) unsigned char smem[C::SMEM];   // four K tiles, then four V tiles
   __shared__ __attribute__((aligned(16))) int s_tok[C::STAGES][BN];   // global position of every key row of a tile (INT_MAX: none)
   // Effective segments: the segments are disjoint ranges of the sequence, so at most one of them
   // holds the first position of the query tile and is split in two; hence kMaxSegAll + 2 entries.
@@ -317,95 +319,122 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   const int fr = tid / C::UNITS, fu = tid % C::UNITS;
   const unsigned row_bytes = static_cast<unsigned>(p.Hkv) * D * 2;
   // Row bookkeeping of the loader.  One wavefront-load covers RW consecutive rows of a tile, and as
-  // long as these are RW consecutive keys of one effective segment, the lane offsets are a
-  // wavefront-uniform base plus a per-lane constant.  So the bookkeeping is scalar: per pass the
-  // wavefront follows the first of its RW rows through the virtual concatenation (w_tok = its global
-  // position, INT_MAX past the last key; w_left = keys from it to the end of its segment; w_seg = its
-  // segment), from one tile to the next it moves 64 keys on, and only when fewer than RW keys are
-  // left in the segment (one tile in about twenty with sub-chunks of a thousand keys) every lane
-  // searches the segment list for its own row.  A vector instruction costs the SIMD's issue port as
-  // much as a third of a matrix instruction, and the port is what bounds this kernel.
+  // long as these are RW consecutive keys of one effective segment, the address of a lane is a
+  // wavefront-uniform base plus a per-lane constant.  So on the common path everything is scalar:
+  // per pass the wavefront follows the first of its RW rows through the virtual concatenation
+  // (w_tok = its global position; w_left = keys from it to the end of its segment; w_seg = its
+  // segment; k_off = byte offset of that key's row), from one tile to the next all of these move 64
+  // keys on, the loads take k_off as their scalar offset and their lane offsets (lane_k, lane_v)
+  // never change.  Only when fewer than RW keys are left in the segment, or the
+  // tile runs past the last key (one tile in about ten with sub-chunks of a thousand keys) every
+  // lane searches the segment list for its own row and gets an offset of its own (base offset 0).
+  // A vector instruction costs the SIMD's issue port as much as a third of a matrix instruction,
+  // and the port is what bounds this kernel.
   constexpr int RW = 64 / C::UNITS;
   const int r_lane = lane / C::UNITS;
+  const unsigned k_col = C::swz_k(fr, fu) * 16, v_col = C::swz_v(fr, fu) * 16;    // byte column this lane reads
+  static_assert(C::RPP % 16 == 0, "the swizzle of a thread's rows must not depend on the pass");
+  const unsigned lane_k_const = static_cast<unsigned>(r_lane) * row_bytes + k_col;
   int w_tok[C::PASSES], w_left[C::PASSES], w_seg[C::PASSES];
+  unsigned k_off[C::PASSES], v_off[C::PASSES];       // scalar: byte offset of the pass's first row, tile u / tile u-1
+  unsigned lane_k[C::PASSES], lane_v[C::PASSES];     // per lane: added to it
 #pragma unroll
-  for (int i = 0; i < C::PASSES; ++i) { w_tok[i] = 0; w_left[i] = 0; w_seg[i] = 0; }
+  for (int i = 0; i < C::PASSES; ++i) {
+    w_tok[i] = 0; w_left[i] = 0; w_seg[i] = 0; k_off[i] = 0; v_off[i] = 0;
+    lane_k[i] = lane_k_const; lane_v[i] = lane_k_const + (v_col - k_col);
+  }
   int tokk[C::PASSES];           // global position of this lane's row of the tile being fetched
+  // The lane offsets differ from their constants while a tile with a searched pass is on its way:
+  // its K loads (this round), its V loads (next round), and back (the round after).  hist = which
+  // of the last two tiles had one; slow_below = RW, or INT_MAX while hist is not 0.
+  int hist = 0, slow_below = RW;
   // every lane finds its own row of tile t (pass i); the wavefront's state is taken from its first lane
   auto locate_slow = [&](int i, int t) __attribute__((always_inline)) {
     const int v = t * BN + fr + C::RPP * i;
     int j = w_seg[i], left;                                   // rows only move forward
     while (j < n_eff && v >= e_vbeg[j + 1]) ++j;
     if (j < n_eff) { tokk[i] = v + e_goff[j]; left = e_vbeg[j + 1] - v; }
-    else { tokk[i] = INT_MAX; left = 1 << 30; }
+    else { tokk[i] = INT_MAX; left = 0; }                     // past the last key: searched again next time
     w_tok[i] = __builtin_amdgcn_readfirstlane(tokk[i]);
     w_left[i] = __builtin_amdgcn_readfirstlane(left);
     w_seg[i] = __builtin_amdgcn_readfirstlane(j);
   };
   // rows of tile t; must be called for t = 0, 1, 2, ... in this order
   auto locate = [&](int t) __attribute__((always_inline)) {
-    int least = 1 << 30;
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
+      v_off[i] = k_off[i];                                    // V of the tile before goes out this round
       w_left[i] -= BN;                                        // tile 0: from 0, i.e. search
-      w_tok[i] = w_tok[i] == INT_MAX ? INT_MAX : w_tok[i] + BN;
-      least = min(least, w_left[i]);
+      w_tok[i] += BN;
+      k_off[i] += BN * row_bytes;
+      tokk[i] = w_tok[i] + r_lane;
+      // The new values are pinned to scalar registers here.  Left alone, the compiler moves these
+      // additions behind the branch below (the other arm overwrites them), which leaves an undefined
+      // input at the join, and it resolves that by keeping the whole chain in vector registers.
+      asm volatile("" : "+s"(k_off[i]), "+s"(w_tok[i]), "+s"(w_left[i]));
     }
+    int least = w_left[0];                                    // (a three-way minimum would become a vector instruction)
 #pragma unroll
-    for (int i = 0; i < C::PASSES; ++i) tokk[i] = w_tok[i] + (r_lane & (w_tok[i] == INT_MAX ? 0 : -1));
-    if (__builtin_expect(least < RW, 0)) {
+    for (int i = 1; i < C::PASSES; ++i) least = min(least, w_left[i]);
+    if (__builtin_expect(least < slow_below, 0)) {
+      int slow = 0;
 #pragma unroll
-      for (int i = 0; i < C::PASSES; ++i)
-        if (w_left[i] < RW) locate_slow(i, t);
+      for (int i = 0; i < C::PASSES; ++i) {
+        lane_v[i] = lane_k[i] + (v_col - k_col);             // unsigned wrap-around is exact
+        lane_k[i] = lane_k_const;
+        k_off[i] = static_cast<unsigned>(w_tok[i]) * row_bytes;
+        asm volatile("" : "+s"(k_off[i]));                    // (pinned, as above)
+        if (w_left[i] < RW) {
+          locate_slow(i, t);
+          // rows past the end fetch key 0 and are masked; both factors are below 2^24 (host check)
+          lane_k[i] = __umul24(tokk[i] == INT_MAX ? 0u : static_cast<unsigned>(tokk[i]), row_bytes) + k_col;
+          k_off[i] = 0;
+          slow = 1;
+        }
+      }
+      hist = ((hist << 1) | slow) & 3;
+      slow_below = hist != 0 ? INT_MAX : RW;
     }
   };
-  // Tiles go straight into the ring (global_load_lds: no registers, no LDS write instructions).
+  // Tiles go straight into the rings (global_load_lds: no registers, no LDS write instructions).
   // A wavefront's 64 lanes fill 1 KiB of consecutive LDS; the XOR swizzle of the tile layout is
   // applied on the source side: the lane that owns LDS slot (row, unit) reads the 16 bytes of column
-  // swz(row, unit) of that row.  Rows past the end fetch token 0 and are masked.
+  // swz(row, unit) of that row.
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   // wavefront-uniform, and known at compile time when every wavefront fetches (a branch costs a
   // wavefront 20-40 cycles even when it is not taken)
   const bool is_loader = C::LOADERS == C::NTHREADS || wave_u < C::LOADERS / 64;
   const unsigned char* Kg = static_cast<const unsigned char*>(p.k) + (bi * p.kv_bstride + static_cast<int64_t>(g) * D) * 2;   // this sequence and KV head, uniform
   const unsigned char* Vg = static_cast<const unsigned char*>(p.v) + (bi * p.kv_bstride + static_cast<int64_t>(g) * D) * 2;
-  const unsigned k_col = C::swz_k(fr, fu) * 16, v_col = C::swz_v(fr, fu) * 16;    // byte column this lane reads
-  static_assert(C::RPP % 16 == 0, "the swizzle of a thread's rows must not depend on the pass");
-  // Round u of the fetch brings K(u) into the K half of stage u % 4 and V(u-1) into the V half of
-  // stage (u-1) % 4 (the main loop says why the two halves of a tile travel a round apart); 2*PASSES
+  const u32x4 k_buf = raw_buffer(Kg), v_buf = raw_buffer(Vg);
+  // Round u of the fetch brings K(u) into stage u % 4 of the K ring and V(u-1) into stage (u-1) % 4
+  // of the V ring (the main loop says why the two halves of a tile travel a round apart); 2*PASSES
   // loads per thread.  The path from L2 into LDS takes roughly 25 cycles per wavefront-load and the
   // issuing wave stalls once its queue is full, so the loads are not issued in one burst:
   // fetch_begin(u) does the bookkeeping of tile u, fetch_piece(j) issues load j (even: K(u), pass
-  // j/2; odd: V(u-1)), and the loop drops the pieces between its matrix instructions.  The V offsets
-  // of a tile are its K offsets moved to the V swizzle column, taken over once the V load of the
-  // tile before has gone out.
-  unsigned fetch_k[C::PASSES], fetch_v[C::PASSES];   // byte offsets from Kg / Vg
+  // j/2; odd: V(u-1)), and the loop drops the pieces between its matrix instructions.
   unsigned char* fetch_dst_k = smem;
   unsigned char* fetch_dst_v = smem;
-  auto fetch_begin = [&](int u) __attribute__((always_inline)) {
+  auto fetch_begin = [&](int u, auto us_) __attribute__((always_inline)) {      // us_ = u % 4 at compile time
+    constexpr int US = decltype(us_)::value;
     if (!is_loader) return;
     locate(u);
-    fetch_dst_k = smem + (u & 3) * 2 * C::TILE_BYTES + wave_u * 1024;
-    fetch_dst_v = smem + ((u - 1) & 3) * 2 * C::TILE_BYTES + C::TILE_BYTES + wave_u * 1024;
+    fetch_dst_k = smem + US * C::TILE_BYTES + wave_u * 1024;
+    fetch_dst_v = smem + C::V_RING + ((US + 3) & 3) * C::TILE_BYTES + wave_u * 1024;
 #pragma unroll
-    for (int i = 0; i < C::PASSES; ++i) {
-      const unsigned row_off = __umul24(tokk[i] == INT_MAX ? 0u : static_cast<unsigned>(tokk[i]), row_bytes);   // both below 2^24 (host check)
-      fetch_k[i] = row_off + k_col;
-      s_tok[u & 3][fr + C::RPP * i] = tokk[i];    // the UNITS lanes of a row write the same value
-    }
+    for (int i = 0; i < C::PASSES; ++i) s_tok[US][fr + C::RPP * i] = tokk[i];    // the UNITS lanes of a row write the same value
   };
   auto fetch_piece = [&](int j, bool with_v = true) __attribute__((always_inline)) {
     const int i = j >> 1;
     if (!is_loader) return;
     if (j & 1) {
-      if (with_v) dma16(Vg, fetch_v[i], fetch_dst_v + i * C::LOADERS * 16);
-      fetch_v[i] = fetch_k[i] + (v_col - k_col);       // tile u, for the next round (unsigned wrap-around is exact)
+      if (with_v) dma16(v_buf, v_off[i], lane_v[i], fetch_dst_v + i * C::LOADERS * 16);
     } else {
-      dma16(Kg, fetch_k[i], fetch_dst_k + i * C::LOADERS * 16);
+      dma16(k_buf, k_off[i], lane_k[i], fetch_dst_k + i * C::LOADERS * 16);
     }
   };
-  auto fetch_round = [&](int u, bool with_v) __attribute__((always_inline)) {
-    fetch_begin(u);
+  auto fetch_round = [&](int u, auto us_, bool with_v) __attribute__((always_inline)) {
+    fetch_begin(u, us_);
 #pragma unroll
     for (int j = 0; j < 2 * C::PASSES; ++j) fetch_piece(j, with_v);
   };
@@ -414,6 +443,11 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
     constexpr int N = decltype(newest)::value * 2 * C::PASSES;
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
   };
+
+  constexpr std::integral_constant<int, 0> stage0{};
+  constexpr std::integral_constant<int, 1> stage1{};
+  constexpr std::integral_constant<int, 2> stage2{};
+  constexpr std::integral_constant<int, 3> stage3{};
 
   // ---- per-lane LDS read addresses, stage 0 (loop invariant)
   const unsigned smem_lds = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)smem));
@@ -428,7 +462,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
 #pragma unroll
   for (int db = 0; db < DB; ++db) {
     const int unit = 4 * db + 2 * (ga & 1) + ((jj & 3) >> 1);
-    vadr[db] = smem_lds + C::TILE_BYTES + (vrow * C::UNITS + C::swz_v(vrow, unit)) * 16 + 8 * (jj & 1);
+    vadr[db] = smem_lds + C::V_RING + (vrow * C::UNITS + C::swz_v(vrow, unit)) * 16 + 8 * (jj & 1);
   }
 
   // ---- running state, per strip
@@ -453,9 +487,9 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   // dominate from the same 32 scores of a lane share one correction).  Summing all rounded
   // probabilities would be exact, but v_dot2c_f32_bf16 is a half-rate instruction: 10 % of the
   // vector port.  lse comes from l alone.
-  float m_run[NS], l_run[NS], l_lo[NS], r_fix[NS];
+  float m_run[NS], m_raise[NS], l_run[NS], l_lo[NS], r_fix[NS];     // m_raise = m_run + the gap
 #pragma unroll
-  for (int s = 0; s < NS; ++s) { m_run[s] = kNegBig; l_run[s] = 0.f; l_lo[s] = 0.f; r_fix[s] = 0.f; }
+  for (int s = 0; s < NS; ++s) { m_run[s] = kNegBig; m_raise[s] = kNegBig; l_run[s] = 0.f; l_lo[s] = 0.f; r_fix[s] = 0.f; }
   const float c = p.scale * kLog2e;
   auto fence_o = [&]() __attribute__((always_inline)) {
     fence_o_first<ACC>(o[0][0]);
@@ -476,7 +510,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   // element-wise mask of the scores of tile t, only for tiles that touch the diagonal or run past the last key
   int m_idx = 0;
   int m_cur_lo = __builtin_amdgcn_readfirstlane(m_lo[0]), m_cur_hi = __builtin_amdgcn_readfirstlane(m_hi[0]);
-  auto mask = [&](int t, f32x16 (&S)[NS][2]) __attribute__((always_inline)) {
+  auto mask = [&](auto ts_, int t, f32x16 (&S)[NS][2]) __attribute__((always_inline)) {
     if (__builtin_expect(t < m_cur_lo, 1)) return;     // one compare on the common path (m_cur_lo <= m_cur_hi)
     while (t > m_cur_hi) {     // t only grows; the last run never ends
       ++m_idx;
@@ -484,7 +518,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
       m_cur_hi = __builtin_amdgcn_readfirstlane(m_hi[m_idx]);
     }
     if (t >= m_cur_lo) {
-      const int stage = t & 3;
+      constexpr int stage = decltype(ts_)::value;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -508,23 +542,23 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   };
   // after the 16 steps: fold the lane halves, raise the running max lazily (only when it grew by more
   // than 2^8) and rescale what has been accumulated; the second product of the tile before must be complete
+  // (a lane tests the 32 scores it holds itself: a row has grown iff one of its two lanes has, and
+  // the exchange between the lane halves is needed only then)
   auto raise_max = [&]() __attribute__((always_inline)) {
-    float m_cand[NS];
     bool grew = false;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const unsigned mu = __builtin_bit_cast(unsigned, mx[s]);
-      const u32x2 sw = __builtin_amdgcn_permlane32_swap(mu, mu, false, false);   // the other 16 keys of a block sit 32 lanes away
-      const float m2 = max2(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
-      m_cand[s] = max2(m_run[s], m2 * c);
-      grew |= m_cand[s] > m_run[s] + kRescaleGap;
-    }
+    for (int s = 0; s < NS; ++s) grew |= mx[s] * c > m_raise[s];
     if (__builtin_amdgcn_ballot_w64(grew) != 0) {
       fence_o();
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
-        const float alpha = fast_exp2(m_run[s] - m_cand[s]);
-        m_run[s] = m_cand[s];
+        const unsigned mu = __builtin_bit_cast(unsigned, mx[s]);
+        const u32x2 sw = __builtin_amdgcn_permlane32_swap(mu, mu, false, false);   // the other 16 keys of a block sit 32 lanes away
+        const float m2 = max2(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
+        const float m_cand = max2(m_run[s], m2 * c);
+        const float alpha = fast_exp2(m_run[s] - m_cand);
+        m_run[s] = m_cand;
+        m_raise[s] = m_cand + kRescaleGap;
         l_run[s] *= alpha;
         l_lo[s] *= alpha;
         r_fix[s] *= alpha;
@@ -572,27 +606,34 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   constexpr int NKM = NS * NKF, NVM = NS * NVF;        // matrix instructions per phase
   constexpr int PD = 4;
   static_assert(NKF >= PD && NVF >= PD, "");
-  constexpr unsigned STAGE_BYTES = 2 * C::TILE_BYTES;
   u32x4 fk[PD];            // K fragments in flight (ring slot = fragment % PD)
   u32x2 fl[PD], fh[PD];    // V^T fragments in flight, low and high half
-  auto issue = [&](auto ff, unsigned base_k, unsigned base_v) __attribute__((always_inline)) {
+  // (sk, sv: ring stages of the K and the V tile, compile-time, so they go into the offset field)
+  auto issue = [&](auto ff, auto sk_, auto sv_) __attribute__((always_inline)) {
     constexpr int F = decltype(ff)::value, slot = F % PD;
+    constexpr int SK = decltype(sk_)::value * C::TILE_BYTES, SV = decltype(sv_)::value * C::TILE_BYTES;
     if constexpr (F < NKF) {
       constexpr int ks = F / 2, kb = F % 2;
-      lds_read_b128<kb * 32 * D * 2>(fk[slot], kadr[ks] + base_k);
+      lds_read_b128<kb * 32 * D * 2 + SK>(fk[slot], kadr[ks]);
     } else {
       constexpr int gg = (F - NKF) / DB, db = (F - NKF) % DB;
-      lds_read_tr_b64<gg * 16 * D * 2>(fl[slot], vadr[db] + base_v);
-      lds_read_tr_b64<gg * 16 * D * 2 + 8 * D * 2>(fh[slot], vadr[db] + base_v);
+      lds_read_tr_b64<gg * 16 * D * 2 + SV>(fl[slot], vadr[db]);
+      lds_read_tr_b64<gg * 16 * D * 2 + 8 * D * 2 + SV>(fh[slot], vadr[db]);
     }
   };
   // The fragment stream never drains: after the last K fragment of a tile come the V^T fragments of
   // the next second product, after those the K fragments of the next score tile.  LDS read
   // instructions issued after those of a fragment and before its wait = those of the PD - 1 fragments
   // behind it in that cyclic order (one per K fragment, two per V^T fragment).
+  // One wait serves two fragments: the matrix instruction of an even fragment waits until its own
+  // reads and those of the odd fragment behind it have landed, the odd one's does not wait (a wait
+  // is an instruction of its own in the wavefront's issue stream; the prefetch depth beyond two
+  // buys nothing).  An even and the following odd fragment are always of the same kind.
+  static_assert(NKF % 2 == 0 && NVF % 2 == 0 && PD >= 3, "");
   auto younger = [](int f) constexpr {
+    if (f % 2 != 0) return -1;
     int n = 0;
-    for (int r = f + 1; r < f + PD; ++r) n += (r % NF) < NKF ? 1 : 2;
+    for (int r = f + 2; r < f + PD; ++r) n += (r % NF) < NKF ? 1 : 2;
     return n < 15 ? n : 15;
   };
   // ---- vector work dealt out to the matrix instructions of a body.  A matrix instruction keeps
@@ -660,19 +701,22 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   // all reach the barrier within about a hundred cycles of each other.  No branch is involved.
   constexpr std::integral_constant<int, 1> one_in_flight{};
   // fragment g of the cyclic stream that starts with the V^T fragments of tile tv and goes on with the K fragments of tile tk
-  auto issue_cyc = [&](auto gg_, unsigned base_k, unsigned base_v) __attribute__((always_inline)) {
+  auto issue_cyc = [&](auto gg_, auto sk_, auto sv_) __attribute__((always_inline)) {
     constexpr int G = decltype(gg_)::value;
-    if constexpr (G < NVF) issue(std::integral_constant<int, NKF + G>{}, base_k, base_v);
-    else issue(std::integral_constant<int, G - NVF>{}, base_k, base_v);
+    if constexpr (G < NVF) issue(std::integral_constant<int, NKF + G>{}, sk_, sv_);
+    else issue(std::integral_constant<int, G - NVF>{}, sk_, sv_);
   };
   // Second product of tile t: S_cur = S(t), S_next = S(t+1).  Its trailing reads are the first K fragments of tile t+2.
-  auto pv_half = [&](int t, f32x16 (&S_cur)[NS][2], f32x16 (&S_next)[NS][2]) __attribute__((always_inline)) {
-    const unsigned base_k = ((t + 2) & 3) * STAGE_BYTES, base_v = (t & 3) * STAGE_BYTES;
+  // ts_ = t % 4, the ring stage of tile t, at compile time (the loop is unrolled four times).
+  auto pv_half = [&](auto ts_, int t, f32x16 (&S_cur)[NS][2], f32x16 (&S_next)[NS][2]) __attribute__((always_inline)) {
+    constexpr int TS = decltype(ts_)::value;
+    constexpr std::integral_constant<int, (TS + 2) & 3> sk_{};
+    constexpr std::integral_constant<int, TS> sv_{};
     static_for<NVF>([&](auto gg_) __attribute__((always_inline)) {
       constexpr int G = decltype(gg_)::value, F = NKF + G, slot = F % PD, W = younger(F);
       constexpr int gg = G / DB, db = G % DB;
       if constexpr (2 * G == NVF) __builtin_amdgcn_s_setprio(2);
-      if constexpr (G == 1) fetch_begin(t + 4);
+      if constexpr (G == 1) fetch_begin(t + 4, ts_);
       if constexpr (db == 0) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) fence_p(pf[s][gg]);
@@ -680,7 +724,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
       if constexpr (NS * G == VS) {
         // the scores of tile t+1 are complete (several matrix instructions of the second product lie between)
         fence_scores(S_next);
-        mask(t + 1, S_next);
+        mask(std::integral_constant<int, (TS + 1) & 3>{}, t + 1, S_next);
       }
       const u32x4 av = {fl[slot][0], fl[slot][1], fh[slot][0], fh[slot][1]};
       static_for<NS>([&](auto ss) __attribute__((always_inline)) {
@@ -689,16 +733,19 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
         vector_slot(std::integral_constant<int, NS * F + s>{}, S_cur, S_next);
         __builtin_amdgcn_sched_barrier(0);
       });
-      issue_cyc(std::integral_constant<int, (G + PD) % NF>{}, base_k, base_v);
+      issue_cyc(std::integral_constant<int, (G + PD) % NF>{}, sk_, sv_);
       if constexpr ((G + 1) % FRAGS_PER_PIECE == 0) fetch_piece((G + 1) / FRAGS_PER_PIECE - 1);
     });
   };
   // Scores of tile t2 into S_next while S_cur = S(t2-1) turns into P(t2-1).  PRIME: nothing is in
   // flight yet (the first call).  Its trailing reads are the first V^T fragments of tile t2-1.
-  auto qk_half = [&](auto prime, int t2, f32x16 (&S_cur)[NS][2], f32x16 (&S_next)[NS][2]) __attribute__((always_inline)) {
+  // (t2s_ = t2 % 4)
+  auto qk_half = [&](auto prime, auto t2s_, f32x16 (&S_cur)[NS][2], f32x16 (&S_next)[NS][2]) __attribute__((always_inline)) {
     constexpr bool PRIME = decltype(prime)::value;
-    const unsigned base_k = (t2 & 3) * STAGE_BYTES, base_v = ((t2 - 1) & 3) * STAGE_BYTES;
-    if constexpr (PRIME) static_for<PD>([&](auto f) __attribute__((always_inline)) { issue(f, base_k, base_v); });
+    constexpr int T2S = decltype(t2s_)::value;
+    constexpr std::integral_constant<int, T2S> sk_{};
+    constexpr std::integral_constant<int, (T2S + 3) & 3> sv_{};
+    if constexpr (PRIME) static_for<PD>([&](auto f) __attribute__((always_inline)) { issue(f, sk_, sv_); });
     else __builtin_amdgcn_s_setprio(1);
     raise_max();                                  // of S_cur
 #pragma unroll
@@ -719,23 +766,23 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
         vector_slot(std::integral_constant<int, NS * F + s>{}, S_cur, S_next);
         __builtin_amdgcn_sched_barrier(0);
       });
-      issue_cyc(std::integral_constant<int, (G + PD) % NF>{}, base_k, base_v);
+      issue_cyc(std::integral_constant<int, (G + PD) % NF>{}, sk_, sv_);
       if constexpr (!PRIME && (G + 1) % FRAGS_PER_PIECE == 0) fetch_piece((G + 1) / FRAGS_PER_PIECE - 1);
     });
   };
-  auto body = [&](int t, f32x16 (&S_a)[NS][2], f32x16 (&S_b)[NS][2]) __attribute__((always_inline)) {
+  auto body = [&](auto ts_, int t, f32x16 (&S_a)[NS][2], f32x16 (&S_b)[NS][2]) __attribute__((always_inline)) {
     __builtin_amdgcn_s_setprio(3);
-    pv_half(t, S_a, S_b);
-    qk_half(std::false_type{}, t + 2, S_b, S_a);
+    pv_half(ts_, t, S_a, S_b);
+    qk_half(std::false_type{}, std::integral_constant<int, (decltype(ts_)::value + 2) & 3>{}, S_b, S_a);
     wait_fetches(one_in_flight);
     __syncthreads();
   };
 
   if (n_tiles > 0) {
-    fetch_round(0, false);                   // rounds 0 .. 3: K(0 .. 3) and V(0 .. 2)
-    fetch_round(1, true);
-    fetch_round(2, true);
-    fetch_round(3, true);
+    fetch_round(0, stage0, false);           // rounds 0 .. 3: K(0 .. 3) and V(0 .. 2)
+    fetch_round(1, stage1, true);
+    fetch_round(2, stage2, true);
+    fetch_round(3, stage3, true);
     __builtin_amdgcn_s_waitcnt(0x0F70);
   }
   __syncthreads();
@@ -755,19 +802,39 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
       }
     });
     fence_scores(Sa);
-    mask(0, Sa);
+    mask(stage0, 0, Sa);
     static_for<16 * NS>([&](auto i) __attribute__((always_inline)) { max_step(i, Sa); });
-    qk_half(std::true_type{}, 1, Sa, Sb);
-    for (int t = 0; t < n_tiles; t += 2) {
-      body(t, Sa, Sb);
-      body(t + 1, Sb, Sa);
-      if ((t & 62) == 62) {                      // every 64 tiles
+    qk_half(std::true_type{}, stage1, Sa, Sb);
+    // Unrolled four times: the ring stage of every tile is then a constant of the code, and the
+    // stage offsets of all LDS reads sit in their offset fields instead of costing vector additions.
+    // An odd pair of bodies follows the loop (a second way out of the loop would do, but then the
+    // compiler keeps the wavefront-uniform loop state in vector registers).
+    const int n_pairs = (n_tiles + 1) / 2;
+    int t = 0;
+    for (int q = 0; q < n_pairs / 2; ++q, t += 4) {
+      body(stage0, t, Sa, Sb);
+      body(stage1, t + 1, Sb, Sa);
+      body(stage2, t + 2, Sa, Sb);
+      body(stage3, t + 3, Sb, Sa);
+      if ((t & 60) == 60) {                      // every 64 tiles
 #pragma unroll
         for (int s = 0; s < NS; ++s) { l_run[s] += l_lo[s]; l_lo[s] = 0.f; }
       }
     }
-    // the first V^T fragments of a tile nobody will use are still on their way into registers
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fl[0]), "+v"(fl[1]), "+v"(fl[2]), "+v"(fl[3]), "+v"(fh[0]), "+v"(fh[1]), "+v"(fh[2]), "+v"(fh[3]));
+    // The first V^T fragments of the next tile are still on their way into registers.  They are
+    // waited for here, where the stream ends; the odd pair of bodies asks for them again (the two
+    // paths then join with all registers landed: the compiler may copy them at the join).
+    auto drain = [&]() __attribute__((always_inline)) {
+      // (inputs only: that keeps the registers reserved up to here and asks for no copies)
+      asm volatile("s_waitcnt lgkmcnt(0)" : : "v"(fl[0]), "v"(fl[1]), "v"(fl[2]), "v"(fl[3]), "v"(fh[0]), "v"(fh[1]), "v"(fh[2]), "v"(fh[3]));
+    };
+    drain();
+    if (n_pairs & 1) {
+      static_for<PD>([&](auto f) __attribute__((always_inline)) { issue(std::integral_constant<int, NKF + decltype(f)::value>{}, stage2, stage0); });
+      body(stage0, t, Sa, Sb);
+      body(stage1, t + 1, Sb, Sa);
+      drain();
+    }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // no fetch may still be writing LDS when the workgroup ends
   if constexpr (PERSIST) __syncthreads();   //   or when any wavefront starts staging the next item there

@@ -47,6 +47,24 @@ __device__ inline void global_to_lds_16(const unsigned char* base, unsigned off,
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base));
 }
 
+// The same load through a buffer descriptor: lane l reads descriptor base + soff + off, where soff
+// is a scalar register.  A gather whose lanes share a moving base then needs no vector arithmetic
+// at all: the base moves in soff.  Raw descriptor (no stride, no swizzle), 2^32 - 1 records, so
+// every offset sum below 2^32 - 4 is in range; offsets are unsigned 32-bit, like the form above.
+__device__ inline u32x4 raw_buffer(const void* base) {
+  const unsigned long long b = reinterpret_cast<unsigned long long>(base);
+  u32x4 r;
+  r[0] = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(b)));
+  r[1] = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(b >> 32))) & 0xffffu;   // 48-bit address, stride 0
+  r[2] = 0xffffffffu;
+  r[3] = 0x00020000u;          // 32-bit data format, raw buffer
+  return r;
+}
+__device__ inline void buffer_to_lds_16(const u32x4& rsrc, unsigned soff, unsigned off, unsigned char* lds_base) {
+  const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)lds_base));
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" : : "s"(lds_addr), "v"(off), "s"(rsrc), "s"(soff));
+}
+
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); this maps the hardware
 // index to a work index such that every XCD gets one contiguous run of the work list.
 __device__ inline int xcd_contiguous(int block, int nblocks) {

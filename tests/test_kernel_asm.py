@@ -42,8 +42,15 @@ def test_attention_kernels_found(attn_asm):
         ops = [s.split()[0] for _, s in ks[k]]
         assert sum(o.startswith("v_mfma_f32_32x32x16_bf16") for o in ops) >= 32
         assert any(o == "ds_read_b64_tr_b16" for o in ops) and any(o == "ds_read_b128" for o in ops)
-        assert any(o == "global_load_lds_dwordx4" for o in ops)
         assert not any(o.startswith("flat_") for o in ops), k
+        # tile fetches: buffer loads straight into LDS.  Their asm statement asks for the descriptor
+        # and the moving offset in scalar registers; the compiler has been seen to hand over a vector
+        # register there (a wavefront-uniform value it had decided to keep in one), which assembles
+        # in this text form and is no valid instruction, so every one of them is checked.
+        loads = [s for _, s in ks[k] if s.startswith("buffer_load_dwordx4")]
+        assert len(loads) >= 8, (k, len(loads))
+        for s in loads:
+            assert re.fullmatch(r"buffer_load_dwordx4 v\d+, s\[\d+:\d+\], s\d+ offen lds", s), (k, s)
 
 
 def test_no_register_of_a_pending_lds_read_is_touched(attn_asm):
@@ -70,19 +77,24 @@ def test_no_spills_in_the_loop(attn_asm):
     assert asm_checks.scratch_in_loops(attn_asm, "ELb1EEEvNS_10AttnLaunch", min_depth=2) == []
 
 
+def _is_lds_load(s):
+    return s.startswith("global_load_lds_dwordx4") or (s.startswith("buffer_load_dwordx4") and s.endswith(" lds"))
+
+
 def _m0_misuse(instructions):
-    """Instructions that name m0 outside the one pattern the direct global->LDS load uses (its asm
-    statement: s_mov_b32 m0, <sgpr> / s_nop 0 / global_load_lds_dwordx4), and loads without it."""
+    """Instructions that name m0 outside the one pattern the direct global->LDS loads use (their asm
+    statement: s_mov_b32 m0, <sgpr> / s_nop 0 / global_load_lds_dwordx4 or buffer_load_dwordx4 .. lds),
+    and such loads without it."""
     ins = [(line, s) for line, s in instructions if not s.endswith(":")]
     bad = []
     for k, (line, s) in enumerate(ins):
         op = s.split()[0]
         if re.search(r"\bm0\b", s):
             ok = (op == "s_mov_b32" and s.split()[1].rstrip(",") == "m0" and k + 2 < len(ins)
-                  and ins[k + 1][1] == "s_nop 0" and ins[k + 2][1].startswith("global_load_lds_dwordx4"))
+                  and ins[k + 1][1] == "s_nop 0" and _is_lds_load(ins[k + 2][1]))
             if not ok:
                 bad.append((line, s))
-        if op.startswith("global_load_lds") and not (k >= 2 and ins[k - 2][1].startswith("s_mov_b32 m0,") and ins[k - 1][1] == "s_nop 0"):
+        if _is_lds_load(s) and not (k >= 2 and ins[k - 2][1].startswith("s_mov_b32 m0,") and ins[k - 1][1] == "s_nop 0"):
             bad.append((line, s))
     return bad
 
@@ -90,6 +102,8 @@ def _m0_misuse(instructions):
 def test_m0_checker_flags_planted_uses():
     good = [(1, "s_mov_b32 m0, s4"), (2, "s_nop 0"), (3, "global_load_lds_dwordx4 v1, s[2:3]")]
     assert _m0_misuse(good) == []
+    assert _m0_misuse([(1, "s_mov_b32 m0, s4"), (2, "s_nop 0"), (3, "buffer_load_dwordx4 v1, s[4:7], s9 offen lds")]) == []
+    assert [b[0] for b in _m0_misuse([(3, "buffer_load_dwordx4 v1, s[4:7], s9 offen lds")])] == [3]
     assert [b[0] for b in _m0_misuse(good + [(4, "v_readlane_b32 s5, v2, m0")])] == [4]
     assert [b[0] for b in _m0_misuse([(1, "s_mov_b32 m0, s4"), (2, "v_mov_b32_e32 v0, v1"), (3, "global_load_lds_dwordx4 v1, s[2:3]")])] == [1, 3]
 
@@ -100,7 +114,7 @@ def test_m0_belongs_to_the_direct_loads_only(attn_asm, bwd_asm):
     kernel that uses these loads, m0 appears in that statement's three instructions and nowhere else."""
     for asm in (attn_asm, bwd_asm):
         for name, ins in asm_checks.kernels(asm).items():
-            if any(s.startswith("global_load_lds") for _, s in ins):
+            if any(_is_lds_load(s) for _, s in ins):
                 assert _m0_misuse(ins) == [], (name, _m0_misuse(ins)[:3])
 
 
