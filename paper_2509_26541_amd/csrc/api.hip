@@ -107,7 +107,6 @@ int build_step(const tasp_schedule_t* s, const tasp_attn_args* a, int step, Attn
   }
   // the block with more keys goes first so that its workgroups are not the tail of the launch
   if (lp->n_tasks == 2 && keys[1] > keys[0]) std::swap(lp->task[0], lp->task[1]);
-  lp->max_keys = std::max(keys[0], keys[1]);
   return TASP_OK;
 }
 
@@ -156,7 +155,6 @@ int build_all_steps(const tasp_schedule_t* s, const tasp_attn_args* a, int32_t* 
     std::swap(all->task[0], all->task[1]);
     std::swap(all->seg_ext[0], all->seg_ext[1]);
   }
-  all->max_keys = std::max(keys[0], keys[1]);
   return TASP_OK;
 }
 

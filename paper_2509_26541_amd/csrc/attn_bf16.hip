@@ -933,18 +933,16 @@ hipError_t launch_variant(const AttnLaunch& p0, hipStream_t stream) {
 hipError_t launch_attn_bf16(const AttnLaunch& p, int d, hipStream_t stream) {
   if (d == 128) return launch_variant<128, 1, 8>(p, stream);
   if (d == 64) {
-    // At d = 64 the kernel needs 160 registers, so three wavefronts fit a SIMD (twelve per
-    // workgroup, 384 query rows): measured 5-15 % faster than eight when the query blocks fill
-    // 384-row tiles as well as 256-row tiles; 3 % more padding already eats the gain.  With all
-    // steps in one launch the eight-wavefront form runs as persistent workgroups, which is worth
-    // more than the third wavefront as long as a work item is short (up to 256 key tiles).
+    // At d = 64 the kernel needs 168 registers, so three wavefronts fit a SIMD (twelve per
+    // workgroup, 384 query rows): measured 5-40 % faster than eight when the query blocks fill
+    // 384-row tiles as well as 256-row tiles; 3 % more padding already eats the gain.  Where eight
+    // are launched and all steps are in one launch, they run as persistent workgroups.
     int64_t rows8 = 0, rows12 = 0;
     for (int t = 0; t < p.n_tasks; ++t) {
       rows8 += (p.task[t].n_q + 255) / 256 * 256;
       rows12 += (p.task[t].n_q + 383) / 384 * 384;
     }
-    const bool short_items = p.seg_ext[0] != nullptr && p.max_keys <= 256 * BN;
-    return rows12 * 100 <= rows8 * 101 && !short_items ? launch_variant<64, 1, 12>(p, stream) : launch_variant<64, 1, 8>(p, stream);
+    return rows12 * 100 <= rows8 * 101 ? launch_variant<64, 1, 12>(p, stream) : launch_variant<64, 1, 8>(p, stream);
   }
   return hipErrorInvalidValue;
 }

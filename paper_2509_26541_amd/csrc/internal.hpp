@@ -39,7 +39,6 @@ struct AttnLaunch {
   // memory as task[t].n_seg (start, end) pairs; task[t].seg_start / seg_end are then unused.
   const int32_t* seg_ext[kMaxTasks];
   int32_t n_items;    // work items of the launch, for persistent workgroups; filled in by the launcher
-  int64_t max_keys;   // most keys one query block of the launch attends to (for the launcher's choice of a variant)
 };
 
 // One contiguous run of local query rows (a half-chunk of the zig-zag layout, or all rows).

@@ -66,6 +66,9 @@ SMALL = [
     ("bf16_full_d64", 2, 8, 5, 8 * 200, 2, 2, 64),
     ("bf16_zz_d64_w12", 1, 8, 2, 16 * 768, 2, 1, 64),           # half-chunks of 768 rows: the twelve-wavefront variant (384-row tiles)
     ("bf16_full_d64_w12", 2, 8, 6, 8 * 1152, 2, 2, 64),         # L = 1152 = 3 x 384
+    ("bf16_zz_d64_mha12", 1, 8, 1, 2048, 12, 12, 64),          # 12 KV heads: pairs of XCDs share three heads
+    ("bf16_full_gqa_kv6", 2, 8, 4, 8 * 256, 12, 6, 128),       # 6 KV heads: four XCDs share three heads
+    ("bf16_zz_kv3", 1, 8, 6, 8 * 2 * 72, 3, 3, 128),           # 3 KV heads: all XCDs share them
     ("fp32_zz_n8", 0, 8, 4, 8 * 2 * 40, 2, 2, 64),
     ("fp32_full_d128", 0, 4, 1, 4 * 70, 2, 1, 128),
 ]

@@ -52,6 +52,8 @@ SMALL = [
     ("zz_n8_outliers", 8, 7, 4096, 4, 2, 128, wl.ZIGZAG_CAUSAL, 4),
     ("zz_d64", 8, 2, 4096, 4, 2, 64, wl.ZIGZAG_CAUSAL, 1),
     ("full_d64", 8, 5, 8 * 200, 2, 2, 64, wl.FULL, 2),
+    ("zz_d64_mha12", 8, 1, 2048, 12, 12, 64, wl.ZIGZAG_CAUSAL, 1),           # 12 KV heads: pairs of XCDs share three heads
+    ("full_gqa_kv3", 8, 4, 8 * 160, 6, 3, 128, wl.FULL, 2),                  # 3 KV heads: all XCDs share them
 ]
 
 
