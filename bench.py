@@ -36,14 +36,26 @@ N_SIMD, CLOCK_HZ = 256 * 4, 2.4e9
 # (from the generated code); flops of that unit of work divided by its port cycles, times the chip's
 # SIMDs and the nominal clock, is the rate at which the port alone would let the kernel run.
 PORT_CYCLES = {"mfma": 12, "valu": 4, "exp": 8, "lds_kib": 4}
-TILE_MIX = {128: {"mfma": 32, "valu": 147, "exp": 32, "lds_kib": 32},
-            64: {"mfma": 16, "valu": 131, "exp": 32, "lds_kib": 16}}
+TILE_MIX = {128: {"mfma": 32, "valu": 107, "exp": 33, "lds_kib": 32},
+            64: {"mfma": 16, "valu": 105, "exp": 33, "lds_kib": 16}}
 
 
 def valu_peak_tflops(d):
     mix = TILE_MIX[d]
     cycles = sum(PORT_CYCLES[k] * n for k, n in mix.items())
     return 4.0 * d * 32 * 64 / cycles * N_SIMD * CLOCK_HZ / 1e12
+
+
+def measure_port_cycles(tb):
+    """The port-cycle figures above, measured on this GPU (tasp_calibration_issue): a slot of one
+    matrix instruction and n instructions of a kind, issued by two wavefronts per SIMD, lasts
+    2 x (matrix + n x kind) port cycles once the port bounds it; two values of n give both terms."""
+    f8, f12 = tb.tasp_calibration_issue(0, 8), tb.tasp_calibration_issue(0, 12)
+    e4, e8 = tb.tasp_calibration_issue(1, 4), tb.tasp_calibration_issue(1, 8)
+    l1, l2 = tb.tasp_calibration_issue(2, 1), tb.tasp_calibration_issue(2, 2)
+    valu = (f12 - f8) / 8.0
+    return {"valu": valu, "mfma": f8 / 2.0 - 8.0 * valu, "exp": (e8 - e4) / 8.0, "lds_kib": (l2 - l1) / 2.0,
+            "cycles_per_slot": {"fma8": f8, "fma12": f12, "exp4": e4, "exp8": e8, "fma8_lds1": l1, "fma8_lds2": l2}}
 
 
 def cpu_baseline(w, q, k, v, budget_s=12.0):
@@ -271,7 +283,8 @@ def main():
     if is_bf16:
         vp = valu_peak_tflops(w.d)
         roofline_valu = {"bound": "valu", "kernel": "attn_bf16_kernel", "achieved": achieved, "peak": vp, "unit": "TFLOP/s",
-                         "frac": achieved / vp, "port_cycles": PORT_CYCLES, "per_tile_and_wavefront": TILE_MIX[w.d]}
+                         "frac": achieved / vp, "port_cycles": PORT_CYCLES, "per_tile_and_wavefront": TILE_MIX[w.d],
+                         "port_cycles_measured": measure_port_cycles(tb)}
     def merge_stats(ms_total, launches, calls):
         # update_out_lse: per (row, head) read 2(4d+4) and write 4d+4 bytes; rows merged per call =
         # all rows of every task of steps 1..N-1

@@ -247,6 +247,19 @@ int tasp_calibration_copy(void* dst, const void* src, size_t bytes, void* hip_st
  * load, next to which a fraction of the published peak can be read.  iters in [1, 1 << 20]. */
 int tasp_calibration_mfma(int32_t iters, double* flops, void* hip_stream);
 
+/* Issue-cost calibration of the vector issue port of a SIMD.  256 workgroups of eight wavefronts
+ * (two per SIMD) repeat `iters` x 4 slots of one v_mfma_f32_32x32x16_bf16 followed by
+ *   kind 0: per_slot (8 or 12) v_fma_f32,   kind 1: per_slot (4 or 8) v_exp_f32,
+ *   kind 2: eight v_fma_f32 and per_slot (1 or 2) ds_read_b128 (1 KiB of LDS data per wavefront each);
+ * cycles_per_slot_x16 (DEVICE pointer, 256 x 8 int64) receives, per workgroup and wavefront, 16 x
+ * the shader-clock cycles per slot.  The slowest wavefront of a workgroup gives the time in which
+ * its SIMD issued two slots: 2 x (matrix instruction + the rest) port cycles, so two values of
+ * per_slot price both terms.  Not part of the method: it is the measurement behind the port-cycle
+ * figures with which a caller bounds the attention kernel by vector issue.  iters in [1, 1 << 20];
+ * other (kind, per_slot) pairs return TASP_EINVAL. */
+int tasp_calibration_issue(int32_t kind, int32_t per_slot, int32_t iters, int64_t* cycles_per_slot_x16,
+                           void* hip_stream);
+
 /* Algorithmic work of one tasp_chunk_attn call: 4*d*Hq*(visible (query,key) pairs). */
 double tasp_chunk_attn_flops(const tasp_schedule_t* s, const tasp_attn_args* a);
 

@@ -25,7 +25,7 @@ EXPORTS = [
     "tasp_schedule_out_mapping", "tasp_schedule_in_mapping", "tasp_schedule_arrival", "tasp_subchunk_ranges",
     "tasp_step_segments", "tasp_chunk_attn_workspace_bytes", "tasp_chunk_attn", "tasp_step_attn",
     "tasp_lse_merge", "tasp_chunk_attn_flops", "tasp_chunk_attn_profile", "tasp_last_hip_error", "tasp_calibration_copy",
-    "tasp_lse_merge_many", "tasp_calibration_mfma", "tasp_schedule_create_multinode",
+    "tasp_lse_merge_many", "tasp_calibration_mfma", "tasp_calibration_issue", "tasp_schedule_create_multinode",
     "tasp_chunk_attn_bwd_workspace_bytes", "tasp_chunk_attn_bwd", "tasp_chunk_attn_bwd_profile",
     "tasp_chunk_attn_bwd_flops", "tasp_chunk_attn_static",
 ]
@@ -112,6 +112,7 @@ def _load():
     lib.tasp_lse_merge_many.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32,
                                         C.c_int64, C.c_int32, C.c_int32, C.c_void_p]
     lib.tasp_calibration_mfma.argtypes = [C.c_int32, C.POINTER(C.c_double), C.c_void_p]
+    lib.tasp_calibration_issue.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.tasp_chunk_attn_flops.argtypes = [C.c_void_p, C.POINTER(AttnArgs)]
     lib.tasp_chunk_attn_flops.restype = C.c_double
     lib.tasp_chunk_attn_bwd_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(AttnBwdArgs)]
@@ -362,6 +363,19 @@ def tasp_calibration_mfma(iters):
     s = torch.cuda.current_stream().cuda_stream
     _check(lib.tasp_calibration_mfma(int(iters), C.byref(flops), C.c_void_p(s)), "tasp_calibration_mfma")
     return flops.value
+
+
+def tasp_calibration_issue(kind, per_slot, iters=2000):
+    """Shader-clock cycles per slot of the issue-cost calibration (kind 0: per_slot fma, 1: per_slot
+    exp, 2: eight fma + per_slot ds_read_b128, each behind one matrix instruction): the slowest
+    wavefront of each of the 256 workgroups, averaged over the workgroups."""
+    torch = _torch()
+    out = torch.zeros((256, 8), dtype=torch.int64, device="cuda")
+    s = torch.cuda.current_stream().cuda_stream
+    _check(lib.tasp_calibration_issue(int(kind), int(per_slot), int(iters), out.data_ptr(), C.c_void_p(s)),
+           "tasp_calibration_issue")
+    torch.cuda.synchronize()
+    return float(out.max(dim=1).values.double().mean()) / 16.0
 
 
 def tasp_lse_merge_many(o_parts, lse_parts, o_out=None, lse_out=None):

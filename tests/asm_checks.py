@@ -159,6 +159,48 @@ def in_flight_violations(instructions):
     return sorted(bad)
 
 
+def tile_body_mix(instructions):
+    """Instruction mix of one 64-key tile on the common path of the attention kernel's key loop: the
+    instructions between two consecutive barriers of the loop (the first such stretch that holds at
+    least 16 matrix instructions, after the barriers of the set-up), following the fall-through of
+    every conditional branch except s_cbranch_vccz, which is taken when no row's maximum has grown.
+    Returns {"mfma", "valu" (vector instructions other than matrix and exponential), "exp",
+    "lds_kib" (KiB returned by LDS reads to a wavefront), "other"}."""
+    ins = list(instructions)
+    bars = [k for k, (_, s) in enumerate(ins) if s == "s_barrier"]
+    seg = None
+    for j in range(3, len(bars) - 1):
+        if sum(1 for _, s in ins[bars[j]:bars[j + 1]] if s.startswith("v_mfma")) >= 16:
+            seg = ins[bars[j] + 1:bars[j + 1] + 1]
+            break
+    assert seg is not None
+    label_at = {s[:-1]: k for k, (_, s) in enumerate(seg) if s.endswith(":")}
+    mix = {"mfma": 0, "valu": 0, "exp": 0, "lds_kib": 0.0, "other": 0}
+    k = 0
+    while k < len(seg):
+        s = seg[k][1]
+        op = s.split()[0]
+        if op == "s_cbranch_vccz" and label_at.get(s.split()[-1], -1) > k:
+            k = label_at[s.split()[-1]]
+            continue
+        k += 1
+        if s.endswith(":"):
+            continue
+        if op.startswith("v_mfma"):
+            mix["mfma"] += 1
+        elif op.startswith("v_exp"):
+            mix["exp"] += 1
+        elif op.startswith("v_"):
+            mix["valu"] += 1
+        else:
+            mix["other"] += 1
+            if op == "ds_read_b128":
+                mix["lds_kib"] += 1.0
+            elif op.startswith("ds_read_b64"):
+                mix["lds_kib"] += 0.5
+    return mix
+
+
 def spill_report(asm):
     """(kernel, vgpr_spill_count, private_segment_fixed_size) per kernel from the metadata block."""
     out = []

@@ -256,6 +256,17 @@ BATCHED = [
 ]
 
 
+def test_calibration_issue_prices_the_vector_port(tb):
+    """The figures bench.py uses for the vector issue port (matrix 12, vector 4, exponential 8, KiB of
+    LDS data 4 cycles) against what the calibration kernel measures on this GPU."""
+    import bench
+    got = bench.measure_port_cycles(tb)
+    for name, want in (("mfma", 12.0), ("valu", 4.0), ("exp", 8.0), ("lds_kib", 4.0)):
+        assert abs(got[name] - want) <= 0.25 * want, got
+    with pytest.raises(tb.TaspError):
+        tb.tasp_calibration_issue(0, 5)
+
+
 def test_paper_grid_shape_batched(tb):
     """A shape of the paper's own grid (Sec. 5.1.2: 12 heads of 64, its shortest sequence 3K) with a
     batch of 3: every row of every sequence against the oracle."""

@@ -53,6 +53,19 @@ def test_attention_kernels_found(attn_asm):
             assert re.fullmatch(r"buffer_load_dwordx4 v\d+, s\[\d+:\d+\], s\d+ offen lds", s), (k, s)
 
 
+def test_bench_tile_mix_matches_the_generated_code(attn_asm):
+    """bench.py prices the vector issue port with the instruction mix of one key tile; the counts it
+    uses are those of the generated code (a few vector instructions of slack for compiler versions)."""
+    import bench
+    for name, ins in asm_checks.kernels(attn_asm).items():
+        if "attn_bf16_kernel" not in name:
+            continue
+        d = 128 if "ILi128E" in name else 64
+        mix, want = asm_checks.tile_body_mix(ins), bench.TILE_MIX[d]
+        assert mix["mfma"] == want["mfma"] and mix["lds_kib"] == want["lds_kib"], (name, mix)
+        assert abs(mix["exp"] - want["exp"]) <= 1 and abs(mix["valu"] - want["valu"]) <= 4, (name, mix)
+
+
 def test_no_register_of_a_pending_lds_read_is_touched(attn_asm):
     for name, ins in asm_checks.kernels(attn_asm).items():
         if "attn_bf16_kernel" not in name:
