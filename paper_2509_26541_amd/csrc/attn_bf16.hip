@@ -19,17 +19,19 @@
 // barrier of a tile either), the softmax arithmetic of tiles t and t+1 is dealt out between them,
 // operand fragments are read four ahead (two would do: the depth from 2 to 8 makes no measurable
 // difference).  Matrix instructions and LDS reads are volatile assembly, so their order is the
-// schedule.
+// schedule.  K and V tiles arrive in two LDS rings of four tiles each through buffer loads that
+// write LDS directly; the loop is unrolled four times, so that the ring stage of every tile is a
+// constant and sits in the offset field of the LDS reads.
 //
 // What bounds it (measured with issue microbenchmarks on this chip): the vector issue port of a
 // SIMD.  A matrix instruction occupies it for 12 cycles (and its own pipe for 32), a plain vector
 // instruction for 4, an exponential for 8, and every KiB of LDS data returned to registers for
-// about 4 more; per 64-key tile and wavefront that is 32 x 12 + ~115 x 4 + 32 x 8 + 32 x 4 cycles,
+// about 4 more; per 64-key tile and wavefront that is 32 x 12 + 107 x 4 + 33 x 8 + 32 x 4 cycles,
 // for two wavefronts more than the 2 048 cycles the matrix pipe needs.  So every vector instruction
-// in the loop counts (the scalar bookkeeping of the loader, the waits folded into the matrix
-// instructions, the few branches), and beyond that the chip's power limit: with operands of
-// ordinary statistics the clock falls as the pipes fill (1.55 - 1.7 GHz in this kernel against
-// 2.4 GHz nominal), so cycles saved come back only in part.
+// in the loop counts (hence the scalar bookkeeping of the loader, the stage offsets in the offset
+// fields, the waits folded into the matrix instructions, the few branches), and beyond that the
+// chip's power limit: with operands of ordinary statistics the clock falls as the pipes fill
+// (about 1.7 GHz in this kernel against 2.4 GHz nominal), so cycles saved come back only in part.
 //
 // A wavefront owns NS strips.  NS = 1 (eight wavefronts, two per SIMD) is what the library
 // launches.  NS = 2 (each LDS fragment feeds two matrix instructions, O^T and Q in AGPRs, one
