@@ -699,14 +699,24 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
   // arbiter always takes the one that was launched first: left alone, the first four wavefronts
   // of the workgroup finish a body in 2 700 cycles and wait 700 at the barrier while the other four,
   // which got what slots were left, take 3 300.  So every wavefront lowers its own priority as it
-  // moves through a body (3, 2, 1, 0 by quarters): whoever is behind outranks whoever is ahead, and
-  // all reach the barrier within about a hundred cycles of each other.  No branch is involved.
+  // moves through a body: whoever is behind outranks whoever is ahead.  At equal priority the
+  // older wavefront still wins, so the steps come late and ever closer together (3 up to 5/8 of
+  // the body, 2 up to 13/16, 1 up to 15/16, then 0): the stretch before the barrier in which the
+  // older one can gain on the younger is short, and they arrive within about sixty cycles of
+  // each other (even quarters: two hundred).  No branch is involved.
   constexpr std::integral_constant<int, 1> one_in_flight{};
   // fragment g of the cyclic stream that starts with the V^T fragments of tile tv and goes on with the K fragments of tile tk
   auto issue_cyc = [&](auto gg_, auto sk_, auto sv_) __attribute__((always_inline)) {
     constexpr int G = decltype(gg_)::value;
     if constexpr (G < NVF) issue(std::integral_constant<int, NKF + G>{}, sk_, sv_);
     else issue(std::integral_constant<int, G - NVF>{}, sk_, sv_);
+  };
+  // the priority ladder of a body (above): position g of its NF matrix instructions
+  auto lower_prio = [](auto gg_) __attribute__((always_inline)) {
+    constexpr int G = decltype(gg_)::value;
+    if constexpr (G == NF * 5 / 8) __builtin_amdgcn_s_setprio(2);
+    if constexpr (G == NF * 13 / 16) __builtin_amdgcn_s_setprio(1);
+    if constexpr (G == NF * 15 / 16) __builtin_amdgcn_s_setprio(0);
   };
   // Second product of tile t: S_cur = S(t), S_next = S(t+1).  Its trailing reads are the first K fragments of tile t+2.
   // ts_ = t % 4, the ring stage of tile t, at compile time (the loop is unrolled four times).
@@ -717,7 +727,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
     static_for<NVF>([&](auto gg_) __attribute__((always_inline)) {
       constexpr int G = decltype(gg_)::value, F = NKF + G, slot = F % PD, W = younger(F);
       constexpr int gg = G / DB, db = G % DB;
-      if constexpr (2 * G == NVF) __builtin_amdgcn_s_setprio(2);
+      lower_prio(std::integral_constant<int, G>{});
       if constexpr (G == 1) fetch_begin(t + 4, ts_);
       if constexpr (db == 0) {
 #pragma unroll
@@ -748,7 +758,6 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
     constexpr std::integral_constant<int, T2S> sk_{};
     constexpr std::integral_constant<int, (T2S + 3) & 3> sv_{};
     if constexpr (PRIME) static_for<PD>([&](auto f) __attribute__((always_inline)) { issue(f, sk_, sv_); });
-    else __builtin_amdgcn_s_setprio(1);
     raise_max();                                  // of S_cur
 #pragma unroll
     for (int s = 0; s < NS; ++s) {                // what rounding adds to this lane's largest probability of the tile
@@ -760,7 +769,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
     static_for<NKF>([&](auto ff) __attribute__((always_inline)) {
       constexpr int F = decltype(ff)::value, slot = F % PD, W = younger(F), G = NVF + F;
       constexpr int ks = F / 2, kb = F % 2;
-      if constexpr (!PRIME && 2 * F == NKF) __builtin_amdgcn_s_setprio(0);
+      if constexpr (!PRIME) lower_prio(std::integral_constant<int, G>{});
       static_for<NS>([&](auto ss) __attribute__((always_inline)) {
         constexpr int s = decltype(ss)::value, WW = s == 0 ? W : -1;
         if constexpr (ks == 0) mfma_s_first<ACC, WW>(S_next[s][kb], fk[slot], qf[s][0]);
