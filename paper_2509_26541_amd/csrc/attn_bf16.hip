@@ -800,17 +800,18 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
 
   if (n_tiles > 0) {
     f32x16 Sa[NS][2], Sb[NS][2];
-    // scores, mask and row maxima of tile 0, not pipelined
+    // scores, mask and row maxima of tile 0: no vector work beside them, but the K fragments are
+    // read PD ahead as in the loop (one LDS round trip instead of one per fragment)
+    static_for<PD>([&](auto f) __attribute__((always_inline)) { issue(f, stage0, stage0); });
     static_for<NKF>([&](auto ff) __attribute__((always_inline)) {
-      constexpr int F = decltype(ff)::value, ks = F / 2, kb = F % 2;
-      u32x4 f;
-      lds_read_b128<kb * 32 * D * 2>(f, kadr[ks]);
-      lds_wait<0>(f);
-#pragma unroll
-      for (int s = 0; s < NS; ++s) {
-        if constexpr (ks == 0) mfma_s_first<ACC>(Sa[s][kb], f, qf[s][0]);
-        else mfma_s<ACC>(Sa[s][kb], f, qf[s][ks]);
-      }
+      constexpr int F = decltype(ff)::value, slot = F % PD, ks = F / 2, kb = F % 2;
+      constexpr int W = NKF - 1 - F < PD - 1 ? NKF - 1 - F : PD - 1;     // K fragments read after this one
+      static_for<NS>([&](auto ss) __attribute__((always_inline)) {
+        constexpr int s = decltype(ss)::value, WW = s == 0 ? W : -1;
+        if constexpr (ks == 0) mfma_s_first<ACC, WW>(Sa[s][kb], fk[slot], qf[s][0]);
+        else mfma_s<ACC, WW>(Sa[s][kb], fk[slot], qf[s][ks]);
+      });
+      if constexpr (F + PD < NKF) issue(std::integral_constant<int, F + PD>{}, stage0, stage0);
     });
     fence_scores(Sa);
     mask(stage0, 0, Sa);
