@@ -217,26 +217,49 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const unsigned char* Kg = static_cast<const unsigned char*>(p.k) + (bi * p.kv_bstride + static_cast<int64_t>(g) * D) * 2;
   const unsigned char* Vg = static_cast<const unsigned char*>(p.v) + (bi * p.kv_bstride + static_cast<int64_t>(g) * D) * 2;
-  int segi[C::PASSES];
+  // Row bookkeeping as in the forward kernel: a wavefront-load covers RW consecutive rows of the
+  // tile, and while these are consecutive keys of one effective segment everything about them is
+  // wavefront-uniform (w_tok = global position of the first, w_left = keys from it to the end of its
+  // segment, w_seg = the segment): the loads take the row's byte offset as their scalar offset and
+  // a lane constant, and nothing is searched.  Otherwise every lane finds its own row.
+  constexpr int RW = 64 / C::UNITS;
+  const int r_lane = lane / C::UNITS;
+  const unsigned lane_const = static_cast<unsigned>(r_lane) * row_bytes + col;
+  const u32x4 k_buf = raw_buffer(Kg), v_buf = raw_buffer(Vg);
+  int w_tok[C::PASSES], w_left[C::PASSES], w_seg[C::PASSES];
 #pragma unroll
-  for (int i = 0; i < C::PASSES; ++i) segi[i] = 0;
+  for (int i = 0; i < C::PASSES; ++i) { w_tok[i] = 0; w_left[i] = 0; w_seg[i] = 0; }
   auto fetch = [&](int t, int stage) __attribute__((always_inline)) {
     unsigned char* dst = smem + stage * C::STAGE_BYTES + wave_u * 1024;
-    bool hidden = false;
+    int any_hidden = 0;
 #pragma unroll
     for (int i = 0; i < C::PASSES; ++i) {
-      const int r = fr + C::RPP * i, v = t * BT + r;
-      int j = segi[i];
-      while (j < n_eff && v >= e_vbeg[j + 1]) ++j;       // rows only move forward
-      segi[i] = j;
-      const int tok = j < n_eff ? v + e_goff[j] : INT_MAX;
-      hidden |= tok > q_first;
-      s_tok[stage][r] = tok;                              // the UNITS lanes of a row write the same value
-      const unsigned off = (tok == INT_MAX ? 0u : static_cast<unsigned>(tok)) * row_bytes + col;
-      dma16(Kg, off, dst + i * NTHREADS * 16);
-      dma16(Vg, off, dst + C::TILE_BYTES + i * NTHREADS * 16);
+      const int r = fr + C::RPP * i;
+      w_left[i] -= BT;                                      // tile 0: from 0, i.e. search
+      w_tok[i] += BT;
+      asm volatile("" : "+s"(w_tok[i]), "+s"(w_left[i]));   // (kept in scalar registers)
+      if (__builtin_expect(w_left[i] >= RW, 1)) {
+        s_tok[stage][r] = w_tok[i] + r_lane;                // the UNITS lanes of a row write the same value
+        any_hidden |= w_tok[i] + RW - 1 > q_first ? 1 : 0;
+        const unsigned soff = static_cast<unsigned>(w_tok[i]) * row_bytes;
+        buffer_to_lds_16<true>(k_buf, soff, lane_const, dst + i * NTHREADS * 16);
+        buffer_to_lds_16<true>(v_buf, soff, lane_const, dst + C::TILE_BYTES + i * NTHREADS * 16);
+      } else {
+        const int v = t * BT + r;
+        int j = w_seg[i];
+        while (j < n_eff && v >= e_vbeg[j + 1]) ++j;       // rows only move forward
+        const int tok = j < n_eff ? v + e_goff[j] : INT_MAX;
+        const int left = j < n_eff ? e_vbeg[j + 1] - v : 0;   // past the last key: searched again next time
+        w_tok[i] = __builtin_amdgcn_readfirstlane(tok);
+        w_left[i] = __builtin_amdgcn_readfirstlane(left);
+        w_seg[i] = __builtin_amdgcn_readfirstlane(j);
+        any_hidden |= __builtin_amdgcn_ballot_w64(tok > q_first) != 0 ? 1 : 0;
+        s_tok[stage][r] = tok;
+        const unsigned off = (tok == INT_MAX ? 0u : static_cast<unsigned>(tok)) * row_bytes + col;
+        buffer_to_lds_16<true>(k_buf, 0u, off, dst + i * NTHREADS * 16);
+        buffer_to_lds_16<true>(v_buf, 0u, off, dst + C::TILE_BYTES + i * NTHREADS * 16);
+      }
     }
-    const int any_hidden = __builtin_amdgcn_ballot_w64(hidden) != 0 ? 1 : 0;
     if (lane == 0) s_msk[stage][wave] = any_hidden;
   };
 

@@ -60,9 +60,13 @@ __device__ inline u32x4 raw_buffer(const void* base) {
   r[3] = 0x00020000u;          // 32-bit data format, raw buffer
   return r;
 }
+template <bool FENCE = false>
 __device__ inline void buffer_to_lds_16(const u32x4& rsrc, unsigned soff, unsigned off, unsigned char* lds_base) {
   const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)lds_base));
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" : : "s"(lds_addr), "v"(off), "s"(rsrc), "s"(soff));
+  if constexpr (FENCE)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" : : "s"(lds_addr), "v"(off), "s"(rsrc), "s"(soff) : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" : : "s"(lds_addr), "v"(off), "s"(rsrc), "s"(soff));
 }
 
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); this maps the hardware

@@ -146,7 +146,10 @@ def test_backward_kernels_shape_and_register_budget(bwd_asm):
         ops = [s.split()[0] for _, s in ins]
         mf = [i for i, o in enumerate(ops) if o.startswith("v_mfma_f32_32x32x16_bf16")]
         assert len(mf) >= 24, (name, len(mf))
-        assert "ds_read_b64_tr_b16" in ops and "ds_read_b128" in ops and "global_load_lds_dwordx4" in ops
+        assert "ds_read_b64_tr_b16" in ops and "ds_read_b128" in ops
+        assert "global_load_lds_dwordx4" in ops or "buffer_load_dwordx4" in ops
+        for s in (s for _, s in ins if s.startswith("buffer_load_dwordx4")):      # descriptor and offset in scalar registers
+            assert re.fullmatch(r"buffer_load_dwordx4 v\d+, s\[\d+:\d+\], (s\d+|0) offen lds", s), (name, s)
         assert not any(o.startswith("flat_load") or o.startswith("flat_store") for o in ops), name
         assert budget[name] <= 256, (name, budget[name])
         spills = [i for i, o in enumerate(ops) if o.startswith("scratch_")]
