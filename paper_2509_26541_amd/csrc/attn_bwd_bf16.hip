@@ -229,11 +229,12 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
   int w_tok[C::PASSES], w_left[C::PASSES], w_seg[C::PASSES];
 #pragma unroll
   for (int i = 0; i < C::PASSES; ++i) { w_tok[i] = 0; w_left[i] = 0; w_seg[i] = 0; }
-  auto fetch = [&](int t, int stage) __attribute__((always_inline)) {
+  int any_hidden = 0;
+  auto fetch_pass = [&](auto ii, int t, int stage) __attribute__((always_inline)) {
+    constexpr int i = decltype(ii)::value;
     unsigned char* dst = smem + stage * C::STAGE_BYTES + wave_u * 1024;
-    int any_hidden = 0;
-#pragma unroll
-    for (int i = 0; i < C::PASSES; ++i) {
+    if constexpr (i == 0) any_hidden = 0;
+    {
       const int r = fr + C::RPP * i;
       w_left[i] -= BT;                                      // tile 0: from 0, i.e. search
       w_tok[i] += BT;
@@ -260,7 +261,10 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
         buffer_to_lds_16<true>(v_buf, 0u, off, dst + C::TILE_BYTES + i * NTHREADS * 16);
       }
     }
-    if (lane == 0) s_msk[stage][wave] = any_hidden;
+    if constexpr (i == C::PASSES - 1) { if (lane == 0) s_msk[stage][wave] = any_hidden; }
+  };
+  auto fetch = [&](int t, int stage) __attribute__((always_inline)) {
+    static_for<C::PASSES>([&](auto ii) __attribute__((always_inline)) { fetch_pass(ii, t, stage); });
   };
 
   ReadAddr<D> ra;
@@ -291,7 +295,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
     const int stage = t & 1;
     wait_all_loads();
     __syncthreads();                 // tile t is complete; nobody reads the other stage any more
-    if (t + 1 < n_tiles) fetch(t + 1, stage ^ 1);
+    const bool more = t + 1 < n_tiles;
     const unsigned char* kt = smem + stage * C::STAGE_BYTES;
     const unsigned char* vt = kt + C::TILE_BYTES;
     // most tiles are seen completely by every row: the element-wise mask is skipped for them
@@ -347,6 +351,8 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
         dq[db] = mfma(ring[slot], __builtin_bit_cast(bf16x8, ef[j]), dq[db]);
       }
       if constexpr (F + PD < NFT) issue(std::integral_constant<int, F + PD>{}, kt, vt);
+      // the fetch of the next tile, one pass at a time between the matrix instructions
+      if constexpr (F % (NFT / C::PASSES) == 1) { if (more) fetch_pass(std::integral_constant<int, F / (NFT / C::PASSES)>{}, t + 1, stage ^ 1); }
       __builtin_amdgcn_sched_barrier(0);
     });
   }
