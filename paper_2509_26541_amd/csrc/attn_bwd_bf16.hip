@@ -481,18 +481,22 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
   const unsigned char* Qg = static_cast<const unsigned char*>(p.q) + bi * p.q_bstride * 2;
   const unsigned char* Og = static_cast<const unsigned char*>(p.dout) + bi * p.q_bstride * 2;
   const unsigned q_row_bytes = static_cast<unsigned>(p.Hq) * D * 2;
-  auto fetch = [&](const It& it, int stage) __attribute__((always_inline)) {
+  // The fetch of a tile comes in pieces (pass i = the Q and dout rows fr + RPP i; lse and delta of
+  // the tile's queries with the last one) that the loop drops between its matrix instructions: a
+  // burst of direct loads stalls the issuing wavefront once its queue is full.
+  static_assert(C::PASSES == 2, "the loop places two fetch pieces per tile");
+  auto fetch_pass = [&](auto ii, const It& it, int stage) __attribute__((always_inline)) {
+    constexpr int i = decltype(ii)::value;
     const BwdBlock& B = p.blk[it.blk];
     const int hq = g * G + it.hh;
     unsigned char* dst = smem + stage * C::STAGE_BYTES + wave_u * 1024;
-#pragma unroll
-    for (int i = 0; i < C::PASSES; ++i) {
+    {
       const int r = min(it.qt * BT + fr + C::RPP * i, B.n - 1);      // rows past the end repeat the last one and are switched off below
       const unsigned off = static_cast<unsigned>(B.row0 + r) * q_row_bytes + static_cast<unsigned>(hq) * D * 2 + col;
       dma16(Qg, off, dst + i * NTHREADS * 16);
       dma16(Og, off, dst + C::TILE_BYTES + i * NTHREADS * 16);
     }
-    if (tid < BT) {
+    if constexpr (i == C::PASSES - 1) if (tid < BT) {
       const int r = it.qt * BT + tid;
       float l2 = __builtin_inff(), dl = 0.f;
       if (r < B.n) {
@@ -504,6 +508,9 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
       s_l2[stage][tid] = l2;
       s_dl[stage][tid] = dl;
     }
+  };
+  auto fetch = [&](const It& it, int stage) __attribute__((always_inline)) {
+    static_for<C::PASSES>([&](auto ii) __attribute__((always_inline)) { fetch_pass(ii, it, stage); });
   };
 
   ReadAddr<D> ra;
@@ -554,7 +561,8 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
     const It nxt = settle(It{cur.hh + 1, cur.blk, cur.qt});
     wait_all_loads();
     __syncthreads();                 // the current tile is complete; nobody reads the other stage any more
-    if (nxt.blk >= 0) fetch(nxt, stage ^ 1);
+    const bool more = nxt.blk >= 0;
+    if (more) fetch_pass(std::integral_constant<int, 0>{}, nxt, stage ^ 1);
     const unsigned char* qt_ = smem + stage * C::STAGE_BYTES;
     const unsigned char* ot_ = qt_ + C::TILE_BYTES;
     const int pos0 = p.causal ? p.blk[cur.blk].pos0 + cur.qt * BT : 0;
@@ -640,6 +648,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
             dk[db] = mfma(lds_tr8(qt_ + ra.tr[db][0] + grp, qt_ + ra.tr[db][1] + grp), eb[j], dk[db]);
         }
         __builtin_amdgcn_sched_barrier(0);
+        if (qb == 0 && more) fetch_pass(std::integral_constant<int, 1>{}, nxt, stage ^ 1);
       }
     } else {
       // The matrix instructions of a tile as one stream of A-operand fragments, per 32-query block qb:
@@ -712,6 +721,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
           dk[db] = mfma(ring[slot], pb[j], dk[db]);
         }
         if constexpr (F + PD < NFT) issue(std::integral_constant<int, F + PD>{}, qt_, ot_);
+        if constexpr (F == NFT / 2) { if (more) fetch_pass(std::integral_constant<int, 1>{}, nxt, stage ^ 1); }
         __builtin_amdgcn_sched_barrier(0);
       });
     }
