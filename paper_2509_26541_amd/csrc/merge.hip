@@ -72,12 +72,17 @@ __global__ __launch_bounds__(MERGE_THREADS) void merge_many_kernel(float* __rest
       for (int p0 = 0; p0 < n_parts; p0 += 8) {
         f32x4 b[8];
         float w[8];
+        // the lse values first (their second read hits the cache): vector memory loads complete in
+        // order, so waiting for them afterwards would wait for the 16-byte loads issued before
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w[k] = parts.lse[p0 + k < n_parts ? p0 + k : n_parts - 1][rh];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           const int p = p0 + k < n_parts ? p0 + k : n_parts - 1;        // a repeat of the last one, weight 0
           b[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(parts.o[p]) + i);
-          w[k] = p0 + k < n_parts ? __expf(parts.lse[p][rh] - mx) : 0.f;  // the second read of lse hits the cache
         }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w[k] = p0 + k < n_parts ? __expf(w[k] - mx) : 0.f;
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           den += w[k];
