@@ -281,7 +281,9 @@ double tasp_chunk_attn_flops(const tasp_schedule_t* s, const tasp_attn_args* a);
  * instructions, the measured path) or TASP_DTYPE_FP32 (a plain small-shape path, all arithmetic
  * fp32); d is 64 or 128.  Every row of dq, dk and dv is written.
  * workspace: device, 256-byte aligned, at least tasp_chunk_attn_bwd_workspace_bytes() (the delta
- * vector; for bf16 also an fp32 copy of dq and, step by step with Hq > Hkv, fp32 partial dk and dv of
+ * vector; for bf16 also lse scaled to base 2 in the same layout, both with one more entry behind the
+ * last row, which is why B*L*Hq must stay below 2^30 there (TASP_EUNSUPPORTED_SHAPE otherwise), an
+ * fp32 copy of dq and, step by step with Hq > Hkv, fp32 partial dk and dv of
  * one step's keys per query head of a group, twice the size of that copy: a step's dk/dv launch with
  * few, unequal key tiles is cut into one workgroup per key tile and query head, and the partial sums
  * are added in the order of the heads, so results do not depend on timing); contents are scratch.

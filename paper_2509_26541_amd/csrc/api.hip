@@ -463,13 +463,13 @@ size_t tasp_chunk_attn_bwd_workspace_bytes(const tasp_schedule_t* s, const tasp_
   if (s == nullptr || b == nullptr || b->S <= 0 || b->Hq <= 0 || b->d <= 0 || s->n <= 0 || b->batch < 0) return 0;
   const int64_t L = b->S / s->n;
   const size_t B = static_cast<size_t>(b->batch == 0 ? 1 : b->batch);
-  const size_t delta_bytes = align_up(B * L * b->Hq * sizeof(float));
-  if (b->dtype == TASP_DTYPE_FP32) return delta_bytes;                   // dq itself is the fp32 accumulator
+  if (b->dtype == TASP_DTYPE_FP32) return align_up(B * L * b->Hq * sizeof(float));   // delta; dq itself is the fp32 accumulator
+  const size_t delta_bytes = align_up((B * L * b->Hq + 1) * sizeof(float));   // and the entry behind the last row
   const size_t table = b->fuse_steps ? align_up(kFusedTableBytes) : 0;    // segment lists of the single launch
   const size_t dq_bytes = align_up(B * L * b->Hq * b->d * sizeof(float));
   // step by step with grouped heads: partial dk and dv per query head of a step's L keys, fp32
   const size_t parts = (!b->fuse_steps && b->Hkv > 0 && b->Hq > b->Hkv) ? 2 * dq_bytes : 0;
-  return dq_bytes + delta_bytes + table + parts;   // fp32 dq, delta
+  return dq_bytes + 2 * delta_bytes + table + parts;   // fp32 dq, delta, lse log2(e)
 }
 
 double tasp_chunk_attn_bwd_flops(const tasp_schedule_t* s, const tasp_attn_bwd_args* b) {
@@ -500,17 +500,19 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
   float* delta = bf16 ? reinterpret_cast<float*>(static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes))
                       : static_cast<float*>(b->workspace);
   const int64_t n_q_elems = static_cast<int64_t>(sh.B) * sh.L * b->Hq * b->d;
+  const int64_t n_rows = static_cast<int64_t>(sh.B) * sh.L * b->Hq;
+  // the dk/dv kernel addresses delta and lse2 with 32-bit byte offsets
+  if (bf16 && n_rows >= (int64_t{1} << 30)) return TASP_EUNSUPPORTED_SHAPE;
+  const size_t row_block = align_up(sh.lse_bytes + sizeof(float));
+  float* lse2 = bf16 ? reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(delta) + row_block) : nullptr;
+  unsigned char* after_rows = static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes) + 2 * row_block;
   // partial dk / dv of a dk/dv launch split by query head (see launch_unit): room for L keys a launch
-  float* part = (bf16 && !b->fuse_steps && b->Hq > b->Hkv)
-                    ? reinterpret_cast<float*>(static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes) +
-                                               align_up(sh.lse_bytes))
-                    : nullptr;
+  float* part = (bf16 && !b->fuse_steps && b->Hq > b->Hkv) ? reinterpret_cast<float*>(after_rows) : nullptr;
 
   try {
     {
       Scope sc(prof, BwdSpans::kOther);
-      const int64_t n_rows = static_cast<int64_t>(sh.B) * sh.L * b->Hq;
-      if ((bf16 ? tasp::launch_bwd_delta_bf16(b->out, b->dout, delta, n_rows, b->d, stream)
+      if ((bf16 ? tasp::launch_bwd_delta_bf16(b->out, b->dout, b->lse, delta, lse2, n_rows, b->d, stream)
                 : tasp::launch_bwd_delta_fp32(b->out, b->dout, delta, n_rows, b->d, stream)) != hipSuccess)
         return TASP_EHIP;
       if (tasp::launch_zero_f32(dq_acc, n_q_elems, stream) != hipSuccess) return TASP_EHIP;
@@ -525,7 +527,7 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
     // One unit = one dq launch and one dk/dv launch: a step, or all steps at once.
     auto launch_unit = [&](const AttnLaunch& lp, std::vector<tasp::Segment>& ranges) -> int {
       tasp::BwdLaunch bp{};
-      bp.q = b->q; bp.k = b->k; bp.v = b->v; bp.dout = b->dout; bp.lse = b->lse; bp.delta = delta;
+      bp.q = b->q; bp.k = b->k; bp.v = b->v; bp.dout = b->dout; bp.lse = b->lse; bp.delta = delta; bp.lse2 = lse2;
       bp.dq_acc = dq_acc; bp.dk = b->dk; bp.dv = b->dv;
       bp.Hq = lp.Hq; bp.Hkv = lp.Hkv; bp.causal = lp.causal; bp.scale = lp.scale; bp.batch = lp.batch;
       bp.q_bstride = lp.q_bstride; bp.kv_bstride = lp.kv_bstride; bp.lse_bstride = lp.lse_bstride;
@@ -597,8 +599,7 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
       std::vector<tasp::Segment> ranges, step_ranges;
       if (b->fuse_steps) {
         AttnLaunch all{};
-        int32_t* dev_table = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(b->workspace) + align_up(sh.o_bytes) +
-                                                        align_up(sh.lse_bytes));
+        int32_t* dev_table = reinterpret_cast<int32_t*>(after_rows);
         {
           Scope sc(prof, BwdSpans::kOther);
           st = build_all_steps(s, &a, dev_table, stream, &all);

@@ -382,14 +382,16 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
 // V rows stay in LDS instead (read as B operand when needed), which is what lets a wavefront with
 // two 32 x D accumulators fit the 256 registers of two wavefronts per SIMD at D = 128.
 // With SPLIT a workgroup serves one query head of the group only and leaves fp32 partial sums.
+// lse log2(e) and delta of a tile's queries come from the arrays the delta kernel left (p.lse2,
+// p.delta), gathered straight into LDS like the tile itself: no wavefront ever waits on them.
 template <int D, int NW, bool VLDS, bool SPLIT>
 __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const BwdLaunch p) {
   using C = BCfg<D, NW>;
   constexpr int KS = D / 16, DB = D / 32, BS = C::BS, NTHREADS = C::NTHREADS;
   constexpr int VST_BYTES = VLDS ? BS * D * 2 : 0;        // stationary V rows, same row layout as a tile
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE_BYTES + VST_BYTES];   // stage: Q tile, dout tile
-  __shared__ __attribute__((aligned(16))) float s_l2[2][BT];    // lse log2(e) of the tile's queries (+inf: row contributes nothing)
-  __shared__ __attribute__((aligned(16))) float s_dl[2][BT];    // delta of the tile's queries
+  __shared__ __attribute__((aligned(256))) float s_l2[2][BT];   // lse log2(e) of the tile's queries (+inf: row contributes nothing)
+  __shared__ __attribute__((aligned(256))) float s_dl[2][BT];   // delta of the tile's queries
   __shared__ int s_tmin, s_tmax;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, lq = lane & 31;
@@ -446,6 +448,14 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
     }
   }
   const float c = p.scale * kLog2e;
+  // The compiler cannot see the hand-written waits on the tile fetches; left alone it would wait
+  // for these loads again inside the loop, before every instruction that reads them, and those
+  // waits would then really wait, for the fetch of the next tile.  Using the values here ends that.
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    asm volatile("" : "+v"(kf[ks]));
+    if constexpr (!VLDS) asm volatile("" : "+v"(vf[ks]));
+  }
   __syncthreads();
   const int tmin = s_tmin;
   // the element-wise mask is needed for tiles with a query before the last key of the workgroup,
@@ -482,8 +492,13 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
   const unsigned char* Og = static_cast<const unsigned char*>(p.dout) + bi * p.q_bstride * 2;
   const unsigned q_row_bytes = static_cast<unsigned>(p.Hq) * D * 2;
   // The fetch of a tile comes in pieces (pass i = the Q and dout rows fr + RPP i; lse and delta of
-  // the tile's queries with the last one) that the loop drops between its matrix instructions: a
-  // burst of direct loads stalls the issuing wavefront once its queue is full.
+  // the tile's queries with the last one, by the first wavefront: rows past the end of the block
+  // take the entry behind the last row, +inf and 0) that the loop drops between its matrix
+  // instructions: a burst of direct loads stalls the issuing wavefront once its queue is full.
+  const int64_t n_rows_all = static_cast<int64_t>(p.batch) * p.lse_bstride;
+  const unsigned char* L2g = reinterpret_cast<const unsigned char*>(p.lse2 + bi * p.lse_bstride);
+  const unsigned char* Dlg = reinterpret_cast<const unsigned char*>(p.delta + bi * p.lse_bstride);
+  const unsigned past_end = static_cast<unsigned>(n_rows_all - bi * p.lse_bstride) * 4;
   static_assert(C::PASSES == 2, "the loop places two fetch pieces per tile");
   auto fetch_pass = [&](auto ii, const It& it, int stage) __attribute__((always_inline)) {
     constexpr int i = decltype(ii)::value;
@@ -496,17 +511,11 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
       dma16(Qg, off, dst + i * NTHREADS * 16);
       dma16(Og, off, dst + C::TILE_BYTES + i * NTHREADS * 16);
     }
-    if constexpr (i == C::PASSES - 1) if (tid < BT) {
-      const int r = it.qt * BT + tid;
-      float l2 = __builtin_inff(), dl = 0.f;
-      if (r < B.n) {
-        const int64_t o = bi * p.lse_bstride + static_cast<int64_t>(B.row0 + r) * p.Hq + hq;
-        const float l = p.lse[o];
-        if (l > -__builtin_inff()) l2 = l * kLog2e;
-        dl = p.delta[o];
-      }
-      s_l2[stage][tid] = l2;
-      s_dl[stage][tid] = dl;
+    if constexpr (i == C::PASSES - 1) if (wave_u == 0) {
+      const int r = it.qt * BT + lane;
+      const unsigned off = r < B.n ? static_cast<unsigned>((B.row0 + r) * p.Hq + hq) * 4 : past_end;
+      global_to_lds_4<true>(L2g, off, reinterpret_cast<unsigned char*>(&s_l2[stage][0]));
+      global_to_lds_4<true>(Dlg, off, reinterpret_cast<unsigned char*>(&s_dl[stage][0]));
     }
   };
   auto fetch = [&](const It& it, int stage) __attribute__((always_inline)) {
@@ -523,7 +532,6 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
     for (int i = 0; i < 16; ++i) { dk[db][i] = 0.f; dv[db][i] = 0.f; }
 
   // the V rows of the workgroup's keys, laid out like a tile (rows past the end repeat a valid row)
-  const unsigned char* vst = smem + 2 * C::STAGE_BYTES + wave * 32 * D * 2;   // this wave's 32 rows
   if constexpr (VLDS) {
     const unsigned char* Vg = static_cast<const unsigned char*>(p.v) + (bi * p.kv_bstride + static_cast<int64_t>(g) * D) * 2;
     const unsigned kv_row_bytes = static_cast<unsigned>(p.Hkv) * D * 2;
@@ -536,22 +544,37 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
     }
   }
 
-  constexpr int NFB = 2 * KS + 4 * DB, NFT = 2 * NFB, PD = 2;
-  bf16x8 ring[PD];   // A-operand fragments in flight (slot = fragment % PD); used without VLDS only
-  auto issue = [&](auto ff, const unsigned char* qt_, const unsigned char* ot_) __attribute__((always_inline)) {
+  // The matrix instructions of a tile take their A operands (and with VLDS the V rows, a B operand)
+  // as one stream of fragments read PD ahead.  A lane's fragment addresses differ from its first one
+  // of the kind only in the swizzled unit number, i.e. by an XOR with a constant below the row
+  // pitch (32 ks for row fragments, 64 db for transposed ones), so three or four address registers
+  // serve the whole tile: the vector instruction per read is cheap here, 24 registers are not.
+  // The empty asm statements make the compiler form each address where it is used instead of
+  // keeping all of them.
+  constexpr int NFB = 2 * KS + 4 * DB, NFT = 2 * NFB, PD = VLDS ? 3 : 2;
+  static_assert(32 * (KS - 1) < D * 2 && 64 * (DB - 1) < D * 2, "the XOR must stay inside a row");
+  bf16x8 ring[PD];                 // fragments in flight (slot = fragment % PD)
+  bf16x8 vring[VLDS ? PD : 1];
+  unsigned a_row = 0, a_tr0 = 0, a_tr1 = 0, a_v = 0;   // byte offsets in smem of this lane's first fragments (current stage; V rows)
+  auto issue = [&](auto ff) __attribute__((always_inline)) {
     constexpr int F = decltype(ff)::value, qb = F / NFB, f = F % NFB, slot = F % PD;
+    unsigned& av_ = a_v;
+    bf16x8* vr_ = vring;
     if constexpr (f < KS) {
-      ring[slot] = lds_row8(qt_ + ra.row[f] + qb * 32 * D * 2);
+      ring[slot] = lds_row8(smem + (a_row ^ (32u * f)) + qb * 32 * D * 2);
     } else if constexpr (f < KS + 2 * DB) {
-      constexpr int j = (f - KS) / DB, db = (f - KS) % DB, grp = (2 * qb + j) * 16 * D * 2;
-      ring[slot] = lds_tr8(ot_ + ra.tr[db][0] + grp, ot_ + ra.tr[db][1] + grp);
+      constexpr int j = (f - KS) / DB, db = (f - KS) % DB, grp = (2 * qb + j) * 16 * D * 2 + C::TILE_BYTES;
+      ring[slot] = lds_tr8(smem + (a_tr0 ^ (64u * db)) + grp, smem + (a_tr1 ^ (64u * db)) + grp);
     } else if constexpr (f < 2 * KS + 2 * DB) {
       constexpr int ks = f - KS - 2 * DB;
-      ring[slot] = lds_row8(ot_ + ra.row[ks] + qb * 32 * D * 2);
+      ring[slot] = lds_row8(smem + (a_row ^ (32u * ks)) + qb * 32 * D * 2 + C::TILE_BYTES);
+      if constexpr (VLDS) vr_[slot] = lds_row8(smem + (av_ ^ (32u * ks)));
     } else {
       constexpr int j = (f - 2 * KS - 2 * DB) / DB, db = (f - 2 * KS - 2 * DB) % DB, grp = (2 * qb + j) * 16 * D * 2;
-      ring[slot] = lds_tr8(qt_ + ra.tr[db][0] + grp, qt_ + ra.tr[db][1] + grp);
+      ring[slot] = lds_tr8(smem + (a_tr0 ^ (64u * db)) + grp, smem + (a_tr1 ^ (64u * db)) + grp);
     }
+    if constexpr (f == KS - 1 || f == KS + 2 * DB - 1 || f == 2 * KS + 2 * DB - 1 || f == NFB - 1)
+      asm volatile("" : "+v"(a_row), "+v"(a_tr0), "+v"(a_tr1), "+v"(av_));
   };
 
   It cur = settle(It{hh_beg, p.n_blk - 1, tiles_of(p.n_blk - 1) - 1});
@@ -563,94 +586,9 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
     __syncthreads();                 // the current tile is complete; nobody reads the other stage any more
     const bool more = nxt.blk >= 0;
     if (more) fetch_pass(std::integral_constant<int, 0>{}, nxt, stage ^ 1);
-    const unsigned char* qt_ = smem + stage * C::STAGE_BYTES;
-    const unsigned char* ot_ = qt_ + C::TILE_BYTES;
     const int pos0 = p.causal ? p.blk[cur.blk].pos0 + cur.qt * BT : 0;
     const bool need_mask = tmax > pos0;
-    if constexpr (VLDS) {
-      // At D = 128 the registers are too few for a fragment ring on top of everything else (the
-      // streamed form below spills inside the loop and measures 2 % slower), so the compiler orders
-      // the reads inside each phase.
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        // Five phases in a fixed order (the compiler may not mix them: that would keep S, dP, p and
-        // ds alive at once, more than the registers hold):  S -> p (in place) -> dv -> dP -> ds (in
-        // place) -> dk.  The other wavefront of the SIMD fills the matrix pipe meanwhile.
-        f32x16 S;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) S[i] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) S = mfma(lds_row8(qt_ + ra.row[ks] + qb * 32 * D * 2), kf[ks], S);
-        __builtin_amdgcn_sched_barrier(0);
-        // p for the 32 queries of this block (register 4 i4 + e: query 8 i4 + 4 h + e)
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const int r0 = 32 * qb + 8 * i4 + 4 * h;
-          const f32x4 l2 = *reinterpret_cast<const f32x4*>(&s_l2[stage][r0]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) S[4 * i4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[4 * i4 + e], c, -l2[e]));
-        }
-        if (need_mask) {
-#pragma unroll
-          for (int i4 = 0; i4 < 4; ++i4)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int q_pos = p.causal ? pos0 + 32 * qb + 8 * i4 + 4 * h + e : INT_MAX - 1;
-              if (key_tok > q_pos) S[4 * i4 + e] = 0.f;
-            }
-        }
-        bf16x8 pb[2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const u32x4 pf = {pack2(S[8 * j + 0], S[8 * j + 1]), pack2(S[8 * j + 2], S[8 * j + 3]),
-                            pack2(S[8 * j + 4], S[8 * j + 5]), pack2(S[8 * j + 6], S[8 * j + 7])};
-          pb[j] = __builtin_bit_cast(bf16x8, pf);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int grp = (2 * qb + j) * 16 * D * 2;
-#pragma unroll
-          for (int db = 0; db < DB; ++db)
-            dv[db] = mfma(lds_tr8(ot_ + ra.tr[db][0] + grp, ot_ + ra.tr[db][1] + grp), pb[j], dv[db]);
-        }
-        f32x16 dP;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) dP[i] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          bf16x8 vb;
-          if constexpr (VLDS) vb = lds_row8(vst + ra.row[ks]);
-          else vb = vf[ks];
-          dP = mfma(lds_row8(ot_ + ra.row[ks] + qb * 32 * D * 2), vb, dP);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const int r0 = 32 * qb + 8 * i4 + 4 * h;
-          const f32x4 dl = *reinterpret_cast<const f32x4*>(&s_dl[stage][r0]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) dP[4 * i4 + e] = S[4 * i4 + e] * (dP[4 * i4 + e] - dl[e]);
-        }
-        bf16x8 eb[2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const u32x4 ef = {pack2(dP[8 * j + 0], dP[8 * j + 1]), pack2(dP[8 * j + 2], dP[8 * j + 3]),
-                            pack2(dP[8 * j + 4], dP[8 * j + 5]), pack2(dP[8 * j + 6], dP[8 * j + 7])};
-          eb[j] = __builtin_bit_cast(bf16x8, ef);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int grp = (2 * qb + j) * 16 * D * 2;
-#pragma unroll
-          for (int db = 0; db < DB; ++db)
-            dk[db] = mfma(lds_tr8(qt_ + ra.tr[db][0] + grp, qt_ + ra.tr[db][1] + grp), eb[j], dk[db]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (qb == 0 && more) fetch_pass(std::integral_constant<int, 1>{}, nxt, stage ^ 1);
-      }
-    } else {
+    {
       // The matrix instructions of a tile as one stream of A-operand fragments, per 32-query block qb:
       // KS row fragments of Q (scores), 2 DB transposed fragments of dout (dv), KS row fragments of
       // dout (dout.v), 2 DB
@@ -660,7 +598,12 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
       // instructions, ds of each 16-query group right before the dk instructions that use it).
       f32x16 S, dP;
       bf16x8 pb[2];
-      static_for<PD>([&](auto ff) __attribute__((always_inline)) { issue(ff, qt_, ot_); });
+      a_row = stage * C::STAGE_BYTES + ra.row[0];
+      a_tr0 = stage * C::STAGE_BYTES + ra.tr[0][0];
+      a_tr1 = stage * C::STAGE_BYTES + ra.tr[0][1];
+      a_v = 2 * C::STAGE_BYTES + wave * 32 * D * 2 + ra.row[0];
+      asm volatile("" : "+v"(a_row), "+v"(a_tr0), "+v"(a_tr1), "+v"(a_v));
+      static_for<PD>([&](auto ff) __attribute__((always_inline)) { issue(ff); });
       __builtin_amdgcn_sched_barrier(0);
       static_for<NFT>([&](auto ff) __attribute__((always_inline)) {
         constexpr int F = decltype(ff)::value, qb = F / NFB, f = F % NFB, slot = F % PD;
@@ -703,7 +646,8 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
 #pragma unroll
             for (int i = 0; i < 16; ++i) dP[i] = 0.f;
           }
-          dP = mfma(ring[slot], vf[ks], dP);
+          if constexpr (VLDS) dP = mfma(ring[slot], vring[slot], dP);
+          else dP = mfma(ring[slot], vf[ks], dP);
         } else {
           constexpr int j = (f - 2 * KS - 2 * DB) / DB, db = (f - 2 * KS - 2 * DB) % DB;
           if constexpr (db == 0) {          // ds of the 16 queries of group j, packed to bf16 (reuses pb[j])
@@ -720,7 +664,7 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
           }
           dk[db] = mfma(ring[slot], pb[j], dk[db]);
         }
-        if constexpr (F + PD < NFT) issue(std::integral_constant<int, F + PD>{}, qt_, ot_);
+        if constexpr (F + PD < NFT) issue(std::integral_constant<int, F + PD>{});
         if constexpr (F == NFT / 2) { if (more) fetch_pass(std::integral_constant<int, 1>{}, nxt, stage ^ 1); }
         __builtin_amdgcn_sched_barrier(0);
       });
@@ -767,11 +711,14 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
 }
 
 // ------------------------------------------------------------------------------------------------
-// delta = sum_d dout * out per (row, head); D / 8 lanes per row
+// delta = sum_d dout * out per (row, head); D / 8 lanes per row.  Beside it the form of lse that
+// the dk/dv kernel wants (lse log2(e), +inf for a row that saw no key), and behind the last row of
+// both arrays the entry for "no such row": delta 0, lse2 +inf.
 // ------------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
-                                                        float* __restrict__ delta, int64_t n_rows) {
+                                                        const float* __restrict__ lse, float* __restrict__ delta,
+                                                        float* __restrict__ lse2, int64_t n_rows) {
   constexpr int LPR = D / 8;                    // lanes per (row, head)
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   const int64_t row = idx / LPR;
@@ -785,7 +732,15 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
   }
 #pragma unroll
   for (int m = LPR / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
-  if (row < n_rows && part == 0) delta[row] = s;
+  if (row < n_rows && part == 0) {
+    delta[row] = s;
+    const float l = lse[row];
+    lse2[row] = l > -__builtin_inff() ? l * kLog2e : __builtin_inff();
+  }
+  if (idx == 0) {
+    delta[n_rows] = 0.f;
+    lse2[n_rows] = __builtin_inff();
+  }
 }
 
 // dk, dv of a launch split by query head: one thread per (sequence, key, KV head, 4 columns) adds the
@@ -890,16 +845,16 @@ hipError_t launch_bwd_dkv_reduce(const BwdLaunch& p, int d, hipStream_t stream) 
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_bwd_delta_bf16(const void* out, const void* dout, float* delta, int64_t n_rows, int d,
-                                 hipStream_t stream) {
+hipError_t launch_bwd_delta_bf16(const void* out, const void* dout, const float* lse, float* delta, float* lse2,
+                                 int64_t n_rows, int d, hipStream_t stream) {
   if (n_rows == 0) return hipSuccess;
   const int64_t threads = n_rows * (d / 8);
   const int64_t blocks = (threads + 255) / 256;
   if (blocks > INT_MAX) return hipErrorInvalidValue;
   const __bf16* o = static_cast<const __bf16*>(out);
   const __bf16* g = static_cast<const __bf16*>(dout);
-  if (d == 128) return TASP_LAUNCH((bwd_delta_kernel<128>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, o, g, delta, n_rows);
-  if (d == 64) return TASP_LAUNCH((bwd_delta_kernel<64>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, o, g, delta, n_rows);
+  if (d == 128) return TASP_LAUNCH((bwd_delta_kernel<128>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, o, g, lse, delta, lse2, n_rows);
+  if (d == 64) return TASP_LAUNCH((bwd_delta_kernel<64>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, o, g, lse, delta, lse2, n_rows);
   return hipErrorInvalidValue;
 }
 

@@ -47,6 +47,17 @@ __device__ inline void global_to_lds_16(const unsigned char* base, unsigned off,
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base));
 }
 
+// Four bytes per lane: lane l's dword lands at lds_base + 4 l (a gather of 64 scalars into one
+// 256-byte row of LDS, with no register in between).
+template <bool FENCE>
+__device__ inline void global_to_lds_4(const unsigned char* base, unsigned off, unsigned char* lds_base) {
+  const unsigned lds_addr = static_cast<unsigned>(reinterpret_cast<size_t>((lds_void_ptr)lds_base));
+  if constexpr (FENCE)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds_addr), "v"(off), "s"(base));
+}
+
 // The same load through a buffer descriptor: lane l reads descriptor base + soff + off, where soff
 // is a scalar register.  A gather whose lanes share a moving base then needs no vector arithmetic
 // at all: the base moves in soff.  Raw descriptor (no stride, no swizzle), 2^32 - 1 records, so

@@ -285,19 +285,21 @@ def test_backward_argument_checks_and_sizes():
     b.batch = 0
     L = 4096 // 8
     pad = lambda x: (x + 255) // 256 * 256
-    # fp32 dq, delta and (grouped heads, step by step) the partial dk and dv of one step per query head
-    assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == 3 * pad(L * 8 * 128 * 4) + pad(L * 8 * 4)
+    # fp32 dq, delta and lse log2(e) (one entry more than rows each) and (grouped heads, step by step)
+    # the partial dk and dv of one step per query head
+    rows = lambda n: 2 * pad((n + 1) * 4)
+    assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == 3 * pad(L * 8 * 128 * 4) + rows(L * 8)
     b.Hkv = 8                                           # one query head per KV head: no partial sums
-    assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == pad(L * 8 * 128 * 4) + pad(L * 8 * 4)
+    assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == pad(L * 8 * 128 * 4) + rows(L * 8)
     b.Hkv = 2
     fwd = att.attention_flops(8, 3, 4096, sch.ZIGZAG_CAUSAL, 8, 128)
     assert tb.lib.tasp_chunk_attn_bwd_flops(s.handle, C.byref(b)) == 2.5 * fwd
     from oracle import attention_bwd as bwd
     assert bwd.attention_bwd_flops(8, 3, 4096, sch.ZIGZAG_CAUSAL, 8, 128) == 2.5 * fwd
     b.batch = 4
-    assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == 3 * pad(4 * L * 8 * 128 * 4) + pad(4 * L * 8 * 4)
+    assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == 3 * pad(4 * L * 8 * 128 * 4) + rows(4 * L * 8)
     b.fuse_steps = 1                                    # plus the segment table of the single launch
-    assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == pad(4 * L * 8 * 128 * 4) + pad(4 * L * 8 * 4) + 2 * 2 * 1024 * 4
+    assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == pad(4 * L * 8 * 128 * 4) + rows(4 * L * 8) + 2 * 2 * 1024 * 4
     b.fuse_steps = 3
     assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(b), None) == tb.EINVAL
     b.fuse_steps = 0

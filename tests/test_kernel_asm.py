@@ -91,12 +91,14 @@ def test_no_spills_in_the_loop(attn_asm):
 
 
 def _is_lds_load(s):
-    return s.startswith("global_load_lds_dwordx4") or (s.startswith("buffer_load_dwordx4") and s.endswith(" lds"))
+    return (s.startswith("global_load_lds_dwordx4") or s.startswith("global_load_lds_dword ")
+            or (s.startswith("buffer_load_dwordx4") and s.endswith(" lds")))
 
 
 def _m0_misuse(instructions):
     """Instructions that name m0 outside the one pattern the direct global->LDS loads use (their asm
-    statement: s_mov_b32 m0, <sgpr> / s_nop 0 / global_load_lds_dwordx4 or buffer_load_dwordx4 .. lds),
+    statement: s_mov_b32 m0, <sgpr> / s_nop 0 / global_load_lds_dwordx4, global_load_lds_dword or
+    buffer_load_dwordx4 .. lds),
     and such loads without it."""
     ins = [(line, s) for line, s in instructions if not s.endswith(":")]
     bad = []
