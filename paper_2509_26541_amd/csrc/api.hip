@@ -512,7 +512,8 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
   try {
     {
       Scope sc(prof, BwdSpans::kOther);
-      if ((bf16 ? tasp::launch_bwd_delta_bf16(b->out, b->dout, b->lse, delta, lse2, n_rows, b->d, stream)
+      const float scale = a.softmax_scale > 0.f ? a.softmax_scale : 1.0f / std::sqrt(static_cast<float>(a.d));   // as the launches below
+      if ((bf16 ? tasp::launch_bwd_delta_bf16(b->out, b->dout, b->lse, delta, lse2, scale, n_rows, b->d, stream)
                 : tasp::launch_bwd_delta_fp32(b->out, b->dout, delta, n_rows, b->d, stream)) != hipSuccess)
         return TASP_EHIP;
       if (tasp::launch_zero_f32(dq_acc, n_q_elems, stream) != hipSuccess) return TASP_EHIP;
@@ -527,7 +528,8 @@ static int run_chunk_attn_bwd(const tasp_schedule_t* s, const tasp_attn_bwd_args
     // One unit = one dq launch and one dk/dv launch: a step, or all steps at once.
     auto launch_unit = [&](const AttnLaunch& lp, std::vector<tasp::Segment>& ranges) -> int {
       tasp::BwdLaunch bp{};
-      bp.q = b->q; bp.k = b->k; bp.v = b->v; bp.dout = b->dout; bp.lse = b->lse; bp.delta = delta; bp.lse2 = lse2;
+      bp.q = b->q; bp.k = b->k; bp.v = b->v; bp.dout = b->dout; bp.lse = b->lse;
+      if (bf16) { bp.ndelta = delta; bp.nlse = lse2; } else { bp.delta = delta; }
       bp.dq_acc = dq_acc; bp.dk = b->dk; bp.dv = b->dv;
       bp.Hq = lp.Hq; bp.Hkv = lp.Hkv; bp.causal = lp.causal; bp.scale = lp.scale; bp.batch = lp.batch;
       bp.q_bstride = lp.q_bstride; bp.kv_bstride = lp.kv_bstride; bp.lse_bstride = lp.lse_bstride;

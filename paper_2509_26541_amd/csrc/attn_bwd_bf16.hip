@@ -202,12 +202,12 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
     }
   }
   const int64_t loff = bi * p.lse_bstride + q_row * p.Hq + hq;
-  const float lse_raw = p.lse[loff];
-  // a row that saw no key (lse = -inf) contributes nothing; exp2(x - inf) = 0 does that
-  const float lse2 = (q_valid && lse_raw > -__builtin_inff()) ? lse_raw * kLog2e : __builtin_inff();
-  const float dl = p.delta[loff];
-  const int q_pos = p.causal ? T.q_pos0 + my_q : INT_MAX - 1;
+  // -lse log2(e) and -delta of the row (the arrays hold -lse / scale and -delta).  A row that saw no
+  // key (-inf there) or does not exist contributes nothing: exp2(-inf) = 0.
   const float c = p.scale * kLog2e;
+  const float nl2 = q_valid ? p.nlse[loff] * c : -__builtin_inff();
+  const float nd = p.ndelta[loff];
+  const int q_pos = p.causal ? T.q_pos0 + my_q : INT_MAX - 1;
 
   // ---- loader: this thread fills rows fr + RPP i, physical unit fu of the K and the V tile
   const int fr = tid / C::UNITS, fu = tid % C::UNITS;
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
         dP = mfma(ring[slot], dof[ks], dP);
         constexpr int per = 16 / KS;
 #pragma unroll
-        for (int i = ks * per; i < (ks + 1) * per; ++i) S[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c, -lse2));
+        for (int i = ks * per; i < (ks + 1) * per; ++i) S[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c, nl2));
         if constexpr (ks == KS - 1) {
           if (need_mask) {
 #pragma unroll
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
         if constexpr (db == 0) {          // ds^T of the 16 keys of group j (registers 8 j .. 8 j + 7), packed to bf16
           float ds[8];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) ds[e] = S[8 * j + e] * (dP[8 * j + e] - dl);
+          for (int e = 0; e < 8; ++e) ds[e] = S[8 * j + e] * (dP[8 * j + e] + nd);
           ef[j] = u32x4{pack2(ds[0], ds[1]), pack2(ds[2], ds[3]), pack2(ds[4], ds[5]), pack2(ds[6], ds[7])};
         }
         dq[db] = mfma(ring[slot], __builtin_bit_cast(bf16x8, ef[j]), dq[db]);
@@ -382,16 +382,17 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
 // V rows stay in LDS instead (read as B operand when needed), which is what lets a wavefront with
 // two 32 x D accumulators fit the 256 registers of two wavefronts per SIMD at D = 128.
 // With SPLIT a workgroup serves one query head of the group only and leaves fp32 partial sums.
-// lse log2(e) and delta of a tile's queries come from the arrays the delta kernel left (p.lse2,
-// p.delta), gathered straight into LDS like the tile itself: no wavefront ever waits on them.
+// -lse / scale and -delta of a tile's queries come from the arrays the delta kernel left (p.nlse,
+// p.ndelta), gathered straight into LDS like the tile itself (no wavefront ever waits on them);
+// they are what the score and dout.v accumulators start from.
 template <int D, int NW, bool VLDS, bool SPLIT>
 __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const BwdLaunch p) {
   using C = BCfg<D, NW>;
   constexpr int KS = D / 16, DB = D / 32, BS = C::BS, NTHREADS = C::NTHREADS;
   constexpr int VST_BYTES = VLDS ? BS * D * 2 : 0;        // stationary V rows, same row layout as a tile
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * C::STAGE_BYTES + VST_BYTES];   // stage: Q tile, dout tile
-  __shared__ __attribute__((aligned(256))) float s_l2[2][BT];   // lse log2(e) of the tile's queries (+inf: row contributes nothing)
-  __shared__ __attribute__((aligned(256))) float s_dl[2][BT];   // delta of the tile's queries
+  __shared__ __attribute__((aligned(256))) float s_nl[2][BT];   // -lse / scale of the tile's queries (-inf: row contributes nothing)
+  __shared__ __attribute__((aligned(256))) float s_nd[2][BT];   // -delta of the tile's queries
   __shared__ int s_tmin, s_tmax;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5, lq = lane & 31;
@@ -493,11 +494,11 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
   const unsigned q_row_bytes = static_cast<unsigned>(p.Hq) * D * 2;
   // The fetch of a tile comes in pieces (pass i = the Q and dout rows fr + RPP i; lse and delta of
   // the tile's queries with the last one, by the first wavefront: rows past the end of the block
-  // take the entry behind the last row, +inf and 0) that the loop drops between its matrix
+  // take the entry behind the last row, -inf and 0) that the loop drops between its matrix
   // instructions: a burst of direct loads stalls the issuing wavefront once its queue is full.
   const int64_t n_rows_all = static_cast<int64_t>(p.batch) * p.lse_bstride;
-  const unsigned char* L2g = reinterpret_cast<const unsigned char*>(p.lse2 + bi * p.lse_bstride);
-  const unsigned char* Dlg = reinterpret_cast<const unsigned char*>(p.delta + bi * p.lse_bstride);
+  const unsigned char* L2g = reinterpret_cast<const unsigned char*>(p.nlse + bi * p.lse_bstride);
+  const unsigned char* Dlg = reinterpret_cast<const unsigned char*>(p.ndelta + bi * p.lse_bstride);
   const unsigned past_end = static_cast<unsigned>(n_rows_all - bi * p.lse_bstride) * 4;
   static_assert(C::PASSES == 2, "the loop places two fetch pieces per tile");
   auto fetch_pass = [&](auto ii, const It& it, int stage) __attribute__((always_inline)) {
@@ -512,10 +513,14 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
       dma16(Og, off, dst + C::TILE_BYTES + i * NTHREADS * 16);
     }
     if constexpr (i == C::PASSES - 1) if (wave_u == 0) {
-      const int r = it.qt * BT + lane;
+      // the lane number, formed here: held in a register across the loop it is one register too many
+      int zero = 0;
+      asm volatile("" : "+v"(zero));
+      const int lane_now = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, zero));
+      const int r = it.qt * BT + lane_now;
       const unsigned off = r < B.n ? static_cast<unsigned>((B.row0 + r) * p.Hq + hq) * 4 : past_end;
-      global_to_lds_4<true>(L2g, off, reinterpret_cast<unsigned char*>(&s_l2[stage][0]));
-      global_to_lds_4<true>(Dlg, off, reinterpret_cast<unsigned char*>(&s_dl[stage][0]));
+      global_to_lds_4<true>(L2g, off, reinterpret_cast<unsigned char*>(&s_nl[stage][0]));
+      global_to_lds_4<true>(Dlg, off, reinterpret_cast<unsigned char*>(&s_nd[stage][0]));
     }
   };
   auto fetch = [&](const It& it, int stage) __attribute__((always_inline)) {
@@ -562,18 +567,18 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
     bf16x8* vr_ = vring;
     if constexpr (f < KS) {
       ring[slot] = lds_row8(smem + (a_row ^ (32u * f)) + qb * 32 * D * 2);
-    } else if constexpr (f < KS + 2 * DB) {
-      constexpr int j = (f - KS) / DB, db = (f - KS) % DB, grp = (2 * qb + j) * 16 * D * 2 + C::TILE_BYTES;
-      ring[slot] = lds_tr8(smem + (a_tr0 ^ (64u * db)) + grp, smem + (a_tr1 ^ (64u * db)) + grp);
-    } else if constexpr (f < 2 * KS + 2 * DB) {
-      constexpr int ks = f - KS - 2 * DB;
+    } else if constexpr (f < 2 * KS) {
+      constexpr int ks = f - KS;
       ring[slot] = lds_row8(smem + (a_row ^ (32u * ks)) + qb * 32 * D * 2 + C::TILE_BYTES);
       if constexpr (VLDS) vr_[slot] = lds_row8(smem + (av_ ^ (32u * ks)));
+    } else if constexpr (f < 2 * KS + 2 * DB) {
+      constexpr int j = (f - 2 * KS) / DB, db = (f - 2 * KS) % DB, grp = (2 * qb + j) * 16 * D * 2 + C::TILE_BYTES;
+      ring[slot] = lds_tr8(smem + (a_tr0 ^ (64u * db)) + grp, smem + (a_tr1 ^ (64u * db)) + grp);
     } else {
       constexpr int j = (f - 2 * KS - 2 * DB) / DB, db = (f - 2 * KS - 2 * DB) % DB, grp = (2 * qb + j) * 16 * D * 2;
       ring[slot] = lds_tr8(smem + (a_tr0 ^ (64u * db)) + grp, smem + (a_tr1 ^ (64u * db)) + grp);
     }
-    if constexpr (f == KS - 1 || f == KS + 2 * DB - 1 || f == 2 * KS + 2 * DB - 1 || f == NFB - 1)
+    if constexpr (f == KS - 1 || f == 2 * KS - 1 || f == 2 * KS + 2 * DB - 1 || f == NFB - 1)
       asm volatile("" : "+v"(a_row), "+v"(a_tr0), "+v"(a_tr1), "+v"(av_));
   };
 
@@ -589,80 +594,70 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
     const int pos0 = p.causal ? p.blk[cur.blk].pos0 + cur.qt * BT : 0;
     const bool need_mask = tmax > pos0;
     {
-      // The matrix instructions of a tile as one stream of A-operand fragments, per 32-query block qb:
-      // KS row fragments of Q (scores), 2 DB transposed fragments of dout (dv), KS row fragments of
-      // dout (dout.v), 2 DB
-      // transposed fragments of Q (dk).  The reads of fragment F + PD are issued right after the
-      // instruction that consumed fragment F; scheduling barriers keep that order and keep S, p, dP
-      // and ds from being alive together more than they must (p is formed in place before the dv
-      // instructions, ds of each 16-query group right before the dk instructions that use it).
+      // The matrix instructions of a tile as one stream of operand fragments, per 32-query block qb:
+      // KS row fragments of Q (scores S), KS row fragments of dout (and of V: dP = dout.v), 2 DB
+      // transposed fragments of dout (dv), 2 DB transposed fragments of Q (dk).  The reads of
+      // fragment F + PD are issued right after the instruction that consumed fragment F.
+      // S starts from -lse / scale and dP from -delta of the row (register 4 i4 + e belongs to query
+      // 8 i4 + 4 h + e of the block: four 16-byte reads each, issued a phase ahead, while the
+      // registers are free), so p = exp2(c S) and ds = p dP are one and two instructions per value.
+      // That vector work rides in the shadow of matrix instructions that do not need it: p of
+      // 16 / KS queries beside each dP instruction, ds of 16 / (2 DB) queries beside each dv
+      // instruction.  p and ds go to bf16 pairs as they are formed (word v / 2 = values v, v + 1;
+      // words 4 j .. 4 j + 3 are the B operand of query group j).  Scheduling barriers keep the order.
+      constexpr int VPS = 16 / KS, VPD = 16 / (2 * DB);
+      static_assert(VPS % 2 == 0 && VPD % 2 == 0, "values are packed in pairs");
       f32x16 S, dP;
-      bf16x8 pb[2];
+      unsigned pw[8], ew[8];
+      auto start_from = [&](f32x16& acc, const float* rows, int qb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const f32x4 t = *reinterpret_cast<const f32x4*>(rows + 32 * qb + 8 * i4 + 4 * h);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[4 * i4 + e] = t[e];
+        }
+      };
       a_row = stage * C::STAGE_BYTES + ra.row[0];
       a_tr0 = stage * C::STAGE_BYTES + ra.tr[0][0];
       a_tr1 = stage * C::STAGE_BYTES + ra.tr[0][1];
       a_v = 2 * C::STAGE_BYTES + wave * 32 * D * 2 + ra.row[0];
       asm volatile("" : "+v"(a_row), "+v"(a_tr0), "+v"(a_tr1), "+v"(a_v));
+      start_from(S, &s_nl[stage][0], 0);
       static_for<PD>([&](auto ff) __attribute__((always_inline)) { issue(ff); });
       __builtin_amdgcn_sched_barrier(0);
       static_for<NFT>([&](auto ff) __attribute__((always_inline)) {
         constexpr int F = decltype(ff)::value, qb = F / NFB, f = F % NFB, slot = F % PD;
         if constexpr (f < KS) {
-          if constexpr (f == 0) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) S[i] = 0.f;
-          }
           S = mfma(ring[slot], kf[f], S);
-        } else if constexpr (f < KS + 2 * DB) {
-          constexpr int j = (f - KS) / DB, db = (f - KS) % DB;
-          if constexpr (f == KS) {
-            // p for the 32 queries of this block (register 4 i4 + e: query 8 i4 + 4 h + e), in place
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-              const f32x4 l2 = *reinterpret_cast<const f32x4*>(&s_l2[stage][32 * qb + 8 * i4 + 4 * h]);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) S[4 * i4 + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[4 * i4 + e], c, -l2[e]));
-            }
-            if (need_mask) {
-#pragma unroll
-              for (int i4 = 0; i4 < 4; ++i4)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  const int q_pos = p.causal ? pos0 + 32 * qb + 8 * i4 + 4 * h + e : INT_MAX - 1;
-                  if (key_tok > q_pos) S[4 * i4 + e] = 0.f;
-                }
-            }
-#pragma unroll
-            for (int jj = 0; jj < 2; ++jj) {
-              const u32x4 pf = {pack2(S[8 * jj + 0], S[8 * jj + 1]), pack2(S[8 * jj + 2], S[8 * jj + 3]),
-                                pack2(S[8 * jj + 4], S[8 * jj + 5]), pack2(S[8 * jj + 6], S[8 * jj + 7])};
-              pb[jj] = __builtin_bit_cast(bf16x8, pf);
-            }
-          }
-          dv[db] = mfma(ring[slot], pb[j], dv[db]);
-        } else if constexpr (f < 2 * KS + 2 * DB) {
-          constexpr int ks = f - KS - 2 * DB;
-          if constexpr (ks == 0) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) dP[i] = 0.f;
-          }
+          if constexpr (f == 0) start_from(dP, &s_nd[stage][0], qb);
+        } else if constexpr (f < 2 * KS) {
+          constexpr int ks = f - KS, u0 = ks * VPS;
           if constexpr (VLDS) dP = mfma(ring[slot], vring[slot], dP);
           else dP = mfma(ring[slot], vf[ks], dP);
+#pragma unroll
+          for (int e = 0; e < VPS; ++e) S[u0 + e] = __builtin_amdgcn_exp2f(S[u0 + e] * c);
+          if (need_mask) {
+#pragma unroll
+            for (int e = 0; e < VPS; ++e) {
+              const int q_pos = p.causal ? pos0 + 32 * qb + 8 * ((u0 + e) / 4) + 4 * h + (u0 + e) % 4 : INT_MAX - 1;
+              if (key_tok > q_pos) S[u0 + e] = 0.f;
+            }
+          }
+#pragma unroll
+          for (int e = 0; e < VPS; e += 2) pw[(u0 + e) / 2] = pack2(S[u0 + e], S[u0 + e + 1]);
+        } else if constexpr (f < 2 * KS + 2 * DB) {
+          constexpr int i = f - 2 * KS, j = i / DB, db = i % DB, u0 = i * VPD;
+          const u32x4 pf = {pw[4 * j], pw[4 * j + 1], pw[4 * j + 2], pw[4 * j + 3]};
+          dv[db] = mfma(ring[slot], __builtin_bit_cast(bf16x8, pf), dv[db]);
+#pragma unroll
+          for (int e = 0; e < VPD; e += 2)
+            ew[(u0 + e) / 2] = pack2(S[u0 + e] * dP[u0 + e], S[u0 + e + 1] * dP[u0 + e + 1]);
         } else {
           constexpr int j = (f - 2 * KS - 2 * DB) / DB, db = (f - 2 * KS - 2 * DB) % DB;
-          if constexpr (db == 0) {          // ds of the 16 queries of group j, packed to bf16 (reuses pb[j])
-            const f32x4 dla = *reinterpret_cast<const f32x4*>(&s_dl[stage][32 * qb + 16 * j + 4 * h]);
-            const f32x4 dlb = *reinterpret_cast<const f32x4*>(&s_dl[stage][32 * qb + 16 * j + 8 + 4 * h]);
-            float ds[8];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              ds[e] = S[8 * j + e] * (dP[8 * j + e] - dla[e]);
-              ds[4 + e] = S[8 * j + 4 + e] * (dP[8 * j + 4 + e] - dlb[e]);
-            }
-            const u32x4 ef = {pack2(ds[0], ds[1]), pack2(ds[2], ds[3]), pack2(ds[4], ds[5]), pack2(ds[6], ds[7])};
-            pb[j] = __builtin_bit_cast(bf16x8, ef);
-          }
-          dk[db] = mfma(ring[slot], pb[j], dk[db]);
+          const u32x4 ef = {ew[4 * j], ew[4 * j + 1], ew[4 * j + 2], ew[4 * j + 3]};
+          dk[db] = mfma(ring[slot], __builtin_bit_cast(bf16x8, ef), dk[db]);
+          // the next block's scores start from its rows' values; S is free from here on
+          if constexpr (f == 2 * KS + 2 * DB && qb == 0) start_from(S, &s_nl[stage][0], 1);
         }
         if constexpr (F + PD < NFT) issue(std::integral_constant<int, F + PD>{});
         if constexpr (F == NFT / 2) { if (more) fetch_pass(std::integral_constant<int, 1>{}, nxt, stage ^ 1); }
@@ -711,14 +706,15 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const
 }
 
 // ------------------------------------------------------------------------------------------------
-// delta = sum_d dout * out per (row, head); D / 8 lanes per row.  Beside it the form of lse that
-// the dk/dv kernel wants (lse log2(e), +inf for a row that saw no key), and behind the last row of
-// both arrays the entry for "no such row": delta 0, lse2 +inf.
+// delta = sum_d dout * out per (row, head); D / 8 lanes per row.  Written as -delta, and beside it
+// -lse / scale (-inf for a row that saw no key): what the dq and dk/dv kernels start their dout.v
+// and score accumulators from.  Behind the last row of both arrays sits the entry for "no such
+// row": 0 and -inf.
 // ------------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict__ out, const __bf16* __restrict__ dout,
-                                                        const float* __restrict__ lse, float* __restrict__ delta,
-                                                        float* __restrict__ lse2, int64_t n_rows) {
+                                                        const float* __restrict__ lse, float* __restrict__ ndelta,
+                                                        float* __restrict__ nlse, float scale, int64_t n_rows) {
   constexpr int LPR = D / 8;                    // lanes per (row, head)
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   const int64_t row = idx / LPR;
@@ -733,13 +729,13 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(const __bf16* __restrict
 #pragma unroll
   for (int m = LPR / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
   if (row < n_rows && part == 0) {
-    delta[row] = s;
+    ndelta[row] = -s;
     const float l = lse[row];
-    lse2[row] = l > -__builtin_inff() ? l * kLog2e : __builtin_inff();
+    nlse[row] = l > -__builtin_inff() ? -l / scale : -__builtin_inff();
   }
   if (idx == 0) {
-    delta[n_rows] = 0.f;
-    lse2[n_rows] = __builtin_inff();
+    ndelta[n_rows] = 0.f;
+    nlse[n_rows] = -__builtin_inff();
   }
 }
 
@@ -845,16 +841,16 @@ hipError_t launch_bwd_dkv_reduce(const BwdLaunch& p, int d, hipStream_t stream) 
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_bwd_delta_bf16(const void* out, const void* dout, const float* lse, float* delta, float* lse2,
-                                 int64_t n_rows, int d, hipStream_t stream) {
+hipError_t launch_bwd_delta_bf16(const void* out, const void* dout, const float* lse, float* ndelta, float* nlse,
+                                 float scale, int64_t n_rows, int d, hipStream_t stream) {
   if (n_rows == 0) return hipSuccess;
   const int64_t threads = n_rows * (d / 8);
   const int64_t blocks = (threads + 255) / 256;
   if (blocks > INT_MAX) return hipErrorInvalidValue;
   const __bf16* o = static_cast<const __bf16*>(out);
   const __bf16* g = static_cast<const __bf16*>(dout);
-  if (d == 128) return TASP_LAUNCH((bwd_delta_kernel<128>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, o, g, lse, delta, lse2, n_rows);
-  if (d == 64) return TASP_LAUNCH((bwd_delta_kernel<64>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, o, g, lse, delta, lse2, n_rows);
+  if (d == 128) return TASP_LAUNCH((bwd_delta_kernel<128>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, o, g, lse, ndelta, nlse, scale, n_rows);
+  if (d == 64) return TASP_LAUNCH((bwd_delta_kernel<64>), dim3(static_cast<unsigned>(blocks)), dim3(256), stream, o, g, lse, ndelta, nlse, scale, n_rows);
   return hipErrorInvalidValue;
 }
 

@@ -55,8 +55,9 @@ struct BwdLaunch {
   const void* v;
   const void* dout;     // [B, L, Hq, d]
   const float* lse;     // [B, L, Hq] final lse of the forward pass
-  const float* delta;   // [B, L, Hq] sum_d dout * out, then one 0
-  const float* lse2;    // [B, L, Hq] lse log2(e), +inf where lse is -inf (the row saw no key), then one +inf
+  const float* delta;   // [B, L, Hq] sum_d dout * out (fp32 kernels)
+  const float* ndelta;  // [B, L, Hq] -delta, then one 0 (bf16 kernels)
+  const float* nlse;    // [B, L, Hq] -lse / scale, -inf where lse is -inf (the row saw no key), then one -inf (bf16 kernels)
   float* dq_acc;        // [B, L, Hq, d] fp32, accumulated into
   void* dk;             // [B, S, Hkv, d] bf16; the rows of this step's keys are written
   void* dv;
@@ -119,10 +120,10 @@ hipError_t launch_bwd_dkv_reduce(const BwdLaunch& p, int d, hipStream_t stream);
 // workgroups of the dk/dv launch without the split, and how many of them the chip holds at once
 int64_t bwd_dkv_workgroups(const BwdLaunch& p, int d);
 int bwd_dkv_resident_workgroups(int d);
-// delta[r] = sum_d dout out and lse2[r] = lse[r] log2(e) (+inf for -inf) for the n_rows (row, head)
-// pairs; both arrays hold n_rows + 1 floats, the last one being 0 and +inf.
-hipError_t launch_bwd_delta_bf16(const void* out, const void* dout, const float* lse, float* delta, float* lse2,
-                                 int64_t n_rows, int d, hipStream_t stream);
+// ndelta[r] = -sum_d dout out and nlse[r] = -lse[r] / scale (-inf for -inf) for the n_rows (row, head)
+// pairs; both arrays hold n_rows + 1 floats, the last one being 0 and -inf.
+hipError_t launch_bwd_delta_bf16(const void* out, const void* dout, const float* lse, float* ndelta, float* nlse,
+                                 float scale, int64_t n_rows, int d, hipStream_t stream);
 hipError_t launch_zero_f32(float* dst, int64_t n, hipStream_t stream);   // n a multiple of 4, dst 16-byte aligned
 // Implemented in attn_bwd_fp32.hip (all tensors fp32; dq_acc is dq itself).
 hipError_t launch_bwd_dq_fp32(const BwdLaunch& p, int d, hipStream_t stream);
