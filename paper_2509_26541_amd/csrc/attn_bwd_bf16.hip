@@ -205,8 +205,8 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
   // -lse log2(e) and -delta of the row (the arrays hold -lse / scale and -delta).  A row that saw no
   // key (-inf there) or does not exist contributes nothing: exp2(-inf) = 0.
   const float c = p.scale * kLog2e;
-  const float nl2 = q_valid ? p.nlse[loff] * c : -__builtin_inff();
-  const float nd = p.ndelta[loff];
+  float nl2 = q_valid ? p.nlse[loff] * c : -__builtin_inff();
+  float nd = p.ndelta[loff];
   const int q_pos = p.causal ? T.q_pos0 + my_q : INT_MAX - 1;
 
   // ---- loader: this thread fills rows fr + RPP i, physical unit fu of the K and the V tile
@@ -291,6 +291,12 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
   };
 
   if (n_tiles > 0) fetch(0, 0);
+  // The compiler cannot see the hand-written waits on the tile fetches; left alone it waits inside
+  // the loop for the loads of the stationary rows again, before the instructions that read them,
+  // and in hardware those waits hit the fetch of the next tile.  Using the values here ends that.
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]), "+v"(dof[ks]));
+  asm volatile("" : "+v"(nl2), "+v"(nd));
   for (int t = 0; t < n_tiles; ++t) {
     const int stage = t & 1;
     wait_all_loads();

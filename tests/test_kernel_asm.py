@@ -159,3 +159,39 @@ def test_backward_kernels_shape_and_register_budget(bwd_asm):
     for name, n_spill, _ in asm_checks.spill_report(bwd_asm):
         if name in ks:
             assert n_spill <= 4, (name, n_spill)
+
+
+def _vmcnt_waits_in_matrix_loop(ins):
+    """(line, text) of every s_waitcnt that names vmcnt between the first and the last matrix
+    instruction, except the hand-written one on the tile fetch (vmcnt(0) alone, followed by the
+    barrier)."""
+    ops = [s for _, s in ins if not s.endswith(":")]
+    lines = [l for l, s in ins if not s.endswith(":")]
+    mf = [i for i, s in enumerate(ops) if s.startswith("v_mfma_")]
+    bad = []
+    for i in range(mf[0], mf[-1]):
+        if ops[i].startswith("s_waitcnt") and "vmcnt" in ops[i]:
+            if ops[i] == "s_waitcnt vmcnt(0)" and any(o.startswith("s_barrier") for o in ops[i + 1:i + 4]):
+                continue
+            bad.append((lines[i], ops[i]))
+    return bad
+
+
+def test_vmcnt_checker_flags_planted_waits():
+    loop = [(1, "v_mfma_f32_32x32x16_bf16 v[0:15], v[16:19], v[20:23], v[0:15]"), (2, "s_waitcnt vmcnt(0)"), (3, "s_barrier"),
+            (4, "s_waitcnt lgkmcnt(2)"), (5, "v_mfma_f32_32x32x16_bf16 v[0:15], v[16:19], v[20:23], v[0:15]")]
+    assert _vmcnt_waits_in_matrix_loop(loop) == []
+    planted = loop[:3] + [(4, "s_waitcnt vmcnt(1) lgkmcnt(2)")] + loop[4:]
+    assert _vmcnt_waits_in_matrix_loop(planted) == [(4, "s_waitcnt vmcnt(1) lgkmcnt(2)")]
+
+
+def test_backward_loops_never_wait_on_vector_memory_by_themselves(bwd_asm):
+    """The tile fetches of the dq and dk/dv kernels are direct global->LDS loads inside asm statements, waited
+    for by a hand-written vmcnt(0) before the barrier.  The compiler does not see that wait: if it
+    believes other loads (the stationary rows, lse, delta) are still on their way inside the loop,
+    it waits for them there, and in hardware such a wait stalls on the fetch of the next tile.  So the
+    matrix loop holds no vmcnt wait but the hand-written one."""
+    ks = {k: v for k, v in asm_checks.kernels(bwd_asm).items() if "bwd_dkv_kernel" in k or "bwd_dq_kernel" in k}
+    assert len(ks) == 6, list(ks)
+    for name, ins in ks.items():
+        assert _vmcnt_waits_in_matrix_loop(ins) == [], (name, _vmcnt_waits_in_matrix_loop(ins)[:3])
