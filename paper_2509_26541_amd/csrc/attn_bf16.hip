@@ -786,7 +786,14 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void attn_bf16_kernel(const AttnLa
     pv_half(ts_, t, S_a, S_b);
     qk_half(std::false_type{}, std::integral_constant<int, (decltype(ts_)::value + 2) & 3>{}, S_b, S_a);
     wait_fetches(one_in_flight);
-    __syncthreads();
+    // A bare barrier where it fits: __syncthreads() also drains this wavefront's LDS reads, i.e. the
+    // operand fragments just requested for the next tile, and all eight wavefronts would sit out
+    // that round trip together.  Nothing needs the drain: a stage is overwritten only after every
+    // read of it has fed a matrix instruction that precedes an earlier barrier, and the fragments
+    // in flight belong to stages that stay.  (With twelve wavefronts the bare form costs a
+    // register the kernel does not have.)
+    if constexpr (NW == 12) __syncthreads();
+    else __builtin_amdgcn_s_barrier();
   };
 
   if (n_tiles > 0) {
