@@ -298,6 +298,13 @@ def test_backward_argument_checks_and_sizes():
     assert bwd.attention_bwd_flops(8, 3, 4096, sch.ZIGZAG_CAUSAL, 8, 128) == 2.5 * fwd
     b.batch = 4
     assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == 3 * pad(4 * L * 8 * 128 * 4) + rows(4 * L * 8)
+    # bf16: the row arrays are addressed with 32-bit byte offsets, so 2^30 (row, head) pairs are refused
+    # (checked after the workspace and before anything is enqueued)
+    big = tb.AttnBwdArgs()
+    big.q = big.k = big.v = big.out = big.lse = big.dout = big.dq = big.dk = big.dv = big.workspace = 4096
+    big.workspace_bytes = 1 << 62
+    big.S, big.Hq, big.Hkv, big.d, big.dtype, big.mask_mode, big.batch = 1 << 20, 64, 1, 64, tb.DTYPE_BF16, tb.MASK_ZIGZAG_CAUSAL, 128
+    assert tb.lib.tasp_chunk_attn_bwd(s.handle, C.byref(big), None) == tb.EUNSUPPORTED_SHAPE
     b.fuse_steps = 1                                    # plus the segment table of the single launch
     assert tb.lib.tasp_chunk_attn_bwd_workspace_bytes(s.handle, C.byref(b)) == pad(4 * L * 8 * 128 * 4) + rows(4 * L * 8) + 2 * 2 * 1024 * 4
     b.fuse_steps = 3
