@@ -386,13 +386,14 @@ __global__ __launch_bounds__(256, D == 64 ? 3 : 2) void bwd_dq_kernel(const BwdL
 // ------------------------------------------------------------------------------------------------
 // NW wavefronts of 32 keys each.  The K rows of a wavefront's keys stay in registers; with VLDS the
 // V rows stay in LDS instead (read as B operand when needed), which is what lets a wavefront with
-// two 32 x D accumulators fit the 256 registers of two wavefronts per SIMD at D = 128.
+// two 32 x D accumulators fit the 256 registers of two wavefronts per SIMD at D = 128.  At D = 64
+// the kernel fits 168 registers, i.e. three workgroups of four wavefronts per CU (-6 % against two).
 // With SPLIT a workgroup serves one query head of the group only and leaves fp32 partial sums.
 // -lse / scale and -delta of a tile's queries come from the arrays the delta kernel left (p.nlse,
 // p.ndelta), gathered straight into LDS like the tile itself (no wavefront ever waits on them);
 // they are what the score and dout.v accumulators start from.
 template <int D, int NW, bool VLDS, bool SPLIT>
-__global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void bwd_dkv_kernel(const BwdLaunch p) {
+__global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 3) void bwd_dkv_kernel(const BwdLaunch p) {
   using C = BCfg<D, NW>;
   constexpr int KS = D / 16, DB = D / 32, BS = C::BS, NTHREADS = C::NTHREADS;
   constexpr int VST_BYTES = VLDS ? BS * D * 2 : 0;        // stationary V rows, same row layout as a tile
@@ -840,7 +841,7 @@ int bwd_dkv_resident_workgroups(int d) {
   int dev = 0, cus = 256;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
     cus = 256;
-  return cus * (d == 128 ? 1 : 2);
+  return cus * (d == 128 ? 1 : 3);
 }
 
 hipError_t launch_bwd_dkv_reduce(const BwdLaunch& p, int d, hipStream_t stream) {
